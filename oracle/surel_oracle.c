@@ -1,0 +1,236 @@
+/*
+ * CPU oracle for the walk -> RPE -> join path of SUREL.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, single-threaded C that states what the path computes, so that a
+ * reader can check it against the paper by eye.  It shares no code, header,
+ * table or helper with the HIP library, and only tests, the smoke check and
+ * the benchmark's cpu_baseline leg may call it.  The product never does.
+ *
+ * What each function follows:
+ *   oracle_philox4x32_10   Salmon, Moraes, Dror, Shaw, "Parallel random numbers:
+ *                          as easy as 1, 2, 3" (SC'11), Philox-4x32 with 10 rounds.
+ *                          The paper names no generator; this build fixes this one.
+ *   oracle_sample_walks    Sec. 3.2 "Walk Sampling" and Algorithm 1, step "run M
+ *                          times m-step random walks" on the CSR arrays
+ *                          (idxptr, indices) of Sec. 3.2.
+ *   oracle_build_rpe       Sec. 3.2 "Relative Positional Encoding": V_u is the set
+ *                          of distinct nodes in W_u, and X_{u,x}[i] is the landing
+ *                          count of x at position i over the walks of W_u.
+ *   oracle_join_queries    Sec. 3.4: X_{Q,x} is the concatenation over u in Q of
+ *                          X_{u,x}, all zeros where x is not in V_u; taken over the
+ *                          union of the V_u (the set-union form the section's
+ *                          closing remarks describe).
+ *
+ * Readings where the paper is silent:
+ *   - a walk is stored with its start: m+1 positions, position 0 is the seed
+ *     (the RPE has m+1 slots and Sec. 3.5 writes a walk as (w_0..w_m));
+ *   - a step moves to a uniformly chosen entry of the current node's CSR row:
+ *     entry index = r mod degree for a 32-bit random word r; a node of degree 0
+ *     keeps the walker where it is;
+ *   - the random word of (start node u, walk w, step s>=1) is word (s-1)&3 of
+ *     Philox4x32-10 with counter (u, w, (s-1)>>2, 0) and key (low 32 bits of
+ *     rng_seed, high 32 bits of rng_seed);
+ *   - counts are raw unsigned 16-bit integers (the worked example of Sec. 3.3/3.4
+ *     shows integer vectors such as [2,0,0]);
+ *   - V_u and the union are listed in ascending node id (the paper's hash
+ *     dictionary has no order; ascending is the canonical one);
+ *   - a query is an ordered tuple; its entries select rows of the RPE table
+ *     (the i-th seed's block), and the halves of X_{Q,x} follow tuple order.
+ *
+ * Return values: >= 0 on success (row totals for the two variable-size calls),
+ * -1 for a bad argument, -2 if the output capacity is too small (nothing beyond
+ * the capacity is written), -3 out of memory.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------- */
+/* Philox-4x32-10                                                            */
+/* ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 32-bit random word that decides step s (1-based) of walk w started at node u. */
+static uint32_t step_word(uint32_t u, uint32_t w, int s, uint64_t rng_seed)
+{
+    uint32_t ctr[4] = { u, w, (uint32_t)((s - 1) >> 2), 0u };
+    uint32_t key[2] = { (uint32_t)(rng_seed & 0xFFFFFFFFu), (uint32_t)(rng_seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return out[(s - 1) & 3];
+}
+
+/* ------------------------------------------------------------------------- */
+/* Walks: walks[i][w][0..m], i over seeds, w over the M walks of that seed.   */
+/* ------------------------------------------------------------------------- */
+int oracle_sample_walks(const int32_t *row_ptr, const int32_t *col_idx, int32_t n_nodes,
+                        const int32_t *seeds, int64_t n_seeds, int32_t M, int32_t m,
+                        uint64_t rng_seed, int32_t *walks)
+{
+    if (!row_ptr || (!col_idx && row_ptr[n_nodes] > 0) || n_nodes < 1 || n_seeds < 0 ||
+        M < 1 || m < 1 || (n_seeds > 0 && (!seeds || !walks)))
+        return -1;
+    const int64_t L = (int64_t)m + 1;
+    for (int64_t i = 0; i < n_seeds; ++i) {
+        const int32_t u = seeds[i];
+        if (u < 0 || u >= n_nodes)
+            return -1;
+        for (int32_t w = 0; w < M; ++w) {
+            int32_t *walk = walks + (i * M + w) * L;
+            int32_t cur = u;
+            walk[0] = u;
+            for (int s = 1; s <= m; ++s) {
+                const uint32_t deg = (uint32_t)(row_ptr[cur + 1] - row_ptr[cur]);
+                if (deg != 0u) {
+                    const uint32_t r = step_word((uint32_t)u, (uint32_t)w, s, rng_seed);
+                    cur = col_idx[(int64_t)row_ptr[cur] + (int64_t)(r % deg)];
+                }
+                walk[s] = cur;
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Node-level RPE table.                                                     */
+/*   rpe_off[i]..rpe_off[i+1] are the rows of seed i; rpe_ids ascending in    */
+/*   each block; rpe_cnt[row][s] = number of walks of seed i standing on      */
+/*   rpe_ids[row] at position s.  ids / cnt may be NULL to only count rows.   */
+/* ------------------------------------------------------------------------- */
+static int cmp_i32(const void *a, const void *b)
+{
+    const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+int64_t oracle_build_rpe(const int32_t *walks, int64_t n_seeds, int32_t M, int32_t m,
+                         int64_t cap_rows, int64_t *rpe_off, int32_t *rpe_ids,
+                         uint16_t *rpe_cnt)
+{
+    if (n_seeds < 0 || M < 1 || M > 65535 || m < 1 || !rpe_off || (n_seeds > 0 && !walks))
+        return -1;
+    const int64_t L = (int64_t)m + 1;
+    const int64_t per_seed = (int64_t)M * L;
+    int32_t *set = (int32_t *)malloc((size_t)per_seed * sizeof(int32_t));
+    uint16_t *cnt = (uint16_t *)malloc((size_t)per_seed * (size_t)L * sizeof(uint16_t));
+    if (!set || !cnt) { free(set); free(cnt); return -3; }
+
+    const int fill = rpe_ids != NULL && rpe_cnt != NULL;
+    int64_t total = 0;
+    int overflow = 0;
+    rpe_off[0] = 0;
+    for (int64_t i = 0; i < n_seeds; ++i) {
+        const int32_t *W = walks + i * per_seed;
+        /* V_u = set(W_u), ascending */
+        memcpy(set, W, (size_t)per_seed * sizeof(int32_t));
+        qsort(set, (size_t)per_seed, sizeof(int32_t), cmp_i32);
+        int64_t n_set = 0;
+        for (int64_t j = 0; j < per_seed; ++j)
+            if (j == 0 || set[j] != set[j - 1])
+                set[n_set++] = set[j];
+        /* X_{u,x}[s] = #{ w : W_u[w][s] == x } */
+        memset(cnt, 0, (size_t)n_set * (size_t)L * sizeof(uint16_t));
+        for (int32_t w = 0; w < M; ++w) {
+            for (int64_t s = 0; s < L; ++s) {
+                const int32_t x = W[w * L + s];
+                const int32_t *hit = (const int32_t *)bsearch(&x, set, (size_t)n_set,
+                                                              sizeof(int32_t), cmp_i32);
+                cnt[(hit - set) * L + s] += 1;
+            }
+        }
+        if (fill) {
+            if (total + n_set <= cap_rows) {
+                memcpy(rpe_ids + total, set, (size_t)n_set * sizeof(int32_t));
+                memcpy(rpe_cnt + total * L, cnt, (size_t)n_set * (size_t)L * sizeof(uint16_t));
+            } else {
+                overflow = 1;
+            }
+        }
+        total += n_set;
+        rpe_off[i + 1] = total;
+    }
+    free(set);
+    free(cnt);
+    return overflow ? -2 : total;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Query-level RPE by set union.                                             */
+/*   queries[q][j], j < k, are row-block indices of the RPE table.            */
+/*   join_ids: ascending union of the k id lists;                             */
+/*   join_cnt[row][j][s] = X_{u_j,x}[s], zeros where x is not in V_{u_j}.      */
+/* ------------------------------------------------------------------------- */
+int64_t oracle_join_queries(const int64_t *rpe_off, const int32_t *rpe_ids,
+                            const uint16_t *rpe_cnt, int64_t n_blocks, int32_t m,
+                            const int32_t *queries, int64_t n_queries, int32_t k,
+                            int64_t cap_rows, int64_t *join_off, int32_t *join_ids,
+                            uint16_t *join_cnt)
+{
+    if (!rpe_off || n_blocks < 0 || m < 1 || n_queries < 0 || k < 1 || k > 8 || !join_off ||
+        (n_queries > 0 && !queries))
+        return -1;
+    const int64_t L = (int64_t)m + 1;
+    const int fill = join_ids != NULL && join_cnt != NULL;
+    int64_t total = 0;
+    int overflow = 0;
+    join_off[0] = 0;
+    for (int64_t q = 0; q < n_queries; ++q) {
+        int64_t head[8], end[8];
+        for (int j = 0; j < k; ++j) {
+            const int32_t b = queries[q * k + j];
+            if (b < 0 || b >= n_blocks)
+                return -1;
+            head[j] = rpe_off[b];
+            end[j] = rpe_off[b + 1];
+        }
+        for (;;) {
+            /* smallest id among the heads of the k lists */
+            int have = 0;
+            int32_t x = 0;
+            for (int j = 0; j < k; ++j)
+                if (head[j] < end[j] && (!have || rpe_ids[head[j]] < x)) {
+                    x = rpe_ids[head[j]];
+                    have = 1;
+                }
+            if (!have)
+                break;
+            const int writable = fill && total < cap_rows;
+            if (fill && !writable)
+                overflow = 1;
+            if (writable)
+                join_ids[total] = x;
+            for (int j = 0; j < k; ++j) {
+                const int present = head[j] < end[j] && rpe_ids[head[j]] == x;
+                if (writable) {
+                    uint16_t *dst = join_cnt + (total * k + j) * L;
+                    if (present)
+                        memcpy(dst, rpe_cnt + head[j] * L, (size_t)L * sizeof(uint16_t));
+                    else
+                        memset(dst, 0, (size_t)L * sizeof(uint16_t));
+                }
+                if (present)
+                    head[j] += 1;
+            }
+            total += 1;
+        }
+        join_off[q + 1] = total;
+    }
+    return overflow ? -2 : total;
+}

@@ -1,0 +1,502 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+What fixes each part:
+  Philox      the published known-answer vectors (tests/golden/philox4x32_10_kat.txt).
+  walks       closed forms on P2 / star / path / isolated nodes, the edge-validity
+              invariant, bipartite parity, and a chi-square test of whole-walk
+              frequencies against the exact distribution obtained by enumerating every
+              neighbour-choice sequence of tiny graphs (Sec. 3.2, walk sampling).
+  RPE         the paper's own worked fragment (Sec. 3.3 / 3.4), a dense counter written
+              with NumPy scatter-adds, and the invariants of the definition (Sec. 3.2).
+  join        Python set / dict union with zero fill (Sec. 3.4), symmetry under swapping
+              the query's nodes, u == v, and triple-versus-pair consistency.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import oracle
+from paper_2202_13538_amd import synth
+
+MASK32 = 0xFFFFFFFF
+
+
+# --------------------------------------------------------------------------- #
+# Philox
+# --------------------------------------------------------------------------- #
+def _read_kat(golden_dir):
+    rows = []
+    with open(os.path.join(golden_dir, "philox4x32_10_kat.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            w = [int(x, 16) for x in line.split()]
+            rows.append((w[0:4], w[4:6], w[6:10]))
+    return rows
+
+
+def py_philox(ctr, key):
+    """Philox-4x32-10 in Python big integers (independent of the C oracle)."""
+    c = [int(x) & MASK32 for x in ctr]
+    k = [int(x) & MASK32 for x in key]
+    for _ in range(10):
+        p0 = 0xD2511F53 * c[0]
+        p1 = 0xCD9E8D57 * c[2]
+        c = [((p1 >> 32) ^ c[1] ^ k[0]) & MASK32, p1 & MASK32,
+             ((p0 >> 32) ^ c[3] ^ k[1]) & MASK32, p0 & MASK32]
+        k = [(k[0] + 0x9E3779B9) & MASK32, (k[1] + 0xBB67AE85) & MASK32]
+    return c
+
+
+def test_philox_known_answers(golden_dir):
+    kat = _read_kat(golden_dir)
+    assert len(kat) == 3
+    for ctr, key, want in kat:
+        assert oracle.philox4x32_10(ctr, key).tolist() == want
+        assert py_philox(ctr, key) == want
+
+
+def test_philox_matches_bigint_evaluator_on_random_inputs():
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        ctr = rng.integers(0, 1 << 32, size=4, dtype=np.uint64)
+        key = rng.integers(0, 1 << 32, size=2, dtype=np.uint64)
+        assert oracle.philox4x32_10(ctr, key).tolist() == py_philox(ctr, key)
+
+
+# --------------------------------------------------------------------------- #
+# tiny graphs
+# --------------------------------------------------------------------------- #
+def path_graph(n):
+    return synth.csr_from_edge_list(n, [(i, i + 1) for i in range(n - 1)])
+
+
+def star_graph(n_leaves):
+    return synth.csr_from_edge_list(n_leaves + 1, [(0, i) for i in range(1, n_leaves + 1)])
+
+
+def cycle_graph(n):
+    return synth.csr_from_edge_list(n, [(i, (i + 1) % n) for i in range(n)])
+
+
+def complete_graph(n):
+    return synth.csr_from_edge_list(n, itertools.combinations(range(n), 2))
+
+
+def lollipop_graph():
+    # triangle 0-1-2 with a tail 2-3-4 and a pendant 5 on node 3: degrees 2,2,3,3,1,1
+    return synth.csr_from_edge_list(6, [(0, 1), (1, 2), (0, 2), (2, 3), (3, 4), (3, 5)])
+
+
+def neighbours(row_ptr, col_idx, v):
+    return col_idx[row_ptr[v]:row_ptr[v + 1]].tolist()
+
+
+# --------------------------------------------------------------------------- #
+# walks: closed forms
+# --------------------------------------------------------------------------- #
+def test_walks_two_node_path_alternates():
+    rp, ci = path_graph(2)
+    M, m = 7, 6
+    w = oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=3)
+    assert w.shape == (2, M, m + 1)
+    assert (w[0] == np.array([0, 1, 0, 1, 0, 1, 0])).all()
+    assert (w[1] == np.array([1, 0, 1, 0, 1, 0, 1])).all()
+    off, ids, cnt = oracle.build_rpe(w)
+    assert off.tolist() == [0, 2, 4]
+    assert ids.tolist() == [0, 1, 0, 1]
+    assert cnt[0].tolist() == [M, 0, M, 0, M, 0, M]      # X_{0,0}
+    assert cnt[1].tolist() == [0, M, 0, M, 0, M, 0]      # X_{0,1}
+    assert cnt[2].tolist() == [0, M, 0, M, 0, M, 0]      # X_{1,0}
+    assert cnt[3].tolist() == [M, 0, M, 0, M, 0, M]      # X_{1,1}
+
+
+def test_walks_star_centre_and_leaf():
+    n_leaves = 9
+    rp, ci = star_graph(n_leaves)
+    M, m = 64, 5
+    w = oracle.sample_walks(rp, ci, np.arange(n_leaves + 1), M, m, rng_seed=5)
+    # from the centre: even positions on the centre, odd positions on leaves
+    assert (w[0, :, 0::2] == 0).all()
+    assert (w[0, :, 1::2] >= 1).all()
+    # from a leaf: odd positions on the centre, even positions on leaves
+    for leaf in range(1, n_leaves + 1):
+        assert (w[leaf, :, 1::2] == 0).all()
+        assert (w[leaf, :, 0::2] >= 1).all()
+        assert (w[leaf, :, 0] == leaf).all()
+    # several different leaves must be reached (a constant choice would be a bug)
+    assert len(set(w[0, :, 1].tolist())) >= 6
+    off, ids, cnt = oracle.build_rpe(w)
+    blk = slice(off[0], off[1])
+    centre_row = cnt[blk][ids[blk] == 0][0]
+    assert centre_row.tolist() == [M, 0, M, 0, M, 0]
+
+
+def test_walks_path_end_and_isolated_node():
+    # nodes 0-1-2-3 form a path, node 4 is isolated
+    rp, ci = synth.csr_from_edge_list(5, [(0, 1), (1, 2), (2, 3)])
+    M, m = 33, 4
+    w = oracle.sample_walks(rp, ci, [0, 3, 4], M, m, rng_seed=9)
+    assert (w[0, :, 1] == 1).all()             # the end node has one neighbour
+    assert (w[1, :, 1] == 2).all()
+    assert (w[2] == 4).all()                   # the walker of a degree-0 node stays put
+    off, ids, cnt = oracle.build_rpe(w[2:3])
+    assert ids.tolist() == [4] and cnt.tolist() == [[M] * (m + 1)]
+
+
+@pytest.mark.parametrize("graph", ["path6", "star5", "cycle6", "grid"])
+def test_walks_bipartite_parity(graph):
+    if graph == "path6":
+        rp, ci = path_graph(6)
+    elif graph == "star5":
+        rp, ci = star_graph(5)
+    elif graph == "cycle6":
+        rp, ci = cycle_graph(6)
+    else:
+        edges = []
+        for r in range(3):
+            for c in range(4):
+                v = r * 4 + c
+                if c < 3:
+                    edges.append((v, v + 1))
+                if r < 2:
+                    edges.append((v, v + 4))
+        rp, ci = synth.csr_from_edge_list(12, edges)
+    n = rp.size - 1
+    # two-colouring by BFS
+    colour = -np.ones(n, dtype=int)
+    colour[0] = 0
+    todo = [0]
+    while todo:
+        v = todo.pop()
+        for x in neighbours(rp, ci, v):
+            if colour[x] < 0:
+                colour[x] = 1 - colour[v]
+                todo.append(x)
+    w = oracle.sample_walks(rp, ci, np.arange(n), 40, 5, rng_seed=1)
+    steps = np.arange(6)[None, None, :]
+    assert ((colour[w] ^ colour[w[:, :, :1]]) == (steps & 1)).all()
+
+
+def test_walk_steps_are_edges_on_a_random_graph():
+    wl = synth.WORKLOADS["rmat4k"]
+    rp, ci = synth.make_graph(wl)
+    n = wl.n_nodes
+    seeds = np.arange(n, dtype=np.int32)
+    w = oracle.sample_walks(rp, ci, seeds, 20, 4, rng_seed=0)
+    assert (w[:, :, 0] == seeds[:, None]).all()
+    deg = np.diff(rp)
+    a = w[:, :, :-1].reshape(-1).astype(np.int64)
+    b = w[:, :, 1:].reshape(-1).astype(np.int64)
+    edge_keys = np.repeat(np.arange(n, dtype=np.int64), deg) * n + ci
+    is_edge = np.isin(a * n + b, edge_keys)
+    stays = (a == b) & (deg[a] == 0)
+    assert (is_edge | stays).all()
+    assert not (is_edge & stays).any()
+
+
+def test_walk_stream_is_keyed_on_seed_start_walk_and_step():
+    rp, ci = complete_graph(9)
+    M, m = 16, 9               # m > 8: the third Philox block (steps 9..) is exercised too
+    base = oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=0)
+    again = oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=0)
+    assert (base == again).all()                                   # deterministic
+    # a seed's walks depend on the start node only, not on its place in the seed list
+    swapped = oracle.sample_walks(rp, ci, [1, 0, 1], M, m, rng_seed=0)
+    assert (swapped[0] == base[1]).all() and (swapped[1] == base[0]).all()
+    assert (swapped[2] == base[1]).all()
+    # low and high half of rng_seed both matter
+    assert (oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=1) != base).any()
+    assert (oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=1 << 32) != base).any()
+    assert (oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=1 << 32) !=
+            oracle.sample_walks(rp, ci, [0, 1], M, m, rng_seed=1)).any()
+    # different walks of one seed, and different steps of one walk, use different words
+    assert len({tuple(x) for x in base[0].tolist()}) > M // 2
+    # different start nodes use different words: in K9 every degree is 8, so a stream that
+    # ignored the start node would pick the same row position at every (walk, step)
+    def row_positions(walks):
+        pos = []
+        for a, b in zip(walks[:, :-1].reshape(-1), walks[:, 1:].reshape(-1)):
+            pos.append(neighbours(rp, ci, a).index(b))
+        return pos
+    assert row_positions(base[0]) != row_positions(base[1])
+
+
+def test_walks_follow_the_stated_stream_exactly():
+    """Replay with the big-integer Philox: word (s-1)&3 of block (s-1)>>2, r mod degree."""
+    rp, ci = lollipop_graph()
+    M, m = 5, 6
+    rng_seed = (0xDEADBEEF << 32) | 0x12345678
+    seeds = [2, 0, 4]
+    got = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed=rng_seed)
+    key = [rng_seed & MASK32, rng_seed >> 32]
+    for i, u in enumerate(seeds):
+        for w in range(M):
+            cur = u
+            want = [u]
+            for s in range(1, m + 1):
+                nb = neighbours(rp, ci, cur)
+                r = py_philox([u, w, (s - 1) >> 2, 0], key)[(s - 1) & 3]
+                cur = nb[r % len(nb)]
+                want.append(cur)
+            assert got[i, w].tolist() == want
+
+
+# --------------------------------------------------------------------------- #
+# walks: distribution against brute-force enumeration
+# --------------------------------------------------------------------------- #
+def enumerate_walks(rp, ci, start, m):
+    """Every m-step neighbour-choice sequence from ``start`` with its exact probability."""
+    out = {}
+
+    def rec(prefix, p):
+        if len(prefix) == m + 1:
+            out[tuple(prefix)] = out.get(tuple(prefix), 0.0) + p
+            return
+        nb = neighbours(rp, ci, prefix[-1])
+        for x in nb:
+            rec(prefix + [x], p / len(nb))
+
+    rec([start], 1.0)
+    return out
+
+
+@pytest.mark.parametrize("name,m", [("path5", 4), ("star6", 3), ("cycle5", 4), ("k4", 3),
+                                    ("lollipop", 4)])
+def test_walk_distribution_matches_enumeration(name, m):
+    rp, ci = {"path5": path_graph(5), "star6": star_graph(6), "cycle5": cycle_graph(5),
+              "k4": complete_graph(4), "lollipop": lollipop_graph()}[name]
+    n = rp.size - 1
+    M, n_rng = 100, 120
+    seeds = np.arange(n)
+    tallies = [dict() for _ in range(n)]
+    landing = np.zeros((n, m + 1, n))
+    for rs in range(n_rng):
+        w = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed=1000 + rs)
+        for u in range(n):
+            for row in w[u].tolist():
+                t = tuple(row)
+                tallies[u][t] = tallies[u].get(t, 0) + 1
+            for s in range(m + 1):
+                landing[u, s] += np.bincount(w[u, :, s], minlength=n)
+    total = M * n_rng
+    for u in range(n):
+        exact = enumerate_walks(rp, ci, u, m)
+        assert abs(sum(exact.values()) - 1.0) < 1e-12
+        assert set(tallies[u]) <= set(exact)          # no impossible walk
+        # whole-walk frequencies: catches any dependence between steps
+        keys = sorted(exact)
+        obs = np.array([tallies[u].get(k, 0) for k in keys], dtype=float)
+        exp = np.array([exact[k] for k in keys]) * total
+        if len(keys) > 1:
+            assert exp.min() >= 5
+            chi = ((obs - exp) ** 2 / exp).sum()
+            assert chi < stats.chi2.ppf(1 - 1e-6, len(keys) - 1), (name, u, chi)
+        # landing counts per step: expectation M * (P^s)[u, x]
+        for s in range(1, m + 1):
+            p = np.zeros(n)
+            for k, pr in exact.items():
+                p[k[s]] += pr
+            sup = p > 0
+            assert landing[u, s][~sup].sum() == 0
+            if sup.sum() > 1:
+                chi = ((landing[u, s][sup] - p[sup] * total) ** 2 / (p[sup] * total)).sum()
+                assert chi < stats.chi2.ppf(1 - 1e-6, sup.sum() - 1), (name, u, s, chi)
+
+
+def test_walks_of_one_seed_are_not_copies_of_each_other():
+    """If the stream ignored the walk index, pooled counts would be over-dispersed by M."""
+    rp, ci = complete_graph(6)
+    M, m = 200, 3
+    w = oracle.sample_walks(rp, ci, [0], M, m, rng_seed=4)
+    # 5 equally likely neighbours at step 1: Pearson statistic with 4 degrees of freedom
+    obs = np.bincount(w[0, :, 1], minlength=6)[1:]
+    chi = ((obs - M / 5) ** 2 / (M / 5)).sum()
+    assert chi < stats.chi2.ppf(1 - 1e-6, 4)
+    assert obs.min() > 0
+
+
+# --------------------------------------------------------------------------- #
+# RPE
+# --------------------------------------------------------------------------- #
+def _read_example(golden_dir):
+    spec = {}
+    with open(os.path.join(golden_dir, "paper_worked_example.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            tok = line.split()
+            if tok[0] == "expect":
+                spec[tok[1]] = [int(x) for x in tok[2:]]
+            else:
+                spec[tok[0]] = [int(x) for x in tok[1:]]
+    return spec
+
+
+def test_paper_worked_example_fragment(golden_dir):
+    ex = _read_example(golden_dir)
+    m, M = ex["m"][0], ex["M"][0]
+    u, v, a = 0, 1, 2
+    walks = np.array([ex["walks_u"], ex["walks_v"]], dtype=np.int32).reshape(2, M, m + 1)
+    off, ids, cnt = oracle.build_rpe(walks)
+
+    def x(block, node):
+        lo, hi = off[block], off[block + 1]
+        hit = np.nonzero(ids[lo:hi] == node)[0]
+        return cnt[lo + hit[0]].tolist() if hit.size else None
+
+    assert cnt.shape[1] == m + 1
+    assert x(0, u) == ex["X_u,u"]
+    assert x(0, a) == ex["X_u,a"]
+    assert x(0, v) == ex["X_u,v"]
+    joff, jids, jcnt = oracle.join_queries(off, ids, cnt, [[u, v]])
+    row = jcnt[np.nonzero(jids == u)[0][0]]
+    assert row.reshape(-1).tolist() == ex["X_Q,u"]
+    # a node of the union that the second patch never visits gets a zero half
+    row_a = jcnt[np.nonzero(jids == a)[0][0]]
+    assert row_a[0].tolist() == ex["X_u,a"] and row_a[1].tolist() == [0] * (m + 1)
+
+
+def dense_rpe(walks, n):
+    """X[i, x, s] by NumPy scatter-add on a dense array (tiny graphs only)."""
+    n_seeds, M, L = walks.shape
+    dense = np.zeros((n_seeds, n, L), dtype=np.int64)
+    i_idx = np.repeat(np.arange(n_seeds), M * L)
+    s_idx = np.tile(np.arange(L), n_seeds * M)
+    np.add.at(dense, (i_idx, walks.reshape(-1), s_idx), 1)
+    return dense
+
+
+@pytest.mark.parametrize("M,m", [(1, 1), (3, 2), (50, 4), (130, 3), (64, 15)])
+def test_rpe_equals_dense_counter_and_keeps_invariants(M, m):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, M, m, 0, 2, "uniform", graph_seed=5)
+    rp, ci = synth.make_graph(wl)
+    n = wl.n_nodes
+    seeds = np.random.default_rng(3).permutation(n)[:97].astype(np.int32)
+    w = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed=77)
+    off, ids, cnt = oracle.build_rpe(w)
+    dense = dense_rpe(w, n)
+    assert off[0] == 0 and off[-1] == ids.size == cnt.shape[0]
+    for i, u in enumerate(seeds):
+        lo, hi = off[i], off[i + 1]
+        blk_ids, blk_cnt = ids[lo:hi], cnt[lo:hi].astype(np.int64)
+        assert 1 <= hi - lo <= 1 + M * m                              # |V_u| bound, App. D.4
+        assert (np.diff(blk_ids) > 0).all()                           # ascending, distinct
+        assert blk_ids.tolist() == np.nonzero(dense[i].sum(axis=1))[0].tolist()
+        assert (blk_cnt == dense[i][blk_ids]).all()
+        assert (blk_cnt.sum(axis=0) == M).all()                       # every step sums to M
+        assert (blk_cnt.sum(axis=1) > 0).all()                        # no empty row
+        own = blk_cnt[blk_ids == u]
+        assert own.shape[0] == 1 and own[0, 0] == M                   # slot 0 = M at the seed
+        assert blk_cnt[blk_ids != u][:, 0].sum() == 0
+
+
+def test_rpe_hand_worked_table():
+    # one seed (node 7), three walks of two steps, written out by hand
+    walks = np.array([[[7, 2, 7], [7, 9, 2], [7, 2, 2]]], dtype=np.int32)
+    off, ids, cnt = oracle.build_rpe(walks)
+    assert off.tolist() == [0, 3]
+    assert ids.tolist() == [2, 7, 9]
+    assert cnt.tolist() == [[0, 2, 2], [3, 0, 1], [0, 1, 0]]
+
+
+def test_rpe_empty_input():
+    off, ids, cnt = oracle.build_rpe(np.zeros((0, 4, 3), dtype=np.int32))
+    assert off.tolist() == [0] and ids.size == 0 and cnt.shape == (0, 3)
+
+
+# --------------------------------------------------------------------------- #
+# join
+# --------------------------------------------------------------------------- #
+def python_join(off, ids, cnt, query):
+    """Sorted set union with zero fill, through Python sets and dicts."""
+    L = cnt.shape[1]
+    maps = []
+    for b in query:
+        lo, hi = off[b], off[b + 1]
+        maps.append({int(x): cnt[lo + j].tolist() for j, x in enumerate(ids[lo:hi])})
+    union = sorted(set().union(*[set(mp) for mp in maps]))
+    rows = [[mp.get(x, [0] * L) for mp in maps] for x in union]
+    return union, rows
+
+
+def _small_table(M=40, m=3, n_seeds=60, graph_seed=8):
+    wl = synth.Workload("t", "chung_lu", 300, 1200, 2.2, M, m, 0, 2, "uniform",
+                        graph_seed=graph_seed)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(n_seeds, dtype=np.int32)
+    w = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed=21)
+    return oracle.build_rpe(w)
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_join_equals_python_set_union(k):
+    off, ids, cnt = _small_table()
+    n_blocks = off.size - 1
+    rng = np.random.default_rng(5)
+    queries = rng.integers(0, n_blocks, size=(80, k)).astype(np.int32)
+    queries[0] = 7                       # a query that repeats one node
+    joff, jids, jcnt = oracle.join_queries(off, ids, cnt, queries)
+    assert joff[0] == 0 and joff[-1] == jids.size
+    assert jcnt.shape == (jids.size, k, cnt.shape[1])
+    overlap_seen = False
+    for q, query in enumerate(queries):
+        union, rows = python_join(off, ids, cnt, query.tolist())
+        lo, hi = joff[q], joff[q + 1]
+        assert jids[lo:hi].tolist() == union
+        assert jcnt[lo:hi].tolist() == rows
+        sizes = [off[b + 1] - off[b] for b in query]
+        overlap_seen |= len(union) < sum(sizes)
+        assert max(sizes) <= len(union) <= sum(sizes)
+    assert overlap_seen                   # the inputs do exercise the shared-node case
+
+
+def test_join_symmetry_and_repeated_node():
+    M, m = 40, 3
+    off, ids, cnt = _small_table(M, m)
+    pairs = np.array([[3, 11], [11, 3], [5, 5], [0, 59]], dtype=np.int32)
+    joff, jids, jcnt = oracle.join_queries(off, ids, cnt, pairs)
+    a = slice(joff[0], joff[1])
+    b = slice(joff[1], joff[2])
+    assert jids[a].tolist() == jids[b].tolist()
+    assert (jcnt[a][:, 0] == jcnt[b][:, 1]).all() and (jcnt[a][:, 1] == jcnt[b][:, 0]).all()
+    # each half keeps "every step sums to M"
+    assert (jcnt[a].astype(np.int64).sum(axis=0) == M).all()
+    # u == v: the union is V_u and both halves are equal
+    c = slice(joff[2], joff[3])
+    assert jids[c].tolist() == ids[off[5]:off[6]].tolist()
+    assert (jcnt[c][:, 0] == jcnt[c][:, 1]).all()
+    assert (jcnt[c][:, 0] == cnt[off[5]:off[6]]).all()
+
+
+def test_triple_join_restricted_to_two_columns_is_the_pair_join():
+    off, ids, cnt = _small_table()
+    L = cnt.shape[1]
+    triple = np.array([[4, 9, 17]], dtype=np.int32)
+    toff, tids, tcnt = oracle.join_queries(off, ids, cnt, triple)
+    for cols in [(0, 1), (0, 2), (1, 2)]:
+        pair = triple[:, list(cols)]
+        poff, pids, pcnt = oracle.join_queries(off, ids, cnt, pair)
+        sub = tcnt[:, list(cols)]
+        in_pair = sub.reshape(tids.size, -1).any(axis=1)
+        assert tids[in_pair].tolist() == pids.tolist()
+        assert (sub[in_pair] == pcnt).all()
+        assert (sub[~in_pair] == 0).all()
+    assert tcnt.shape == (tids.size, 3, L)
+
+
+def test_join_empty_and_single_row_blocks():
+    # block 0 is an isolated node (one row), block 1 a path end
+    rp, ci = synth.csr_from_edge_list(4, [(1, 2), (2, 3)])
+    w = oracle.sample_walks(rp, ci, [0, 1], 6, 2, rng_seed=0)
+    off, ids, cnt = oracle.build_rpe(w)
+    joff, jids, jcnt = oracle.join_queries(off, ids, cnt, np.zeros((0, 2), dtype=np.int32))
+    assert joff.tolist() == [0] and jids.size == 0
+    joff, jids, jcnt = oracle.join_queries(off, ids, cnt, [[0, 1]])
+    assert jids[0] == 0 and jcnt[0].tolist() == [[6, 6, 6], [0, 0, 0]]
+    assert jids.tolist() == sorted(set(ids.tolist()))
