@@ -1,0 +1,159 @@
+/*
+ * libsurel: the walk -> RPE -> join hot path of SUREL on one AMD MI355X (gfx950).
+ *
+ * Three operations, named after the paper's statement of the problem:
+ *   surel_sample_walks   M random walks of m steps from every seed node
+ *                        (Sec. 3.2 "Walk Sampling"; Algorithm 1, walk step);
+ *   surel_build_rpe      per seed u, the set V_u of distinct visited nodes and, for each
+ *                        x in V_u, the landing counts X_{u,x}[0..m]
+ *                        (Sec. 3.2 "Relative Positional Encoding"; Algorithm 1, RPE step);
+ *   surel_join_queries   per query tuple Q, the union of the V_u, u in Q, and for each
+ *                        node x of it the query-level RPE X_{Q,x} = [X_{u,x}]_{u in Q},
+ *                        zeros where x is not in V_u (Sec. 3.4, set-union form).
+ *
+ * Conventions
+ *   - Plain C ABI.  Pointers named d_* are DEVICE memory owned by the caller, on the
+ *     device the context was created for; pointers named h_* are HOST memory.  The library
+ *     never frees or keeps a caller pointer beyond the call's work on the stream.
+ *   - All work is enqueued on the context's stream.  A call returns without waiting unless
+ *     a non-NULL h_rows is passed (then it waits for its own work and reports the row
+ *     total).  Calls on one context must not overlap from several host threads.
+ *   - The context owns a grow-only device workspace (per-seed / per-query counts and scan
+ *     partials) and a 4-byte device error word; nothing else is allocated.
+ *   - Return value: SUREL_OK (0) or a negative SUREL_E_* code.  Arguments are validated on
+ *     the host before anything is enqueued, so a call that returns SUREL_E_NULL or
+ *     SUREL_E_RANGE has launched nothing.  Problems only visible on the device (a seed or
+ *     query index out of range, a malformed CSR row, a node set larger than max_set, an
+ *     output that does not fit cap_rows) never fault: the offending item is skipped or
+ *     clamped, a bit is set in the sticky error word, and surel_check reports it.
+ *   - No function throws, prints, or touches errno.
+ *
+ * Layouts (row-major, densely packed, no padding)
+ *   CSR      d_row_ptr int32[n_nodes+1], d_col_idx int32[n_edges]; entries of a row are the
+ *            neighbours of that node.  The walk treats every entry of a row as equally
+ *            likely, so a simple graph gives the uniform walk over distinct neighbours.
+ *   walks    int32[n_seeds][M][m+1]; walks[i][w][0] = seeds[i].
+ *   RPE      d_rpe_off int64[n_seeds+1] (d_rpe_off[0] = 0); rows d_rpe_off[i] ..
+ *            d_rpe_off[i+1]-1 belong to seed i; d_rpe_ids int32[rows] ascending inside a
+ *            seed's block; d_rpe_cnt uint16[rows][m+1].
+ *   queries  int32[n_queries][k]; an entry selects a seed's block of the RPE table (it is
+ *            the node id when seeds = 0..n_nodes-1).
+ *   join     d_join_off int64[n_queries+1]; d_join_ids int32[rows] ascending inside a
+ *            query's block; d_join_cnt uint16[rows][k][m+1], halves in tuple order.
+ */
+#ifndef SUREL_H
+#define SUREL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define SUREL_OK            0
+#define SUREL_E_NULL       (-1)  /* a required pointer is NULL                              */
+#define SUREL_E_RANGE      (-2)  /* a size or parameter is outside the documented limits    */
+#define SUREL_E_HIP        (-3)  /* a HIP runtime call failed                               */
+#define SUREL_E_CAPACITY   (-4)  /* the output needs more rows than cap_rows (see h_rows)   */
+#define SUREL_E_CTX        (-5)  /* the context pointer is NULL                             */
+#define SUREL_E_DEVICE     (-6)  /* the device error word is non-zero (surel_check)         */
+
+/* bits of the device error word */
+#define SUREL_DEV_BAD_SEED      0x01u  /* a seed is not in [0, n_nodes)                     */
+#define SUREL_DEV_BAD_GRAPH     0x02u  /* a visited CSR row is malformed or names a bad node */
+#define SUREL_DEV_BAD_WALK      0x04u  /* a walk entry is not in [0, n_nodes)               */
+#define SUREL_DEV_BAD_QUERY     0x08u  /* a query entry is not in [0, n_blocks)             */
+#define SUREL_DEV_SET_TOO_LARGE 0x10u  /* a block of the RPE table has more than max_set rows */
+#define SUREL_DEV_CAPACITY      0x20u  /* rows beyond cap_rows were not written             */
+#define SUREL_DEV_BAD_TABLE     0x40u  /* d_rpe_off is not non-decreasing at a queried block */
+
+/* limits */
+#define SUREL_MAX_NODES   268435455   /* 2^28 - 1: node id and step share one 32-bit sort key */
+#define SUREL_MAX_STEPS   15          /* m                                                   */
+#define SUREL_MAX_WALKS   65535       /* M: counts are uint16                                */
+#define SUREL_MAX_WALK_ENTRIES 2048   /* build_rpe: M*(m+1) keys are sorted in one wavefront */
+#define SUREL_MAX_SET     2048        /* join: rows per block of the RPE table               */
+#define SUREL_MAX_TUPLE   3           /* join: k                                             */
+
+typedef struct surel_ctx surel_ctx;
+
+/* Create a context for `device` whose work runs on `hip_stream` (a hipStream_t passed as
+ * void*; NULL = the device's default stream).  The stream is borrowed, not owned.
+ * Errors: SUREL_E_NULL (out), SUREL_E_HIP (no such device, allocation failure). */
+int surel_create(surel_ctx** out, int device, void* hip_stream);
+
+/* Wait for the context's stream, then free the workspace and the context.  NULL is ignored. */
+void surel_destroy(surel_ctx* ctx);
+
+/* A static, human-readable string for a status code. */
+const char* surel_strerror(int status);
+
+/* Largest possible row total of surel_build_rpe for walks made by surel_sample_walks:
+ * n_seeds * (1 + M*m) (App. D.4: at most m*M distinct nodes besides the seed).  Hand-made
+ * walks whose position 0 differs inside one seed can exceed it (up to M*(m+1) per seed);
+ * cap_rows handling covers that.  Non-positive arguments give 0. */
+int64_t surel_rpe_rows_bound(int64_t n_seeds, int32_t M, int32_t m);
+
+/* Sec. 3.2 "Walk Sampling" / Algorithm 1: for every seed i and walk w < M, walk m steps from
+ * u = d_seeds[i].  Step s (1..m) from node c with degree deg = row_ptr[c+1]-row_ptr[c] goes
+ * to col_idx[row_ptr[c] + r mod deg], where r is word (s-1)&3 of Philox-4x32-10 with counter
+ * (u, w, (s-1)>>2, 0) and key (rng_seed & 0xffffffff, rng_seed >> 32); a node of degree 0
+ * keeps the walker in place.  The result depends on (rng_seed, u, w, s) only.
+ *   d_row_ptr, d_col_idx  CSR (device, read-only); n_edges = number of col_idx entries.
+ *   d_seeds               int32[n_seeds] (device, read-only).
+ *   d_walks               int32[n_seeds][M][m+1] (device, written).
+ * Limits: 1 <= n_nodes <= SUREL_MAX_NODES, 0 <= n_edges < 2^31, n_seeds >= 0,
+ * 1 <= M <= SUREL_MAX_WALKS, 1 <= m <= SUREL_MAX_STEPS.  n_seeds = 0 is a no-op.
+ * Device-detected: BAD_SEED (that seed's walks are filled with -1), BAD_GRAPH (the walker
+ * stays in place for that step). */
+int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                       int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                       int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                       int32_t* d_walks);
+
+/* Sec. 3.2 "Relative Positional Encoding" / Algorithm 1: for every seed i, V_i = distinct
+ * node ids in walks[i] (ascending) and cnt[x][s] = #{w : walks[i][w][s] == x}.
+ *   d_walks      int32[n_seeds][M][m+1] (device, read-only), entries in [0, n_nodes).
+ *   cap_rows     rows that d_rpe_ids / d_rpe_cnt can hold.
+ *   d_rpe_off    int64[n_seeds+1] (device, written; always complete, even on overflow).
+ *   d_rpe_ids    int32[cap_rows], d_rpe_cnt uint16[cap_rows][m+1] (device, written).  Both
+ *                may be NULL together: then only d_rpe_off and the total are produced
+ *                (use it to size the outputs exactly; surel_rpe_rows_bound avoids it).
+ *   h_rows       host int64, may be NULL.  If given, the call waits and stores the row total
+ *                (the number needed, also when it exceeds cap_rows).
+ * Limits: as for surel_sample_walks, and M*(m+1) <= SUREL_MAX_WALK_ENTRIES.
+ * Returns SUREL_E_CAPACITY if h_rows is given and the total exceeds cap_rows; rows at or
+ * beyond cap_rows are never written (blocks that do not fit entirely are skipped).
+ * Device-detected: BAD_WALK (the entry counts as node 0), CAPACITY. */
+int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
+                    int32_t m, int32_t n_nodes, int64_t cap_rows, int64_t* d_rpe_off,
+                    int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows);
+
+/* Sec. 3.4, set-union form: for every query q with tuple (b_1..b_k) of table blocks, the
+ * ascending union of the blocks' id lists and, per union node x and j < k, block b_j's count
+ * vector for x, or m+1 zeros when x is not in block b_j.
+ *   d_rpe_off / d_rpe_ids / d_rpe_cnt   an RPE table of n_blocks blocks (device, read-only).
+ *   max_set      an upper bound on the rows of any queried block (1 + M*m always is one).
+ *   d_queries    int32[n_queries][k] (device, read-only), entries in [0, n_blocks).
+ *   cap_rows, d_join_off, d_join_ids, d_join_cnt, h_rows   as in surel_build_rpe, with
+ *                d_join_cnt uint16[cap_rows][k][m+1]; ids / cnt may be NULL together.
+ * Limits: 1 <= m <= SUREL_MAX_STEPS, 2 <= k <= SUREL_MAX_TUPLE, 1 <= max_set <=
+ * SUREL_MAX_SET, n_blocks >= 0, n_queries >= 0.
+ * Device-detected: BAD_QUERY, BAD_TABLE and SET_TOO_LARGE (that query yields zero rows),
+ * CAPACITY (as above). */
+int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                       const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m,
+                       int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                       int32_t k, int64_t cap_rows, int64_t* d_join_off,
+                       int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
+
+/* Wait for the context's stream and read the device error word.  *h_flags (may be NULL)
+ * receives the SUREL_DEV_* bits; the word is then cleared.  Returns SUREL_OK if it was
+ * zero, SUREL_E_DEVICE otherwise, SUREL_E_HIP if the stream reported a failure. */
+int surel_check(surel_ctx* ctx, uint32_t* h_flags);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUREL_H */

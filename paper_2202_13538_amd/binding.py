@@ -1,0 +1,217 @@
+"""ctypes binding of libsurel's C ABI (see include/surel.h).
+
+Argument marshalling only: tensors are passed as raw device pointers, outputs are allocated
+with torch, and every step of the path runs in the library's HIP kernels.  There is no CPU
+fallback: if ``libsurel.so`` has not been built, ``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libsurel.so")
+
+OK, E_NULL, E_RANGE, E_HIP, E_CAPACITY, E_CTX, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
+DEV_BAD_SEED, DEV_BAD_GRAPH, DEV_BAD_WALK, DEV_BAD_QUERY = 0x01, 0x02, 0x04, 0x08
+DEV_SET_TOO_LARGE, DEV_CAPACITY, DEV_BAD_TABLE = 0x10, 0x20, 0x40
+MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
+MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
+
+_vp = ctypes.c_void_p
+_i32, _i64, _u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
+
+# name -> (restype, argtypes); the order and types of include/surel.h
+SIGNATURES = {
+    "surel_create": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.c_int, _vp]),
+    "surel_destroy": (None, [_vp]),
+    "surel_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "surel_rpe_rows_bound": (_i64, [_i64, _i32, _i32]),
+    "surel_sample_walks": (ctypes.c_int, [_vp, _vp, _vp, _i32, _i64, _vp, _i64, _i32, _i32,
+                                          _u64, _vp]),
+    "surel_build_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _i64, _vp, _vp, _vp,
+                                       ctypes.POINTER(_i64)]),
+    "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
+                                          _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
+}
+
+_lib = None
+
+
+class SurelError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load().surel_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def load() -> ctypes.CDLL:
+    """Load libsurel.so.  Raises if it is missing: there is no other implementation."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is not built; run `python -m paper_2202_13538_amd.build` "
+                "(hipcc cross-compiles for gfx950, no GPU needed)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (restype, argtypes) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = restype
+            fn.argtypes = argtypes
+        _lib = lib
+    return _lib
+
+
+def _ptr(t: torch.Tensor | None, dtype: torch.dtype, what: str) -> int | None:
+    if t is None:
+        return None
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError(f"{what} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t.data_ptr()
+
+
+class Context:
+    """Owns one ``surel_ctx`` bound to a device and a HIP stream (torch's current one)."""
+
+    def __init__(self, device: int | torch.device | None = None,
+                 stream: torch.cuda.Stream | None = None):
+        if device is None:
+            device = torch.cuda.current_device()
+        self.device = torch.device("cuda", device) if isinstance(device, int) else device
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        self.stream = stream
+        self._h = _vp()
+        rc = load().surel_create(ctypes.byref(self._h), self.device.index or 0,
+                                 _vp(stream.cuda_stream))
+        if rc != OK:
+            raise SurelError(rc, "surel_create")
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        return self._h
+
+    def check(self) -> int:
+        """Synchronise and return the device error word (also clears it)."""
+        flags = ctypes.c_uint32(0)
+        rc = load().surel_check(self._h, ctypes.byref(flags))
+        if rc not in (OK, E_DEVICE):
+            raise SurelError(rc, "surel_check")
+        return flags.value
+
+    def close(self):
+        if self._h:
+            load().surel_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def rpe_rows_bound(n_seeds: int, M: int, m: int) -> int:
+    return load().surel_rpe_rows_bound(n_seeds, M, m)
+
+
+def sample_walks(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                 seeds: torch.Tensor, M: int, m: int, rng_seed: int = 0,
+                 out: torch.Tensor | None = None) -> torch.Tensor:
+    """walks int32[n_seeds][M][m+1] on the GPU."""
+    n_nodes = row_ptr.numel() - 1
+    n_seeds = seeds.numel()
+    if out is None:
+        out = torch.empty((n_seeds, M, m + 1), dtype=torch.int32, device=row_ptr.device)
+    elif out.numel() != n_seeds * M * (m + 1):
+        raise ValueError("out has the wrong size")
+    rc = load().surel_sample_walks(
+        ctx.handle, _ptr(row_ptr, torch.int32, "row_ptr"), _ptr(col_idx, torch.int32, "col_idx"),
+        n_nodes, col_idx.numel(), _ptr(seeds, torch.int32, "seeds"), n_seeds, M, m,
+        _u64(rng_seed), _ptr(out, torch.int32, "walks"))
+    if rc != OK:
+        raise SurelError(rc, "surel_sample_walks")
+    return out
+
+
+def build_rpe_raw(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int,
+                  rpe_off: torch.Tensor, rpe_ids: torch.Tensor | None,
+                  rpe_cnt: torch.Tensor | None, want_rows: bool = True):
+    """One call of surel_build_rpe into caller buffers.  Returns (status, rows or None)."""
+    n_seeds, M, L = walks.shape
+    rows = _i64(-1)
+    rc = load().surel_build_rpe(
+        ctx.handle, _ptr(walks, torch.int32, "walks"), n_seeds, M, L - 1, n_nodes, cap_rows,
+        _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), ctypes.byref(rows) if want_rows else None)
+    return rc, (rows.value if want_rows else None)
+
+
+def build_rpe(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int | None = None):
+    """(rpe_off int64[n_seeds+1], rpe_ids int32[R], rpe_cnt uint16[R][m+1]) on the GPU.
+
+    ``cap_rows=None`` sizes the outputs with a counting call first; a number allocates that
+    many rows up front (``rpe_rows_bound`` always suffices for sampled walks) and returns
+    views of the first R rows.
+    """
+    n_seeds, M, L = walks.shape
+    dev = walks.device
+    off = torch.empty(n_seeds + 1, dtype=torch.int64, device=dev)
+    if cap_rows is None:
+        rc, rows = build_rpe_raw(ctx, walks, n_nodes, 0, off, None, None)
+        if rc != OK:
+            raise SurelError(rc, "surel_build_rpe (count)")
+        cap_rows = rows
+    ids = torch.empty(cap_rows, dtype=torch.int32, device=dev)
+    cnt = torch.empty((cap_rows, L), dtype=torch.uint16, device=dev)
+    rc, rows = build_rpe_raw(ctx, walks, n_nodes, cap_rows, off, ids, cnt)
+    if rc != OK:
+        raise SurelError(rc, "surel_build_rpe")
+    return off, ids[:rows], cnt[:rows]
+
+
+def join_queries_raw(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
+                     rpe_cnt: torch.Tensor, queries: torch.Tensor, max_set: int, cap_rows: int,
+                     join_off: torch.Tensor, join_ids: torch.Tensor | None,
+                     join_cnt: torch.Tensor | None, want_rows: bool = True):
+    """One call of surel_join_queries into caller buffers.  Returns (status, rows or None)."""
+    n_q, k = queries.shape
+    L = rpe_cnt.shape[1]
+    rows = _i64(-1)
+    rc = load().surel_join_queries(
+        ctx.handle, _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), rpe_off.numel() - 1, L - 1, max_set,
+        _ptr(queries, torch.int32, "queries"), n_q, k, cap_rows,
+        _ptr(join_off, torch.int64, "join_off"), _ptr(join_ids, torch.int32, "join_ids"),
+        _ptr(join_cnt, torch.uint16, "join_cnt"), ctypes.byref(rows) if want_rows else None)
+    return rc, (rows.value if want_rows else None)
+
+
+def join_queries(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
+                 rpe_cnt: torch.Tensor, queries: torch.Tensor, max_set: int,
+                 cap_rows: int | None = None):
+    """(join_off int64[n_q+1], join_ids int32[J], join_cnt uint16[J][k][m+1]) on the GPU."""
+    n_q, k = queries.shape
+    L = rpe_cnt.shape[1]
+    dev = queries.device
+    off = torch.empty(n_q + 1, dtype=torch.int64, device=dev)
+    if cap_rows is None:
+        rc, rows = join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, queries, max_set, 0, off,
+                                    None, None)
+        if rc != OK:
+            raise SurelError(rc, "surel_join_queries (count)")
+        cap_rows = rows
+    ids = torch.empty(cap_rows, dtype=torch.int32, device=dev)
+    cnt = torch.empty((cap_rows, k, L), dtype=torch.uint16, device=dev)
+    rc, rows = join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, queries, max_set, cap_rows, off,
+                                ids, cnt)
+    if rc != OK:
+        raise SurelError(rc, "surel_join_queries")
+    return off, ids[:rows], cnt[:rows]

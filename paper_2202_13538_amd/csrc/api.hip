@@ -1,0 +1,247 @@
+// The C ABI of libsurel: argument validation, workspace management and the launch sequence
+// of each call.  See include/surel.h for the contract of every entry point.
+#include "../../include/surel.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "kernels.h"
+
+struct surel_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int max_lds_bytes = 0;
+    uint32_t* d_err = nullptr;    // sticky device error word
+    int64_t* h_pinned = nullptr;  // 2 x int64 of pinned host memory for small read-backs
+    void* d_ws = nullptr;         // grow-only workspace
+    size_t ws_bytes = 0;
+};
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int device) {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == device) || (hipSetDevice(device) == hipSuccess);
+        if (prev == device) prev = -1;
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace: int32 counts[n] followed by the int64 scan partials.
+int ensure_workspace(surel_ctx* ctx, int64_t n, int32_t** counts, int64_t** partials) {
+    const size_t counts_bytes = align_up((size_t)(n > 0 ? n : 1) * sizeof(int32_t), 256);
+    const size_t part_bytes = (size_t)surel::scan_partials_len(n) * sizeof(int64_t);
+    const size_t need = counts_bytes + align_up(part_bytes, 256);
+    if (need > ctx->ws_bytes) {
+        // the old workspace may still be in use by earlier work on the stream
+        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+        if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+        ctx->d_ws = nullptr;
+        ctx->ws_bytes = 0;
+        if (hipMalloc(&ctx->d_ws, need) != hipSuccess) return SUREL_E_HIP;
+        ctx->ws_bytes = need;
+    }
+    *counts = static_cast<int32_t*>(ctx->d_ws);
+    *partials = reinterpret_cast<int64_t*>(static_cast<char*>(ctx->d_ws) + counts_bytes);
+    return SUREL_OK;
+}
+
+// Wait for the stream and fetch off[n] (the row total) into *h_rows.
+int read_total(surel_ctx* ctx, const int64_t* d_off, int64_t n, int64_t* h_rows) {
+    if (hipMemcpyAsync(ctx->h_pinned, d_off + n, sizeof(int64_t), hipMemcpyDeviceToHost,
+                       ctx->stream) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    *h_rows = ctx->h_pinned[0];
+    return SUREL_OK;
+}
+
+int check_walk_shape(int32_t n_nodes, int64_t n_seeds, int32_t M, int32_t m) {
+    if (n_nodes < 1 || n_nodes > SUREL_MAX_NODES) return SUREL_E_RANGE;
+    if (n_seeds < 0 || n_seeds > 0x7FFFFFFFll) return SUREL_E_RANGE;
+    if (M < 1 || M > SUREL_MAX_WALKS) return SUREL_E_RANGE;
+    if (m < 1 || m > SUREL_MAX_STEPS) return SUREL_E_RANGE;
+    return SUREL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int surel_create(surel_ctx** out, int device, void* hip_stream) {
+    if (!out) return SUREL_E_NULL;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) {
+        (void)hipGetLastError();
+        return SUREL_E_HIP;
+    }
+    DeviceGuard guard(device);
+    if (!guard.ok) return SUREL_E_HIP;
+    surel_ctx* ctx = new (std::nothrow) surel_ctx();
+    if (!ctx) return SUREL_E_HIP;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    bool ok = hipDeviceGetAttribute(&ctx->max_lds_bytes, hipDeviceAttributeMaxSharedMemoryPerBlock,
+                                    device) == hipSuccess;
+    ok = ok && hipMalloc(reinterpret_cast<void**>(&ctx->d_err), 256) == hipSuccess;
+    ok = ok && hipMemsetAsync(ctx->d_err, 0, 256, ctx->stream) == hipSuccess;
+    ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 2 * sizeof(int64_t),
+                             hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipStreamSynchronize(ctx->stream) == hipSuccess;
+    if (!ok) {
+        if (ctx->d_err) (void)hipFree(ctx->d_err);
+        if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
+        delete ctx;
+        (void)hipGetLastError();
+        return SUREL_E_HIP;
+    }
+    *out = ctx;
+    return SUREL_OK;
+}
+
+void surel_destroy(surel_ctx* ctx) {
+    if (!ctx) return;
+    DeviceGuard guard(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+    if (ctx->d_err) (void)hipFree(ctx->d_err);
+    if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
+    delete ctx;
+}
+
+const char* surel_strerror(int status) {
+    switch (status) {
+        case SUREL_OK: return "ok";
+        case SUREL_E_NULL: return "a required pointer is NULL";
+        case SUREL_E_RANGE: return "a size or parameter is outside the documented limits";
+        case SUREL_E_HIP: return "a HIP runtime call failed";
+        case SUREL_E_CAPACITY: return "the output needs more rows than cap_rows";
+        case SUREL_E_CTX: return "the context pointer is NULL";
+        case SUREL_E_DEVICE: return "the device error word is non-zero";
+        default: return "unknown status";
+    }
+}
+
+int64_t surel_rpe_rows_bound(int64_t n_seeds, int32_t M, int32_t m) {
+    if (n_seeds <= 0 || M <= 0 || m <= 0) return 0;
+    return n_seeds * (1 + (int64_t)M * m);
+}
+
+int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                       int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                       int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                       int32_t* d_walks) {
+    if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
+    if (n_edges < 0 || n_edges > 0x7FFFFFFFll) return SUREL_E_RANGE;
+    if (!d_row_ptr || (n_edges > 0 && !d_col_idx)) return SUREL_E_NULL;
+    if (n_seeds > 0 && (!d_seeds || !d_walks)) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    if (n_seeds == 0) return SUREL_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    hipError_t rc = surel::launch_walks(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
+                                        d_seeds, n_seeds, M, m, rng_seed, d_walks, ctx->d_err);
+    return rc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
+}
+
+int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
+                    int32_t m, int32_t n_nodes, int64_t cap_rows, int64_t* d_rpe_off,
+                    int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows) {
+    if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
+    if ((int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
+    if (cap_rows < 0) return SUREL_E_RANGE;
+    if (!d_rpe_off || (n_seeds > 0 && !d_walks)) return SUREL_E_NULL;
+    if ((d_rpe_ids == nullptr) != (d_rpe_cnt == nullptr)) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+
+    int32_t* counts = nullptr;
+    int64_t* partials = nullptr;
+    if (int rc = ensure_workspace(ctx, n_seeds, &counts, &partials)) return rc;
+    hipError_t hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m,
+                                       n_nodes, counts, nullptr, 0, nullptr, nullptr, ctx->d_err);
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    if (hrc != hipSuccess) return SUREL_E_HIP;
+    if (surel::launch_exclusive_scan(ctx->stream, counts, n_seeds, d_rpe_off, partials) !=
+        hipSuccess)
+        return SUREL_E_HIP;
+    if (d_rpe_ids) {
+        hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m, n_nodes,
+                                nullptr, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt, ctx->d_err);
+        if (hrc != hipSuccess) return SUREL_E_HIP;
+    }
+    if (h_rows) {
+        if (int rc = read_total(ctx, d_rpe_off, n_seeds, h_rows)) return rc;
+        if (d_rpe_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
+    }
+    return SUREL_OK;
+}
+
+int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                       const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m,
+                       int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                       int32_t k, int64_t cap_rows, int64_t* d_join_off,
+                       int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows) {
+    if (m < 1 || m > SUREL_MAX_STEPS) return SUREL_E_RANGE;
+    if (k < 2 || k > SUREL_MAX_TUPLE) return SUREL_E_RANGE;
+    if (max_set < 1 || max_set > SUREL_MAX_SET) return SUREL_E_RANGE;
+    if (n_blocks < 0 || n_queries < 0 || n_queries > 0x7FFFFFFFll || cap_rows < 0)
+        return SUREL_E_RANGE;
+    if (!d_join_off) return SUREL_E_NULL;
+    if (n_queries > 0 && (!d_queries || !d_rpe_off || !d_rpe_ids)) return SUREL_E_NULL;
+    if ((d_join_ids == nullptr) != (d_join_cnt == nullptr)) return SUREL_E_NULL;
+    if (n_queries > 0 && d_join_ids && !d_rpe_cnt) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+
+    int32_t* counts = nullptr;
+    int64_t* partials = nullptr;
+    if (int rc = ensure_workspace(ctx, n_queries, &counts, &partials)) return rc;
+    hipError_t hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids,
+                                        d_rpe_cnt, n_blocks, m, max_set, d_queries, n_queries, k,
+                                        counts, nullptr, 0, nullptr, nullptr, ctx->d_err);
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    if (hrc != hipSuccess) return SUREL_E_HIP;
+    if (surel::launch_exclusive_scan(ctx->stream, counts, n_queries, d_join_off, partials) !=
+        hipSuccess)
+        return SUREL_E_HIP;
+    if (d_join_ids) {
+        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
+                                 n_blocks, m, max_set, d_queries, n_queries, k, nullptr,
+                                 d_join_off, cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
+        if (hrc != hipSuccess) return SUREL_E_HIP;
+    }
+    if (h_rows) {
+        if (int rc = read_total(ctx, d_join_off, n_queries, h_rows)) return rc;
+        if (d_join_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
+    }
+    return SUREL_OK;
+}
+
+int surel_check(surel_ctx* ctx, uint32_t* h_flags) {
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    uint32_t* h_word = reinterpret_cast<uint32_t*>(ctx->h_pinned + 1);
+    if (hipMemcpyAsync(h_word, ctx->d_err, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                       ctx->stream) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipMemsetAsync(ctx->d_err, 0, sizeof(uint32_t), ctx->stream) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    if (h_flags) *h_flags = *h_word;
+    return *h_word == 0 ? SUREL_OK : SUREL_E_DEVICE;
+}
+
+}  // extern "C"

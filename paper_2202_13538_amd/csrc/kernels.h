@@ -1,0 +1,34 @@
+// Host-side launch wrappers of the HIP kernels (internal to libsurel).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace surel {
+
+// walk.hip
+hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
+                        int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
+                        int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks, uint32_t* err);
+
+// rpe.hip.  counts != nullptr: write per-seed row counts.  ids != nullptr: write the rows of
+// every seed at rpe_off[i] (seeds whose block would pass cap_rows are skipped).
+hipError_t launch_rpe(hipStream_t stream, int max_lds_bytes, const int32_t* walks,
+                      int64_t n_seeds, int32_t M, int32_t m, int32_t n_nodes, int32_t* counts,
+                      const int64_t* rpe_off, int64_t cap_rows, int32_t* ids, uint16_t* cnt,
+                      uint32_t* err);
+
+// join.hip.  Same two modes as launch_rpe.
+hipError_t launch_join(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
+                       const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
+                       int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
+                       int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
+                       int32_t* out_ids, uint16_t* out_cnt, uint32_t* err);
+
+// scan.hip.  off[0..n] = exclusive prefix sums of counts[0..n-1] (off[n] = total).
+// partials: device scratch of scan_partials_len(n) int64.
+int64_t scan_partials_len(int64_t n);
+hipError_t launch_exclusive_scan(hipStream_t stream, const int32_t* counts, int64_t n,
+                                 int64_t* off, int64_t* partials);
+
+}  // namespace surel

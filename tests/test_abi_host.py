@@ -1,0 +1,181 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the public header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2202_13538_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "surel.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2202_13538_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(surel_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_name_the_same_entry_points():
+    assert declared_functions() == sorted(binding.SIGNATURES)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_header_constants_match_binding():
+    text = open(HEADER).read()
+    defs = dict(re.findall(r"#define\s+(SUREL_[A-Z_]+)\s+\(?(-?[0-9a-fx]+)u?\)?", text))
+    val = {k: int(v, 0) for k, v in defs.items()}
+    assert val["SUREL_OK"] == binding.OK
+    assert val["SUREL_E_NULL"] == binding.E_NULL
+    assert val["SUREL_E_RANGE"] == binding.E_RANGE
+    assert val["SUREL_E_HIP"] == binding.E_HIP
+    assert val["SUREL_E_CAPACITY"] == binding.E_CAPACITY
+    assert val["SUREL_E_CTX"] == binding.E_CTX
+    assert val["SUREL_E_DEVICE"] == binding.E_DEVICE
+    assert val["SUREL_DEV_BAD_SEED"] == binding.DEV_BAD_SEED
+    assert val["SUREL_DEV_BAD_GRAPH"] == binding.DEV_BAD_GRAPH
+    assert val["SUREL_DEV_BAD_WALK"] == binding.DEV_BAD_WALK
+    assert val["SUREL_DEV_BAD_QUERY"] == binding.DEV_BAD_QUERY
+    assert val["SUREL_DEV_SET_TOO_LARGE"] == binding.DEV_SET_TOO_LARGE
+    assert val["SUREL_DEV_CAPACITY"] == binding.DEV_CAPACITY
+    assert val["SUREL_DEV_BAD_TABLE"] == binding.DEV_BAD_TABLE
+    assert val["SUREL_MAX_NODES"] == binding.MAX_NODES
+    assert val["SUREL_MAX_STEPS"] == binding.MAX_STEPS
+    assert val["SUREL_MAX_WALKS"] == binding.MAX_WALKS
+    assert val["SUREL_MAX_WALK_ENTRIES"] == binding.MAX_WALK_ENTRIES
+    assert val["SUREL_MAX_SET"] == binding.MAX_SET
+    assert val["SUREL_MAX_TUPLE"] == binding.MAX_TUPLE
+
+
+def test_strerror_and_bound(lib):
+    for status in range(-6, 1):
+        assert lib.surel_strerror(status)
+    assert lib.surel_strerror(-99) == b"unknown status"
+    assert lib.surel_rpe_rows_bound(10, 50, 4) == 10 * 201
+    assert lib.surel_rpe_rows_bound(2_900_000, 100, 4) == 2_900_000 * 401
+    assert lib.surel_rpe_rows_bound(0, 50, 4) == 0
+    assert lib.surel_rpe_rows_bound(-1, 50, 4) == 0
+
+
+# A fake non-NULL pointer: argument checks must finish before anything is dereferenced.
+P = ctypes.c_void_p(0x1000)
+NULL = None
+
+
+def walks_args(**kw):
+    a = dict(ctx=NULL, row_ptr=P, col_idx=P, n_nodes=100, n_edges=500, seeds=P, n_seeds=10,
+             M=50, m=4, rng_seed=0, walks=P)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "row_ptr", "col_idx", "n_nodes", "n_edges", "seeds", "n_seeds",
+                           "M", "m", "rng_seed", "walks")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),                      # everything valid except the context
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(n_nodes=binding.MAX_NODES + 1), binding.E_RANGE),
+    (dict(n_edges=-1), binding.E_RANGE),
+    (dict(n_edges=1 << 31), binding.E_RANGE),
+    (dict(n_seeds=-1), binding.E_RANGE),
+    (dict(M=0), binding.E_RANGE),
+    (dict(M=binding.MAX_WALKS + 1), binding.E_RANGE),
+    (dict(m=0), binding.E_RANGE),
+    (dict(m=binding.MAX_STEPS + 1), binding.E_RANGE),
+    (dict(row_ptr=NULL), binding.E_NULL),
+    (dict(col_idx=NULL), binding.E_NULL),
+    (dict(col_idx=NULL, n_edges=0), binding.E_CTX),   # an edgeless graph needs no col_idx
+    (dict(seeds=NULL), binding.E_NULL),
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(seeds=NULL, walks=NULL, n_seeds=0), binding.E_CTX),
+])
+def test_sample_walks_argument_checks(lib, kw, want):
+    assert lib.surel_sample_walks(*walks_args(**kw)) == want
+
+
+def rpe_args(**kw):
+    a = dict(ctx=NULL, walks=P, n_seeds=10, M=50, m=4, n_nodes=100, cap_rows=1000, off=P, ids=P,
+             cnt=P, h_rows=NULL)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "walks", "n_seeds", "M", "m", "n_nodes", "cap_rows", "off",
+                           "ids", "cnt", "h_rows")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(M=400, m=4), binding.E_CTX),            # 2000 walk entries: the paper's largest M
+    (dict(M=410, m=4), binding.E_RANGE),          # 2050 > SUREL_MAX_WALK_ENTRIES
+    (dict(M=128, m=15), binding.E_CTX),           # exactly 2048
+    (dict(M=129, m=15), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(M=0), binding.E_RANGE),
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(n_seeds=-5), binding.E_RANGE),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),             # ids and cnt go together
+    (dict(cnt=NULL), binding.E_NULL),
+    (dict(ids=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),   # counting call
+])
+def test_build_rpe_argument_checks(lib, kw, want):
+    assert lib.surel_build_rpe(*rpe_args(**kw)) == want
+
+
+def join_args(**kw):
+    a = dict(ctx=NULL, off=P, ids=P, cnt=P, n_blocks=100, m=4, max_set=201, queries=P, n_q=10,
+             k=2, cap_rows=1000, joff=P, jids=P, jcnt=P, h_rows=NULL)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "off", "ids", "cnt", "n_blocks", "m", "max_set", "queries",
+                           "n_q", "k", "cap_rows", "joff", "jids", "jcnt", "h_rows")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(k=3), binding.E_CTX),
+    (dict(k=1), binding.E_RANGE),
+    (dict(k=4), binding.E_RANGE),
+    (dict(m=0), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(max_set=0), binding.E_RANGE),
+    (dict(max_set=binding.MAX_SET), binding.E_CTX),
+    (dict(max_set=binding.MAX_SET + 1), binding.E_RANGE),
+    (dict(n_blocks=-1), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(joff=NULL), binding.E_NULL),
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(cnt=NULL), binding.E_NULL),
+    (dict(jids=NULL), binding.E_NULL),
+    (dict(jids=NULL, jcnt=NULL, cap_rows=0), binding.E_CTX),
+    (dict(jids=NULL, jcnt=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),  # counting needs no counts
+])
+def test_join_queries_argument_checks(lib, kw, want):
+    assert lib.surel_join_queries(*join_args(**kw)) == want
+
+
+def test_check_and_destroy_tolerate_null(lib):
+    assert lib.surel_check(NULL, NULL) == binding.E_CTX
+    lib.surel_destroy(NULL)
+
+
+def test_create_reports_missing_device_or_bad_arguments(lib):
+    assert lib.surel_create(None, 0, None) == binding.E_NULL
+    handle = ctypes.c_void_p()
+    rc = lib.surel_create(ctypes.byref(handle), 1 << 20, None)   # no such device anywhere
+    assert rc == binding.E_HIP and not handle.value

@@ -1,0 +1,378 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on a real MI355X.
+
+Bit-exact comparison of walks, RPE tables and joins: element by element on small and
+medium inputs (several tiles, ragged tails, the degenerate cases), and at the full workload
+sizes on sampled seeds / queries that the oracle computes one by one plus invariants that
+hold at any size.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2202_13538_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    assert os.path.exists(binding.LIB_PATH), "libsurel.so is not built"
+    c = binding.Context()
+    yield c
+    c.close()
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def host_u16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def gpu_pipeline(ctx, rp, ci, seeds, M, m, rng_seed, queries=None):
+    d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(np.asarray(seeds, dtype=np.int32))
+    n_nodes = rp.size - 1
+    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, rng_seed)
+    off, ids, cnt = binding.build_rpe(ctx, walks, n_nodes)
+    out = {"walks": walks, "rpe": (off, ids, cnt)}
+    if queries is not None:
+        d_q = dev(np.asarray(queries, dtype=np.int32))
+        out["join"] = binding.join_queries(ctx, off, ids, cnt, d_q, max_set=1 + M * m)
+    assert ctx.check() == 0
+    return out
+
+
+def assert_table_equal(got, want, what):
+    g_off, g_ids, g_cnt = got
+    w_off, w_ids, w_cnt = want
+    assert np.array_equal(g_off.cpu().numpy(), w_off), f"{what}: offsets differ"
+    assert np.array_equal(g_ids.cpu().numpy(), w_ids), f"{what}: ids differ"
+    assert np.array_equal(host_u16(g_cnt), w_cnt), f"{what}: counts differ"
+
+
+def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
+    out = gpu_pipeline(ctx, rp, ci, seeds, M, m, rng_seed, queries)
+    w = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed)
+    assert np.array_equal(out["walks"].cpu().numpy(), w), "walks differ"
+    table = oracle.build_rpe(w)
+    assert_table_equal(out["rpe"], table, "rpe")
+    if queries is not None:
+        assert_table_equal(out["join"], oracle.join_queries(*table, queries), "join")
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# small and medium inputs, element by element
+# --------------------------------------------------------------------------- #
+def test_rmat4k_whole_pipeline_bit_exact(ctx):
+    wl = synth.WORKLOADS["rmat4k"]
+    rp, ci = synth.make_graph(wl)
+    queries = synth.make_queries(wl, rp, ci)
+    seeds = np.arange(wl.n_nodes, dtype=np.int32)
+    full_compare(ctx, rp, ci, seeds, wl.M, wl.m, wl.rng_seed, queries)
+
+
+@pytest.mark.parametrize("M,m", [(1, 1), (3, 2), (50, 4), (64, 3), (65, 3), (100, 4), (130, 3),
+                                 (200, 4), (200, 3), (128, 15), (400, 4), (341, 5), (7, 15)])
+@pytest.mark.parametrize("k", [2, 3])
+def test_shapes_bit_exact(ctx, M, m, k):
+    wl = synth.Workload("t", "rmat", 1024, 5000, 0.0, M, m, 300, k, "uniform",
+                        graph_seed=100 + M + m)
+    rp, ci = synth.make_graph(wl)
+    rng = np.random.default_rng(M * 31 + m)
+    # a ragged, unordered seed list with repeats: 4 waves per workgroup leave a tail
+    seeds = rng.integers(0, wl.n_nodes, size=203).astype(np.int32)
+    queries = rng.integers(0, seeds.size, size=(301, k)).astype(np.int32)
+    queries[0] = 5                                    # every entry the same block
+    full_compare(ctx, rp, ci, seeds, M, m, 0xABCDEF0123456789 & ((1 << 64) - 1), queries)
+
+
+def test_tiny_graphs_and_isolated_nodes(ctx):
+    # path 0-1-2-3, isolated node 4, star centred on 5 with leaves 6..9
+    rp, ci = synth.csr_from_edge_list(10, [(0, 1), (1, 2), (2, 3), (5, 6), (5, 7), (5, 8), (5, 9)])
+    seeds = np.arange(10, dtype=np.int32)
+    queries = np.array([[4, 4], [4, 0], [0, 3], [5, 6], [9, 4]], dtype=np.int32)
+    out = full_compare(ctx, rp, ci, seeds, 33, 4, 7, queries)
+    walks = out["walks"].cpu().numpy()
+    assert (walks[4] == 4).all()
+    assert (walks[0, :, 1] == 1).all()
+
+
+def test_edgeless_graph(ctx):
+    rp = np.zeros(6, dtype=np.int32)
+    ci = np.zeros(0, dtype=np.int32)
+    seeds = np.array([3, 0, 4], dtype=np.int32)
+    queries = np.array([[0, 1], [2, 2]], dtype=np.int32)
+    full_compare(ctx, rp, ci, seeds, 10, 3, 1, queries)
+
+
+def test_empty_seed_and_query_lists(ctx):
+    wl = synth.WORKLOADS["rmat4k"]
+    rp, ci = synth.make_graph(wl)
+    out = gpu_pipeline(ctx, rp, ci, np.zeros(0, dtype=np.int32), 50, 4, 0,
+                       np.zeros((0, 2), dtype=np.int32))
+    assert out["walks"].shape == (0, 50, 5)
+    off, ids, cnt = out["rpe"]
+    assert off.cpu().tolist() == [0] and ids.numel() == 0 and cnt.numel() == 0
+    joff, jids, jcnt = out["join"]
+    assert joff.cpu().tolist() == [0] and jids.numel() == 0
+    # an empty query list against a non-empty table
+    out = gpu_pipeline(ctx, rp, ci, np.arange(8, dtype=np.int32), 50, 4, 0,
+                       np.zeros((0, 3), dtype=np.int32))
+    assert out["join"][0].cpu().tolist() == [0]
+
+
+def test_paper_worked_example_on_the_gpu(ctx, golden_dir):
+    from test_oracle_pins import _read_example
+    ex = _read_example(golden_dir)
+    m, M = ex["m"][0], ex["M"][0]
+    walks = np.array([ex["walks_u"], ex["walks_v"]], dtype=np.int32).reshape(2, M, m + 1)
+    off, ids, cnt = binding.build_rpe(ctx, dev(walks), n_nodes=7)
+    joff, jids, jcnt = binding.join_queries(ctx, off, ids, cnt, dev(np.array([[0, 1]], np.int32)),
+                                            max_set=1 + M * m)
+    assert ctx.check() == 0
+    ids_h, cnt_h = ids.cpu().numpy(), host_u16(cnt)
+    blk = slice(int(off[0]), int(off[1]))
+    assert cnt_h[blk][ids_h[blk] == 0][0].tolist() == ex["X_u,u"]
+    assert cnt_h[blk][ids_h[blk] == 2][0].tolist() == ex["X_u,a"]
+    assert cnt_h[blk][ids_h[blk] == 1][0].tolist() == ex["X_u,v"]
+    row = host_u16(jcnt)[jids.cpu().numpy() == 0][0]
+    assert row.reshape(-1).tolist() == ex["X_Q,u"]
+    assert_table_equal((off, ids, cnt), oracle.build_rpe(walks), "rpe")
+
+
+def test_hand_made_walks_with_mixed_start_nodes(ctx):
+    # build_rpe counts whatever the walk block holds, also when position 0 varies
+    rng = np.random.default_rng(4)
+    walks = rng.integers(0, 40, size=(37, 20, 4)).astype(np.int32)
+    off, ids, cnt = binding.build_rpe(ctx, dev(walks), n_nodes=40)
+    assert ctx.check() == 0
+    assert_table_equal((off, ids, cnt), oracle.build_rpe(walks), "rpe")
+
+
+def test_two_runs_are_identical(ctx):
+    wl = synth.WORKLOADS["rmat4k"]
+    rp, ci = synth.make_graph(wl)
+    queries = synth.make_queries(wl, rp, ci)
+    seeds = np.arange(wl.n_nodes, dtype=np.int32)
+    a = gpu_pipeline(ctx, rp, ci, seeds, wl.M, wl.m, 5, queries)
+    b = gpu_pipeline(ctx, rp, ci, seeds, wl.M, wl.m, 5, queries)
+    assert torch.equal(a["walks"], b["walks"])
+    for x, y in zip(a["rpe"] + a["join"], b["rpe"] + b["join"]):
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.uint16 else x,
+                           y.view(torch.int16) if y.dtype == torch.uint16 else y)
+
+
+# --------------------------------------------------------------------------- #
+# device-detected problems never fault and are reported
+# --------------------------------------------------------------------------- #
+def test_bad_seed_is_flagged_and_skipped(ctx):
+    rp, ci = synth.csr_from_edge_list(5, [(0, 1), (1, 2), (2, 3), (3, 4)])
+    seeds = np.array([1, 99, -3, 2], dtype=np.int32)
+    walks = binding.sample_walks(ctx, dev(rp), dev(ci), dev(seeds), 9, 3, 0)
+    assert ctx.check() == binding.DEV_BAD_SEED
+    assert ctx.check() == 0                                # the word is cleared by the read
+    w = walks.cpu().numpy()
+    assert (w[1] == -1).all() and (w[2] == -1).all()
+    good = oracle.sample_walks(rp, ci, seeds[[0, 3]], 9, 3, 0)
+    assert np.array_equal(w[[0, 3]], good)
+
+
+def test_malformed_csr_is_flagged(ctx):
+    rp = np.array([0, 2, 4, 6], dtype=np.int32)
+    ci = np.array([1, 2, 0, 77, 0, 1], dtype=np.int32)     # node 77 does not exist
+    walks = binding.sample_walks(ctx, dev(rp), dev(ci), dev(np.arange(3, dtype=np.int32)), 64, 4, 0)
+    assert ctx.check() == binding.DEV_BAD_GRAPH
+    w = walks.cpu().numpy()
+    assert ((w >= 0) & (w < 3)).all()
+
+
+def test_bad_walk_entry_is_flagged(ctx):
+    walks = np.zeros((3, 4, 3), dtype=np.int32)
+    walks[1, 2, 1] = 1000
+    off = torch.empty(4, dtype=torch.int64, device="cuda")
+    rc, rows = binding.build_rpe_raw(ctx, dev(walks), 10, 0, off, None, None)
+    assert rc == binding.OK and rows == 3
+    assert ctx.check() == binding.DEV_BAD_WALK
+
+
+def test_rpe_capacity_overflow_is_reported_and_nothing_is_written_past_it(ctx):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(64, dtype=np.int32)
+    walks = binding.sample_walks(ctx, dev(rp), dev(ci), dev(seeds), wl.M, wl.m, 0)
+    want_off, want_ids, want_cnt = oracle.build_rpe(walks.cpu().numpy())
+    total = int(want_off[-1])
+    cap = total // 2
+    L = wl.m + 1
+    off = torch.empty(65, dtype=torch.int64, device="cuda")
+    ids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((total, L), 0x7777, dtype=torch.int16, device="cuda").view(torch.uint16)
+    rc, rows = binding.build_rpe_raw(ctx, walks, wl.n_nodes, cap, off, ids, cnt)
+    assert rc == binding.E_CAPACITY and rows == total
+    assert ctx.check() == binding.DEV_CAPACITY
+    assert np.array_equal(off.cpu().numpy(), want_off)      # offsets are complete anyway
+    ids_h, cnt_h = ids.cpu().numpy(), host_u16(cnt)
+    assert (ids_h[cap:] == -7).all() and (cnt_h[cap:] == 0x7777).all()
+    fits = want_off[1:] <= cap                               # blocks that fit are written
+    last = int(want_off[1:][fits].max())
+    assert np.array_equal(ids_h[:last], want_ids[:last])
+    assert np.array_equal(cnt_h[:last], want_cnt[:last])
+
+
+def test_join_problems_are_flagged(ctx):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(32, dtype=np.int32)
+    out = gpu_pipeline(ctx, rp, ci, seeds, wl.M, wl.m, 0)
+    off, ids, cnt = out["rpe"]
+    table = oracle.build_rpe(out["walks"].cpu().numpy())
+    good = np.array([[1, 2], [3, 4]], dtype=np.int32)
+    want = oracle.join_queries(*table, good)
+    # a query entry outside the table: that query yields no rows, the others are intact
+    q = np.array([[1, 2], [5, 32], [-1, 0], [3, 4]], dtype=np.int32)
+    joff, jids, jcnt = binding.join_queries(ctx, off, ids, cnt, dev(q), max_set=61)
+    assert ctx.check() == binding.DEV_BAD_QUERY
+    joff_h = joff.cpu().numpy()
+    assert joff_h[2] == joff_h[1] and joff_h[3] == joff_h[2]
+    assert np.array_equal(jids.cpu().numpy(), want[1])
+    assert np.array_equal(host_u16(jcnt), want[2])
+    # max_set smaller than a queried block
+    sizes = np.diff(table[0])
+    big = int(np.argmax(sizes))
+    assert sizes[big] >= 2
+    joff, jids, jcnt = binding.join_queries(ctx, off, ids, cnt,
+                                            dev(np.array([[big, big]], np.int32)),
+                                            max_set=int(sizes[big]) - 1)
+    assert ctx.check() == binding.DEV_SET_TOO_LARGE
+    assert jids.numel() == 0
+    # capacity
+    joff = torch.empty(3, dtype=torch.int64, device="cuda")
+    total = int(want[0][-1])
+    jids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    jcnt = torch.zeros((total, 2, 4), dtype=torch.int16, device="cuda").view(torch.uint16)
+    cap = int(want[0][1])                                    # room for the first query only
+    rc, rows = binding.join_queries_raw(ctx, off, ids, cnt, dev(good), 61, cap, joff, jids, jcnt)
+    assert rc == binding.E_CAPACITY and rows == total
+    assert ctx.check() == binding.DEV_CAPACITY
+    assert np.array_equal(jids.cpu().numpy()[:cap], want[1][:cap])
+    assert (jids.cpu().numpy()[cap:] == -7).all()
+
+
+# --------------------------------------------------------------------------- #
+# full workload sizes: sampled blocks against the oracle + invariants at any size
+# --------------------------------------------------------------------------- #
+def segment_sums(flat_u16, off, chunk=1 << 24):
+    """Per-segment column sums of a uint16 [rows][cols] tensor, segments given by ``off``."""
+    n_seg = off.numel() - 1
+    rows, cols = flat_u16.shape
+    sizes = off[1:] - off[:-1]
+    seg_of_row = torch.repeat_interleave(torch.arange(n_seg, device=off.device), sizes)
+    sums = torch.zeros((n_seg, cols), dtype=torch.int64, device=off.device)
+    as_i16 = flat_u16.view(torch.int16)
+    for s in range(0, rows, chunk):
+        e = min(rows, s + chunk)
+        sums.index_add_(0, seg_of_row[s:e], as_i16[s:e].to(torch.int64) & 0xFFFF)
+    return sums
+
+
+def rows_u16(t, rows_d):
+    """Selected rows of a uint16 device tensor as a host uint16 array."""
+    return t.view(torch.int16)[rows_d].cpu().numpy().view(np.uint16)
+
+
+def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
+    wl = synth.WORKLOADS[name]
+    rp, ci = synth.make_graph(wl)
+    queries = synth.make_queries(wl, rp, ci)
+    N, M, m, k = wl.n_nodes, wl.M, wl.m, wl.k
+    L = m + 1
+    d_rp, d_ci = dev(rp), dev(ci)
+    d_seeds = torch.arange(N, dtype=torch.int32, device="cuda")
+    print(f"[{name}] graph ready: N={N} E2={ci.size} M={M} m={m} queries={queries.shape}",
+          flush=True)
+
+    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed)
+    off, ids, cnt = binding.build_rpe(ctx, walks, N, cap_rows=binding.rpe_rows_bound(N, M, m))
+    assert ctx.check() == 0
+    R = int(off[-1])
+    print(f"[{name}] walks + rpe done: R={R} rows", flush=True)
+
+    rng = np.random.default_rng(12345)
+    deg = np.diff(rp)
+    pick = np.unique(np.concatenate([
+        [0, 1, N - 2, N - 1], rng.integers(0, N, size=n_sample_seeds),
+        np.argsort(deg)[-8:], np.nonzero(deg == 0)[0][:8]])).astype(np.int32)
+    w_or = oracle.sample_walks(rp, ci, pick, M, m, wl.rng_seed)
+    assert np.array_equal(walks[torch.from_numpy(pick).long().cuda()].cpu().numpy(), w_or), \
+        "sampled walks differ"
+    t_off, t_ids, t_cnt = oracle.build_rpe(w_or)
+    off_h = off.cpu().numpy()
+    assert np.array_equal(off_h[pick + 1] - off_h[pick], np.diff(t_off)), "block sizes differ"
+    rows = np.concatenate([np.arange(off_h[u], off_h[u + 1]) for u in pick])
+    rows_d = torch.from_numpy(rows).cuda()
+    assert np.array_equal(ids[rows_d].cpu().numpy(), t_ids), "sampled rpe ids differ"
+    assert np.array_equal(rows_u16(cnt, rows_d), t_cnt), "sampled rpe counts differ"
+
+    # invariants over the whole table
+    assert int(off[0]) == 0 and bool((off[1:] > off[:-1]).all())
+    assert bool((segment_sums(cnt, off) == M).all()), "a step's counts do not sum to M"
+    inner = torch.ones(R, dtype=torch.bool, device="cuda")
+    inner[off[:-1]] = False                                  # first row of every block
+    assert bool((ids[1:] > ids[:-1])[inner[1:]].all()), "ids not ascending inside a block"
+    slot0 = cnt.view(torch.int16)[:, 0].to(torch.int32) & 0xFFFF
+    assert int((slot0 > 0).sum()) == N and bool((slot0[slot0 > 0] == M).all())
+    del inner, slot0
+    print(f"[{name}] rpe parity + invariants ok", flush=True)
+
+    d_q = dev(queries)
+    joff, jids, jcnt = binding.join_queries(ctx, off, ids, cnt, d_q, max_set=1 + M * m)
+    assert ctx.check() == 0
+    J = int(joff[-1])
+    print(f"[{name}] join done: J={J} rows", flush=True)
+    qpick = np.unique(np.concatenate([[0, wl.n_queries - 1],
+                                      rng.integers(0, wl.n_queries, size=n_sample_queries)]))
+    sub_q = queries[qpick]
+    nodes, local = np.unique(sub_q, return_inverse=True)
+    local = local.reshape(sub_q.shape).astype(np.int32)
+    sub_table = oracle.build_rpe(oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m,
+                                                     wl.rng_seed))
+    w_joff, w_jids, w_jcnt = oracle.join_queries(*sub_table, local)
+    joff_h = joff.cpu().numpy()
+    assert np.array_equal(joff_h[qpick + 1] - joff_h[qpick], np.diff(w_joff)), "join sizes differ"
+    jrows = torch.from_numpy(np.concatenate(
+        [np.arange(joff_h[q], joff_h[q + 1]) for q in qpick])).cuda()
+    assert np.array_equal(jids[jrows].cpu().numpy(), w_jids), "sampled join ids differ"
+    assert np.array_equal(rows_u16(jcnt, jrows), w_jcnt), "sampled join counts differ"
+
+    # invariants over the whole join: sizes bounded by the parts, every half sums to M
+    sizes = (off[1:] - off[:-1])[d_q.long()]
+    jn = joff[1:] - joff[:-1]
+    assert bool((jn >= sizes.max(dim=1).values).all()) and bool((jn <= sizes.sum(dim=1)).all())
+    half_sums = segment_sums(jcnt.reshape(J, k * L), joff)
+    assert bool((half_sums == M).all()), "a joined half does not sum to M per step"
+    print(f"[{name}] join parity + invariants ok", flush=True)
+
+
+def test_cl235k_full_size(ctx):
+    check_workload(ctx, "cl235k")
+
+
+def test_rmat512k_full_size(ctx):
+    check_workload(ctx, "rmat512k")
+
+
+def test_cl2900k_full_size(ctx):
+    check_workload(ctx, "cl2900k", n_sample_seeds=1200, n_sample_queries=500)
+
+
+def test_cl1m_triples_full_size(ctx):
+    check_workload(ctx, "cl1m_triples")
