@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the walk -> RPE -> join hot path on one MI355X.
+
+A step is one pass of the whole path over the workload: sample_walks for every node,
+build_rpe over all walks, join_queries over all query tuples, inputs already resident in
+HBM and output buffers allocated beforehand.  The line printed at the end follows the
+driver's contract; `value` is walk-steps/s through the whole pipeline (the stage rates and
+the HBM-roofline fractions are extra keys of the same line).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cl2900k]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+METRIC = "walk-steps/s + joined query-RPE rows/s at 1 GPU; % of HBM roofline"
+
+
+def log(msg: str) -> None:
+    print(msg, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(N, M, m, k, R, J, in_rows, Q):
+    """Bytes the method itself must move, per stage (one pass)."""
+    L = m + 1
+    walk = N * M * m * 12 + N * M * L * 4 + N * 4
+    rpe = N * M * L * 4 + R * (4 + 2 * L) + (N + 1) * 8
+    join = in_rows * (4 + 2 * L) + Q * k * (4 + 16) + J * (4 + 2 * k * L) + (Q + 1) * 8
+    return {"walk": walk, "rpe": rpe, "join": join}
+
+
+def read_traffic(workload: str):
+    """HBM traffic per launch measured with rocprofv3 --pmc, from profiles/ (or None)."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    table = {}
+    if not os.path.exists(path):
+        return table
+    with open(path) as fh:
+        for line in fh:
+            tok = line.split()
+            if len(tok) == 3 and not line.startswith("#"):
+                table[tok[0]] = float(tok[1]) + float(tok[2])
+    return table
+
+
+def cpu_baseline(wl, rp, ci, queries, n_seeds_sample, n_query_sample):
+    """The oracle, as it stands, on one host core over a bounded sample of the workload."""
+    import numpy as np
+
+    import oracle
+
+    N, M, m = wl.n_nodes, wl.M, wl.m
+    seeds = np.arange(min(n_seeds_sample, N), dtype=np.int32)
+    t0 = time.perf_counter()
+    w = oracle.sample_walks(rp, ci, seeds, M, m, wl.rng_seed)
+    t1 = time.perf_counter()
+    sample_off, _, _ = oracle.build_rpe(w)
+    t2 = time.perf_counter()
+    # the join leg needs the RPE blocks of its queries' nodes; building them is not timed
+    sub_q = queries[:n_query_sample]
+    nodes, local = np.unique(sub_q, return_inverse=True)
+    table = oracle.build_rpe(oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m,
+                                                 wl.rng_seed))
+    local = local.reshape(sub_q.shape).astype(np.int32)
+    t3 = time.perf_counter()
+    _, jids, _ = oracle.join_queries(*table, local)
+    t4 = time.perf_counter()
+    per_seed = (t2 - t0) / seeds.size
+    per_query = (t4 - t3) / sub_q.shape[0]
+    full = per_seed * N + per_query * wl.n_queries      # scaled to the whole workload
+    return {
+        "value": N * M * m / full, "unit": "walk-steps/s", "cores": 1, "kind": "oracle",
+        "sample": (f"seeds 0..{seeds.size - 1} for walks+RPE ({t2 - t0:.1f} s: walks "
+                   f"{t1 - t0:.1f} s, RPE {t2 - t1:.1f} s), first {sub_q.shape[0]} queries for "
+                   f"the join ({t4 - t3:.1f} s); per-seed and per-query times scaled to the "
+                   "whole workload"),
+        "walk_steps_per_s": seeds.size * M * m / (t1 - t0),
+        "rpe_rows_per_s": float(sample_off[-1]) / (t2 - t1),
+        "joined_rows_per_s": jids.size / (t4 - t3),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cl2900k")
+    ap.add_argument("--cpu-seeds", type=int, default=1 << 17)
+    ap.add_argument("--cpu-queries", type=int, default=1 << 14)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build is the one-GPU hot path; --gpus must be 1 "
+            "(seeds and queries shard with no change to the kernels, but no multi-GPU run "
+            "is part of this benchmark)")
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2202_13538_amd import binding, synth
+
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 2
+
+    wl = synth.WORKLOADS[args.workload]
+    N, M, m, k, Q = wl.n_nodes, wl.M, wl.m, wl.k, wl.n_queries
+    L = m + 1
+    t0 = time.time()
+    rp, ci = synth.make_graph(wl)
+    queries = synth.make_queries(wl, rp, ci)
+    log(f"[bench] {wl.name}: N={N} E2={ci.size} M={M} m={m} queries={Q}x{k} "
+        f"(generated in {time.time() - t0:.1f} s)")
+
+    torch.cuda.set_device(0)
+    ctx = binding.Context(0)
+    d_rp, d_ci = torch.from_numpy(rp).cuda(), torch.from_numpy(ci).cuda()
+    d_q = torch.from_numpy(queries).cuda()
+    d_seeds = torch.arange(N, dtype=torch.int32, device="cuda")
+    walks = torch.empty((N, M, L), dtype=torch.int32, device="cuda")
+    cap_r = binding.rpe_rows_bound(N, M, m)
+    rpe_off = torch.empty(N + 1, dtype=torch.int64, device="cuda")
+    rpe_ids = torch.empty(cap_r, dtype=torch.int32, device="cuda")
+    rpe_cnt = torch.empty((cap_r, L), dtype=torch.uint16, device="cuda")
+    join_off = torch.empty(Q + 1, dtype=torch.int64, device="cuda")
+    max_set = 1 + M * m
+
+    # sizing pass (untimed): the join's row total fixes its output allocation
+    binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks)
+    rc, R = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt)
+    assert rc == binding.OK, rc
+    rc, J = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, 0, join_off,
+                                     None, None)
+    assert rc == binding.OK, rc
+    join_ids = torch.empty(J, dtype=torch.int32, device="cuda")
+    join_cnt = torch.empty((J, k, L), dtype=torch.uint16, device="cuda")
+    in_rows = int((rpe_off[1:] - rpe_off[:-1])[d_q.long()].sum())
+    log(f"[bench] R={R} RPE rows, J={J} joined rows, {in_rows} table rows read by the join")
+
+    def one_step():
+        binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks)
+        rc1, r = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt)
+        rc2, j = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, J,
+                                          join_off, join_ids, join_cnt)
+        assert rc1 == binding.OK and rc2 == binding.OK and r == R and j == J
+
+    for _ in range(args.warmup):
+        one_step()
+    assert ctx.check() == 0
+
+    ctx.profile(True)            # HIP events around every kernel launch, on the ctx's stream
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    prof = ctx.profile_read()
+    ctx.profile(False)
+    assert ctx.check() == 0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    kern = {name: (tot / n if n else 0.0) for name, (tot, n) in prof.items()}   # avg ms / launch
+    per_step = {name: tot / args.steps for name, (tot, n) in prof.items()}       # ms / step
+    stage_ms = {
+        "walk": per_step.get("walk", 0.0),
+        "rpe": per_step.get("rpe_count", 0.0) + per_step.get("rpe_fill", 0.0),
+        "join": per_step.get("join_count", 0.0) + per_step.get("join_fill", 0.0),
+    }
+    alg = algorithmic_bytes(N, M, m, k, R, J, in_rows, Q)
+    pipeline_bytes = sum(alg.values())
+    traffic = read_traffic(wl.name)
+
+    # roofline of the dominant kernel (largest average launch duration)
+    dom = max(kern, key=lambda n: kern[n])
+    dom_stage = dom.split("_")[0]
+    dom_gbs = alg[dom_stage] / (kern[dom] * 1e-3) / 1e9 if kern[dom] > 0 else 0.0
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+        "traffic": traffic.get(dom),
+        "avg_launch_ms": round(kern[dom], 4),
+        "algorithmic_bytes_per_launch": alg[dom_stage],
+    }
+
+    out = {
+        "metric": METRIC,
+        "value": N * M * m / (ms_per_step * 1e-3),
+        "unit": "walk-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": wl.name, "graph": wl.graph, "n_nodes": N, "n_edges": wl.n_edges,
+                   "M": M, "m": m, "n_queries": Q, "k": k, "rpe_rows": R, "joined_rows": J},
+        "walk_steps_per_s": N * M * m / (stage_ms["walk"] * 1e-3) if stage_ms["walk"] else None,
+        "rpe_rows_per_s": R / (stage_ms["rpe"] * 1e-3) if stage_ms["rpe"] else None,
+        "joined_rows_per_s": J / (stage_ms["join"] * 1e-3) if stage_ms["join"] else None,
+        "stage_ms": {s: round(v, 4) for s, v in stage_ms.items()},
+        "kernel_avg_ms": {n: round(v, 4) for n, v in kern.items()},
+        "stage_hbm_frac": {s: round(alg[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                           for s in stage_ms if stage_ms[s] > 0},
+        "pipeline_algorithmic_bytes": pipeline_bytes,
+        "pipeline_hbm_frac": round(pipeline_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": roofline,
+    }
+    if not args.no_cpu:
+        t0 = time.time()
+        out["cpu_baseline"] = cpu_baseline(wl, rp, ci, queries, args.cpu_seeds, args.cpu_queries)
+        log(f"[bench] cpu_baseline took {time.time() - t0:.1f} s")
+    ctx.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -76,6 +76,15 @@ extern "C" {
 #define SUREL_MAX_SET     2048        /* join: rows per block of the RPE table               */
 #define SUREL_MAX_TUPLE   3           /* join: k                                             */
 
+/* kernel groups for surel_profile_read */
+#define SUREL_K_WALK        0   /* walk kernel                                   */
+#define SUREL_K_RPE_COUNT   1   /* RPE builder, counting launch                  */
+#define SUREL_K_RPE_FILL    2   /* RPE builder, writing launch                   */
+#define SUREL_K_JOIN_COUNT  3   /* join, counting launch                         */
+#define SUREL_K_JOIN_FILL   4   /* join, writing launch                          */
+#define SUREL_K_SCAN        5   /* the offset scans (three small launches each)  */
+#define SUREL_K_COUNT       6
+
 typedef struct surel_ctx surel_ctx;
 
 /* Create a context for `device` whose work runs on `hip_stream` (a hipStream_t passed as
@@ -147,6 +156,17 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                        int32_t k, int64_t cap_rows, int64_t* d_join_off,
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel group the context launches
+ * is bracketed by two HIP events on the context's stream (a few microseconds of host work
+ * per launch).  surel_profile_enable(ctx, 1) clears the totals and starts collecting,
+ * (ctx, 0) stops; both wait for the stream.  surel_profile_read waits for the stream and
+ * returns, for one SUREL_K_* group, the summed device time in milliseconds and the number of
+ * bracketed launches since collecting started.
+ * Errors: SUREL_E_CTX, SUREL_E_RANGE (kernel), SUREL_E_NULL (h_total_ms, h_launches),
+ * SUREL_E_HIP. */
+int surel_profile_enable(surel_ctx* ctx, int on);
+int surel_profile_read(surel_ctx* ctx, int kernel, double* h_total_ms, int64_t* h_launches);
 
 /* Wait for the context's stream and read the device error word.  *h_flags (may be NULL)
  * receives the SUREL_DEV_* bits; the word is then cleared.  Returns SUREL_OK if it was

@@ -20,6 +20,10 @@ DEV_SET_TOO_LARGE, DEV_CAPACITY, DEV_BAD_TABLE = 0x10, 0x20, 0x40
 MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
 
+K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_COUNT = range(7)
+KERNEL_NAMES = {K_WALK: "walk", K_RPE_COUNT: "rpe_count", K_RPE_FILL: "rpe_fill",
+                K_JOIN_COUNT: "join_count", K_JOIN_FILL: "join_fill", K_SCAN: "scan"}
+
 _vp = ctypes.c_void_p
 _i32, _i64, _u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
 
@@ -36,6 +40,9 @@ SIGNATURES = {
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
+    "surel_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "surel_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(_i64)]),
 }
 
 _lib = None
@@ -105,6 +112,23 @@ class Context:
         if rc not in (OK, E_DEVICE):
             raise SurelError(rc, "surel_check")
         return flags.value
+
+    def profile(self, on: bool) -> None:
+        rc = load().surel_profile_enable(self._h, 1 if on else 0)
+        if rc != OK:
+            raise SurelError(rc, "surel_profile_enable")
+
+    def profile_read(self) -> dict:
+        """{kernel name: (total ms, launches)} since profiling was switched on."""
+        out = {}
+        for kid, name in KERNEL_NAMES.items():
+            ms = ctypes.c_double(0.0)
+            n = _i64(0)
+            rc = load().surel_profile_read(self._h, kid, ctypes.byref(ms), ctypes.byref(n))
+            if rc != OK:
+                raise SurelError(rc, "surel_profile_read")
+            out[name] = (ms.value, n.value)
+        return out
 
     def close(self):
         if self._h:

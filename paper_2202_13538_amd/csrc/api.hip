@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <new>
+#include <vector>
 
 #include "kernels.h"
 
@@ -16,6 +17,16 @@ struct surel_ctx {
     int64_t* h_pinned = nullptr;  // 2 x int64 of pinned host memory for small read-backs
     void* d_ws = nullptr;         // grow-only workspace
     size_t ws_bytes = 0;
+    // optional per-kernel timing (surel_profile_*)
+    struct Span {
+        int kernel;
+        hipEvent_t start, stop;
+    };
+    bool profiling = false;
+    std::vector<Span> spans;          // recorded, not yet read
+    std::vector<hipEvent_t> free_events;
+    double prof_ms[SUREL_K_COUNT] = {};
+    int64_t prof_launches[SUREL_K_COUNT] = {};
 };
 
 namespace {
@@ -34,6 +45,70 @@ struct DeviceGuard {
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Brackets the launches made during its lifetime with two events on the context's stream
+// when profiling is on; does nothing otherwise.
+class KernelSpan {
+  public:
+    KernelSpan(surel_ctx* ctx, int kernel) : ctx_(ctx) {
+        if (!ctx->profiling) return;
+        span_.kernel = kernel;
+        span_.start = take();
+        span_.stop = take();
+        if (!span_.start || !span_.stop) {
+            give_back();
+            return;
+        }
+        active_ = hipEventRecord(span_.start, ctx->stream) == hipSuccess;
+        if (!active_) give_back();
+    }
+    ~KernelSpan() {
+        if (!active_) return;
+        if (hipEventRecord(span_.stop, ctx_->stream) == hipSuccess) {
+            ctx_->spans.push_back(span_);
+        } else {
+            give_back();
+        }
+    }
+    KernelSpan(const KernelSpan&) = delete;
+    KernelSpan& operator=(const KernelSpan&) = delete;
+
+  private:
+    hipEvent_t take() {
+        if (!ctx_->free_events.empty()) {
+            hipEvent_t e = ctx_->free_events.back();
+            ctx_->free_events.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+    void give_back() {
+        if (span_.start) ctx_->free_events.push_back(span_.start);
+        if (span_.stop) ctx_->free_events.push_back(span_.stop);
+        span_.start = span_.stop = nullptr;
+    }
+    surel_ctx* ctx_;
+    surel_ctx::Span span_{0, nullptr, nullptr};
+    bool active_ = false;
+};
+
+// Wait for the stream and fold every recorded span into the per-kernel totals.
+int drain_spans(surel_ctx* ctx) {
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    for (const surel_ctx::Span& sp : ctx->spans) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.start, sp.stop) == hipSuccess) {
+            ctx->prof_ms[sp.kernel] += (double)ms;
+            ctx->prof_launches[sp.kernel] += 1;
+        }
+        ctx->free_events.push_back(sp.start);
+        ctx->free_events.push_back(sp.stop);
+    }
+    ctx->spans.clear();
+    return SUREL_OK;
+}
 
 // Workspace: int32 counts[n] followed by the int64 scan partials.
 int ensure_workspace(surel_ctx* ctx, int64_t n, int32_t** counts, int64_t** partials) {
@@ -112,6 +187,11 @@ void surel_destroy(surel_ctx* ctx) {
     if (!ctx) return;
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    for (const surel_ctx::Span& sp : ctx->spans) {
+        (void)hipEventDestroy(sp.start);
+        (void)hipEventDestroy(sp.stop);
+    }
+    for (hipEvent_t e : ctx->free_events) (void)hipEventDestroy(e);
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
     if (ctx->d_err) (void)hipFree(ctx->d_err);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
@@ -148,6 +228,7 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     if (n_seeds == 0) return SUREL_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
+    KernelSpan span(ctx, SUREL_K_WALK);
     hipError_t rc = surel::launch_walks(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
                                         d_seeds, n_seeds, M, m, rng_seed, d_walks, ctx->d_err);
     return rc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
@@ -168,14 +249,21 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
     int32_t* counts = nullptr;
     int64_t* partials = nullptr;
     if (int rc = ensure_workspace(ctx, n_seeds, &counts, &partials)) return rc;
-    hipError_t hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m,
-                                       n_nodes, counts, nullptr, 0, nullptr, nullptr, ctx->d_err);
+    hipError_t hrc;
+    {
+        KernelSpan span(ctx, SUREL_K_RPE_COUNT);
+        hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m, n_nodes,
+                                counts, nullptr, 0, nullptr, nullptr, ctx->d_err);
+    }
     if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
     if (hrc != hipSuccess) return SUREL_E_HIP;
-    if (surel::launch_exclusive_scan(ctx->stream, counts, n_seeds, d_rpe_off, partials) !=
-        hipSuccess)
-        return SUREL_E_HIP;
+    {
+        KernelSpan span(ctx, SUREL_K_SCAN);
+        hrc = surel::launch_exclusive_scan(ctx->stream, counts, n_seeds, d_rpe_off, partials);
+    }
+    if (hrc != hipSuccess) return SUREL_E_HIP;
     if (d_rpe_ids) {
+        KernelSpan span(ctx, SUREL_K_RPE_FILL);
         hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m, n_nodes,
                                 nullptr, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt, ctx->d_err);
         if (hrc != hipSuccess) return SUREL_E_HIP;
@@ -208,15 +296,22 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
     int32_t* counts = nullptr;
     int64_t* partials = nullptr;
     if (int rc = ensure_workspace(ctx, n_queries, &counts, &partials)) return rc;
-    hipError_t hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids,
-                                        d_rpe_cnt, n_blocks, m, max_set, d_queries, n_queries, k,
-                                        counts, nullptr, 0, nullptr, nullptr, ctx->d_err);
+    hipError_t hrc;
+    {
+        KernelSpan span(ctx, SUREL_K_JOIN_COUNT);
+        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
+                                 n_blocks, m, max_set, d_queries, n_queries, k, counts, nullptr, 0,
+                                 nullptr, nullptr, ctx->d_err);
+    }
     if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
     if (hrc != hipSuccess) return SUREL_E_HIP;
-    if (surel::launch_exclusive_scan(ctx->stream, counts, n_queries, d_join_off, partials) !=
-        hipSuccess)
-        return SUREL_E_HIP;
+    {
+        KernelSpan span(ctx, SUREL_K_SCAN);
+        hrc = surel::launch_exclusive_scan(ctx->stream, counts, n_queries, d_join_off, partials);
+    }
+    if (hrc != hipSuccess) return SUREL_E_HIP;
     if (d_join_ids) {
+        KernelSpan span(ctx, SUREL_K_JOIN_FILL);
         hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
                                  n_blocks, m, max_set, d_queries, n_queries, k, nullptr,
                                  d_join_off, cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
@@ -226,6 +321,33 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
         if (int rc = read_total(ctx, d_join_off, n_queries, h_rows)) return rc;
         if (d_join_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
     }
+    return SUREL_OK;
+}
+
+int surel_profile_enable(surel_ctx* ctx, int on) {
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (int rc = drain_spans(ctx)) return rc;
+    if (on) {
+        for (int i = 0; i < SUREL_K_COUNT; ++i) {
+            ctx->prof_ms[i] = 0.0;
+            ctx->prof_launches[i] = 0;
+        }
+    }
+    ctx->profiling = on != 0;
+    return SUREL_OK;
+}
+
+int surel_profile_read(surel_ctx* ctx, int kernel, double* h_total_ms, int64_t* h_launches) {
+    if (!ctx) return SUREL_E_CTX;
+    if (kernel < 0 || kernel >= SUREL_K_COUNT) return SUREL_E_RANGE;
+    if (!h_total_ms || !h_launches) return SUREL_E_NULL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (int rc = drain_spans(ctx)) return rc;
+    *h_total_ms = ctx->prof_ms[kernel];
+    *h_launches = ctx->prof_launches[kernel];
     return SUREL_OK;
 }
 

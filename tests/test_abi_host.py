@@ -38,6 +38,9 @@ def test_library_exports_every_declared_symbol(lib):
 def test_header_constants_match_binding():
     text = open(HEADER).read()
     defs = dict(re.findall(r"#define\s+(SUREL_[A-Z_]+)\s+\(?(-?[0-9a-fx]+)u?\)?", text))
+    for kid, name in binding.KERNEL_NAMES.items():
+        assert int(defs["SUREL_K_" + name.upper()]) == kid
+    assert int(defs["SUREL_K_COUNT"]) == binding.K_COUNT == len(binding.KERNEL_NAMES)
     val = {k: int(v, 0) for k, v in defs.items()}
     assert val["SUREL_OK"] == binding.OK
     assert val["SUREL_E_NULL"] == binding.E_NULL
@@ -171,6 +174,8 @@ def test_join_queries_argument_checks(lib, kw, want):
 
 def test_check_and_destroy_tolerate_null(lib):
     assert lib.surel_check(NULL, NULL) == binding.E_CTX
+    assert lib.surel_profile_enable(NULL, 1) == binding.E_CTX
+    assert lib.surel_profile_read(NULL, 0, None, None) == binding.E_CTX
     lib.surel_destroy(NULL)
 
 
