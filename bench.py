@@ -137,11 +137,14 @@ def main() -> int:
     rpe_ids = torch.empty(cap_r, dtype=torch.int32, device="cuda")
     rpe_cnt = torch.empty((cap_r, L), dtype=torch.uint16, device="cuda")
     join_off = torch.empty(Q + 1, dtype=torch.int64, device="cuda")
+    set_sizes = torch.empty(N, dtype=torch.int32, device="cuda")
     max_set = 1 + M * m
 
     # sizing pass (untimed): the join's row total fixes its output allocation
-    binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks)
-    rc, R = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt)
+    binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
+                         set_sizes=set_sizes)
+    rc, R = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
+                                  set_sizes=set_sizes)
     assert rc == binding.OK, rc
     rc, J = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, 0, join_off,
                                      None, None)
@@ -152,8 +155,10 @@ def main() -> int:
     log(f"[bench] R={R} RPE rows, J={J} joined rows, {in_rows} table rows read by the join")
 
     def one_step():
-        binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks)
-        rc1, r = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt)
+        binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
+                             set_sizes=set_sizes)
+        rc1, r = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
+                                       set_sizes=set_sizes)
         rc2, j = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, J,
                                           join_off, join_ids, join_cnt)
         assert rc1 == binding.OK and rc2 == binding.OK and r == R and j == J

@@ -18,8 +18,8 @@
  *   - All work is enqueued on the context's stream.  A call returns without waiting unless
  *     a non-NULL h_rows is passed (then it waits for its own work and reports the row
  *     total).  Calls on one context must not overlap from several host threads.
- *   - The context owns a grow-only device workspace (per-seed / per-query counts and scan
- *     partials) and a 4-byte device error word; nothing else is allocated.
+ *   - The context owns a grow-only device workspace (per-seed / per-query row counts and
+ *     scan partials) and a device error word; nothing else is allocated.
  *   - Return value: SUREL_OK (0) or a negative SUREL_E_* code.  Arguments are validated on
  *     the host before anything is enqueued, so a call that returns SUREL_E_NULL or
  *     SUREL_E_RANGE has launched nothing.  Problems only visible on the device (a seed or
@@ -67,6 +67,8 @@ extern "C" {
 #define SUREL_DEV_SET_TOO_LARGE 0x10u  /* a block of the RPE table has more than max_set rows */
 #define SUREL_DEV_CAPACITY      0x20u  /* rows beyond cap_rows were not written             */
 #define SUREL_DEV_BAD_TABLE     0x40u  /* d_rpe_off is not non-decreasing at a queried block */
+#define SUREL_DEV_BAD_SIZES     0x80u  /* a seed's d_set_sizes entry is not its number of
+                                          distinct nodes; that seed's rows are not written   */
 
 /* limits */
 #define SUREL_MAX_NODES   268435455   /* 2^28 - 1: node id and step share one 32-bit sort key */
@@ -77,12 +79,12 @@ extern "C" {
 #define SUREL_MAX_TUPLE   3           /* join: k                                             */
 
 /* kernel groups for surel_profile_read */
-#define SUREL_K_WALK        0   /* walk kernel                                   */
-#define SUREL_K_RPE_COUNT   1   /* RPE builder, counting launch                  */
-#define SUREL_K_RPE_FILL    2   /* RPE builder, writing launch                   */
-#define SUREL_K_JOIN_COUNT  3   /* join, counting launch                         */
-#define SUREL_K_JOIN_FILL   4   /* join, writing launch                          */
-#define SUREL_K_SCAN        5   /* the offset scans (three small launches each)  */
+#define SUREL_K_WALK        0   /* walk kernel                                        */
+#define SUREL_K_RPE_COUNT   1   /* RPE builder: set-size kernel (when sizes not given) */
+#define SUREL_K_RPE_FILL    2   /* RPE builder: sort-and-write kernel                 */
+#define SUREL_K_JOIN_COUNT  3   /* join: counting launch                              */
+#define SUREL_K_JOIN_FILL   4   /* join: writing launch                               */
+#define SUREL_K_SCAN        5   /* the offset scans (three small launches each)       */
 #define SUREL_K_COUNT       6
 
 typedef struct surel_ctx surel_ctx;
@@ -112,18 +114,24 @@ int64_t surel_rpe_rows_bound(int64_t n_seeds, int32_t M, int32_t m);
  *   d_row_ptr, d_col_idx  CSR (device, read-only); n_edges = number of col_idx entries.
  *   d_seeds               int32[n_seeds] (device, read-only).
  *   d_walks               int32[n_seeds][M][m+1] (device, written).
+ *   d_set_sizes           int32[n_seeds] (device, written) or NULL: |V_u| of every seed, the
+ *                         number of distinct nodes in its walks (Algorithm 1: V_u = set(W_u)).
+ *                         Passing it on to surel_build_rpe saves that call a pass over the
+ *                         walks.  Needs M*(m+1) <= SUREL_MAX_WALK_ENTRIES.
  * Limits: 1 <= n_nodes <= SUREL_MAX_NODES, 0 <= n_edges < 2^31, n_seeds >= 0,
  * 1 <= M <= SUREL_MAX_WALKS, 1 <= m <= SUREL_MAX_STEPS.  n_seeds = 0 is a no-op.
- * Device-detected: BAD_SEED (that seed's walks are filled with -1), BAD_GRAPH (the walker
- * stays in place for that step). */
+ * Device-detected: BAD_SEED (that seed's walks are filled with -1, its set size is 0),
+ * BAD_GRAPH (the walker stays in place for that step). */
 int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
                        int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
                        int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
-                       int32_t* d_walks);
+                       int32_t* d_walks, int32_t* d_set_sizes);
 
 /* Sec. 3.2 "Relative Positional Encoding" / Algorithm 1: for every seed i, V_i = distinct
  * node ids in walks[i] (ascending) and cnt[x][s] = #{w : walks[i][w][s] == x}.
  *   d_walks      int32[n_seeds][M][m+1] (device, read-only), entries in [0, n_nodes).
+ *   d_set_sizes  int32[n_seeds] (device, read-only) or NULL: |V_i| as surel_sample_walks
+ *                reports it for these walks.  NULL makes the call count them itself.
  *   cap_rows     rows that d_rpe_ids / d_rpe_cnt can hold.
  *   d_rpe_off    int64[n_seeds+1] (device, written; always complete, even on overflow).
  *   d_rpe_ids    int32[cap_rows], d_rpe_cnt uint16[cap_rows][m+1] (device, written).  Both
@@ -134,10 +142,11 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
  * Limits: as for surel_sample_walks, and M*(m+1) <= SUREL_MAX_WALK_ENTRIES.
  * Returns SUREL_E_CAPACITY if h_rows is given and the total exceeds cap_rows; rows at or
  * beyond cap_rows are never written (blocks that do not fit entirely are skipped).
- * Device-detected: BAD_WALK (the entry counts as node 0), CAPACITY. */
+ * Device-detected: BAD_WALK (the entry counts as node 0), CAPACITY, BAD_SIZES. */
 int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
-                    int32_t m, int32_t n_nodes, int64_t cap_rows, int64_t* d_rpe_off,
-                    int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows);
+                    int32_t m, int32_t n_nodes, const int32_t* d_set_sizes, int64_t cap_rows,
+                    int64_t* d_rpe_off, int32_t* d_rpe_ids, uint16_t* d_rpe_cnt,
+                    int64_t* h_rows);
 
 /* Sec. 3.4, set-union form: for every query q with tuple (b_1..b_k) of table blocks, the
  * ascending union of the blocks' id lists and, per union node x and j < k, block b_j's count

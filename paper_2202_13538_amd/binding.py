@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libsurel.so")
 
 OK, E_NULL, E_RANGE, E_HIP, E_CAPACITY, E_CTX, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 DEV_BAD_SEED, DEV_BAD_GRAPH, DEV_BAD_WALK, DEV_BAD_QUERY = 0x01, 0x02, 0x04, 0x08
-DEV_SET_TOO_LARGE, DEV_CAPACITY, DEV_BAD_TABLE = 0x10, 0x20, 0x40
+DEV_SET_TOO_LARGE, DEV_CAPACITY, DEV_BAD_TABLE, DEV_BAD_SIZES = 0x10, 0x20, 0x40, 0x80
 MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
 
@@ -34,9 +34,9 @@ SIGNATURES = {
     "surel_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "surel_rpe_rows_bound": (_i64, [_i64, _i32, _i32]),
     "surel_sample_walks": (ctypes.c_int, [_vp, _vp, _vp, _i32, _i64, _vp, _i64, _i32, _i32,
-                                          _u64, _vp]),
-    "surel_build_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _i64, _vp, _vp, _vp,
-                                       ctypes.POINTER(_i64)]),
+                                          _u64, _vp, _vp]),
+    "surel_build_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _vp, _vp,
+                                       _vp, ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
@@ -148,8 +148,10 @@ def rpe_rows_bound(n_seeds: int, M: int, m: int) -> int:
 
 def sample_walks(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
                  seeds: torch.Tensor, M: int, m: int, rng_seed: int = 0,
-                 out: torch.Tensor | None = None) -> torch.Tensor:
-    """walks int32[n_seeds][M][m+1] on the GPU."""
+                 out: torch.Tensor | None = None,
+                 set_sizes: torch.Tensor | None = None) -> torch.Tensor:
+    """walks int32[n_seeds][M][m+1] on the GPU; ``set_sizes`` (int32[n_seeds], optional)
+    receives the number of distinct nodes of every seed's walks."""
     n_nodes = row_ptr.numel() - 1
     n_seeds = seeds.numel()
     if out is None:
@@ -159,7 +161,8 @@ def sample_walks(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
     rc = load().surel_sample_walks(
         ctx.handle, _ptr(row_ptr, torch.int32, "row_ptr"), _ptr(col_idx, torch.int32, "col_idx"),
         n_nodes, col_idx.numel(), _ptr(seeds, torch.int32, "seeds"), n_seeds, M, m,
-        _u64(rng_seed), _ptr(out, torch.int32, "walks"))
+        _u64(rng_seed), _ptr(out, torch.int32, "walks"),
+        _ptr(set_sizes, torch.int32, "set_sizes"))
     if rc != OK:
         raise SurelError(rc, "surel_sample_walks")
     return out
@@ -167,18 +170,21 @@ def sample_walks(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
 
 def build_rpe_raw(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int,
                   rpe_off: torch.Tensor, rpe_ids: torch.Tensor | None,
-                  rpe_cnt: torch.Tensor | None, want_rows: bool = True):
+                  rpe_cnt: torch.Tensor | None, want_rows: bool = True,
+                  set_sizes: torch.Tensor | None = None):
     """One call of surel_build_rpe into caller buffers.  Returns (status, rows or None)."""
     n_seeds, M, L = walks.shape
     rows = _i64(-1)
     rc = load().surel_build_rpe(
-        ctx.handle, _ptr(walks, torch.int32, "walks"), n_seeds, M, L - 1, n_nodes, cap_rows,
+        ctx.handle, _ptr(walks, torch.int32, "walks"), n_seeds, M, L - 1, n_nodes,
+        _ptr(set_sizes, torch.int32, "set_sizes"), cap_rows,
         _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
         _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), ctypes.byref(rows) if want_rows else None)
     return rc, (rows.value if want_rows else None)
 
 
-def build_rpe(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int | None = None):
+def build_rpe(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int | None = None,
+              set_sizes: torch.Tensor | None = None):
     """(rpe_off int64[n_seeds+1], rpe_ids int32[R], rpe_cnt uint16[R][m+1]) on the GPU.
 
     ``cap_rows=None`` sizes the outputs with a counting call first; a number allocates that
@@ -189,13 +195,13 @@ def build_rpe(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int | N
     dev = walks.device
     off = torch.empty(n_seeds + 1, dtype=torch.int64, device=dev)
     if cap_rows is None:
-        rc, rows = build_rpe_raw(ctx, walks, n_nodes, 0, off, None, None)
+        rc, rows = build_rpe_raw(ctx, walks, n_nodes, 0, off, None, None, set_sizes=set_sizes)
         if rc != OK:
             raise SurelError(rc, "surel_build_rpe (count)")
         cap_rows = rows
     ids = torch.empty(cap_rows, dtype=torch.int32, device=dev)
     cnt = torch.empty((cap_rows, L), dtype=torch.uint16, device=dev)
-    rc, rows = build_rpe_raw(ctx, walks, n_nodes, cap_rows, off, ids, cnt)
+    rc, rows = build_rpe_raw(ctx, walks, n_nodes, cap_rows, off, ids, cnt, set_sizes=set_sizes)
     if rc != OK:
         raise SurelError(rc, "surel_build_rpe")
     return off, ids[:rows], cnt[:rows]

@@ -219,9 +219,10 @@ int64_t surel_rpe_rows_bound(int64_t n_seeds, int32_t M, int32_t m) {
 int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
                        int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
                        int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
-                       int32_t* d_walks) {
+                       int32_t* d_walks, int32_t* d_set_sizes) {
     if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
     if (n_edges < 0 || n_edges > 0x7FFFFFFFll) return SUREL_E_RANGE;
+    if (d_set_sizes && (int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
     if (!d_row_ptr || (n_edges > 0 && !d_col_idx)) return SUREL_E_NULL;
     if (n_seeds > 0 && (!d_seeds || !d_walks)) return SUREL_E_NULL;
     if (!ctx) return SUREL_E_CTX;
@@ -230,12 +231,14 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     if (!guard.ok) return SUREL_E_HIP;
     KernelSpan span(ctx, SUREL_K_WALK);
     hipError_t rc = surel::launch_walks(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
-                                        d_seeds, n_seeds, M, m, rng_seed, d_walks, ctx->d_err);
+                                        d_seeds, n_seeds, M, m, rng_seed, d_walks, d_set_sizes,
+                                        ctx->d_err);
     return rc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
 }
 
 int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
-                    int32_t m, int32_t n_nodes, int64_t cap_rows, int64_t* d_rpe_off,
+                    int32_t m, int32_t n_nodes, const int32_t* d_set_sizes, int64_t cap_rows,
+                    int64_t* d_rpe_off,
                     int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows) {
     if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
     if ((int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
@@ -249,23 +252,26 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
     int32_t* counts = nullptr;
     int64_t* partials = nullptr;
     if (int rc = ensure_workspace(ctx, n_seeds, &counts, &partials)) return rc;
-    hipError_t hrc;
-    {
+    hipError_t hrc = hipSuccess;
+    const int32_t* sizes = d_set_sizes;
+    if (!sizes) {
         KernelSpan span(ctx, SUREL_K_RPE_COUNT);
-        hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m, n_nodes,
-                                counts, nullptr, 0, nullptr, nullptr, ctx->d_err);
+        hrc = surel::launch_rpe_count(ctx->stream, d_walks, n_seeds, M, m, n_nodes, counts,
+                                      ctx->d_err);
+        sizes = counts;
     }
-    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
     if (hrc != hipSuccess) return SUREL_E_HIP;
     {
         KernelSpan span(ctx, SUREL_K_SCAN);
-        hrc = surel::launch_exclusive_scan(ctx->stream, counts, n_seeds, d_rpe_off, partials);
+        hrc = surel::launch_exclusive_scan(ctx->stream, sizes, n_seeds, d_rpe_off, partials);
     }
     if (hrc != hipSuccess) return SUREL_E_HIP;
     if (d_rpe_ids) {
         KernelSpan span(ctx, SUREL_K_RPE_FILL);
-        hrc = surel::launch_rpe(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m, n_nodes,
-                                nullptr, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt, ctx->d_err);
+        hrc = surel::launch_rpe_fill(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m,
+                                     n_nodes, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt,
+                                     ctx->d_err);
+        if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
         if (hrc != hipSuccess) return SUREL_E_HIP;
     }
     if (h_rows) {
@@ -313,8 +319,8 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
     if (d_join_ids) {
         KernelSpan span(ctx, SUREL_K_JOIN_FILL);
         hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
-                                 n_blocks, m, max_set, d_queries, n_queries, k, nullptr,
-                                 d_join_off, cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
+                                 n_blocks, m, max_set, d_queries, n_queries, k, nullptr, d_join_off,
+                                 cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
         if (hrc != hipSuccess) return SUREL_E_HIP;
     }
     if (h_rows) {

@@ -16,6 +16,7 @@ constexpr uint32_t kDevBadQuery = 0x08u;
 constexpr uint32_t kDevSetTooLarge = 0x10u;
 constexpr uint32_t kDevCapacity = 0x20u;
 constexpr uint32_t kDevBadTable = 0x40u;
+constexpr uint32_t kDevBadSizes = 0x80u;
 
 __device__ __forceinline__ int lane_id() {
     return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
@@ -33,6 +34,31 @@ __device__ __forceinline__ void wave_sync() {
 __device__ __forceinline__ void raise_error(uint32_t* err, bool cond, uint32_t bit) {
     if (__ballot(cond) != 0ull) {
         if (lane_id() == 0) atomicOr(err, bit);
+    }
+}
+
+// Value of `x` held by lane (lane ^ MASK), MASK a compile-time constant in 1..63.  Uses the
+// cheapest exchange the pattern allows: DPP quad permutes and row mirrors (folded into the
+// consuming VALU instruction), the LDS crossbar's swizzle for other masks below 32, and a
+// general ds_bpermute otherwise.  None of them touches LDS memory.
+template <int MASK>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane) {
+    static_assert(MASK >= 1 && MASK < kWave, "mask out of range");
+    if constexpr (MASK == 1) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+    } else if constexpr (MASK == 2) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+    } else if constexpr (MASK == 3) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x1B, 0xF, 0xF, false);  // quad_perm [3,2,1,0]
+    } else if constexpr (MASK == 7) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    } else if constexpr (MASK == 15) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false);  // row_mirror
+    } else if constexpr (MASK < 32) {
+        // swizzle, bit mode: new lane = ((lane & and) | or) ^ xor inside each group of 32
+        return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, (MASK << 10) | 0x1F);
+    } else {
+        return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)x);
     }
 }
 

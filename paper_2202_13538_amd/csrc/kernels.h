@@ -6,19 +6,26 @@
 
 namespace surel {
 
-// walk.hip
+// walk.hip.  set_sizes (optional): int32[n_seeds], receives the number of distinct nodes of
+// every seed's walks; needs 1 + M*m <= 2048.
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
-                        int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks, uint32_t* err);
+                        int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
+                        int32_t* set_sizes, uint32_t* err);
 
-// rpe.hip.  counts != nullptr: write per-seed row counts.  ids != nullptr: write the rows of
-// every seed at rpe_off[i] (seeds whose block would pass cap_rows are skipped).
-hipError_t launch_rpe(hipStream_t stream, int max_lds_bytes, const int32_t* walks,
-                      int64_t n_seeds, int32_t M, int32_t m, int32_t n_nodes, int32_t* counts,
-                      const int64_t* rpe_off, int64_t cap_rows, int32_t* ids, uint16_t* cnt,
-                      uint32_t* err);
+// rpe.hip.  launch_rpe_count: set_sizes[i] = distinct nodes in walks[i].  launch_rpe_fill:
+// writes the rows of every seed at rpe_off[i] (seeds whose block would pass cap_rows, or whose
+// row count differs from rpe_off[i+1]-rpe_off[i], are skipped and flagged).
+// hipErrorInvalidValue = the shape does not fit the device's LDS.
+hipError_t launch_rpe_count(hipStream_t stream, const int32_t* walks, int64_t n_seeds, int32_t M,
+                            int32_t m, int32_t n_nodes, int32_t* set_sizes, uint32_t* err);
+hipError_t launch_rpe_fill(hipStream_t stream, int max_lds_bytes, const int32_t* walks,
+                           int64_t n_seeds, int32_t M, int32_t m, int32_t n_nodes,
+                           const int64_t* rpe_off, int64_t cap_rows, int32_t* ids, uint16_t* cnt,
+                           uint32_t* err);
 
-// join.hip.  Same two modes as launch_rpe.
+// join.hip.  counts != nullptr: counting launch (counts[q] = union rows of query q);
+// counts == nullptr: writing launch at join_off[q].
 hipError_t launch_join(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
                        const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                        int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,

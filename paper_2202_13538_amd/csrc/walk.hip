@@ -5,33 +5,53 @@
 // the global stores are full-width instead of lane-strided.  Walk rows are written with
 // non-temporal stores: they are not read again by this kernel and should not push the
 // graph out of the caches that serve the neighbour gathers.
+//
+// Optionally the kernel also reports |V_u|, the number of distinct nodes of each seed's
+// walks (Algorithm 1: V_u = set(W_u)), through an LDS hash set fed while the walkers move.
+// The kernel waits on memory nearly all the time, so this costs little, and it saves the
+// RPE builder a counting pass over the walks.
 #include "device_util.h"
+#include "distinct.h"
 #include "kernels.h"
 
 namespace surel {
 
 constexpr int kWalkWavesPerBlock = 4;
 
+template <bool kCount>
 __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int32_t n_nodes,
     int64_t n_edges, const int32_t* __restrict__ seeds, int64_t n_seeds, int32_t M, int32_t m,
-    uint32_t key0, uint32_t key1, int32_t* __restrict__ walks, uint32_t* __restrict__ err) {
+    uint32_t key0, uint32_t key1, int32_t* __restrict__ walks, int32_t* __restrict__ set_sizes,
+    int32_t slots, uint32_t* __restrict__ err) {
     extern __shared__ int32_t lds[];
     const int lane = lane_id();
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t i = (int64_t)blockIdx.x * kWalkWavesPerBlock + wave;
     if (i >= n_seeds) return;  // whole waves leave; no block-wide barrier is used below
 
     const int L = m + 1;
-    int32_t* stage = lds + wave * kWave * L;
+    const int per_wave = kWave * L + (kCount ? slots : 0);
+    int32_t* stage = lds + wave * per_wave;
+    uint32_t* table = reinterpret_cast<uint32_t*>(stage + kWave * L);
     int32_t* out_seed = walks + i * (int64_t)M * L;
 
     const int32_t u = __builtin_amdgcn_readfirstlane(seeds[i]);
     if (u < 0 || u >= n_nodes) {
-        if (lane == 0) atomicOr(err, kDevBadSeed);
+        if (lane == 0) {
+            atomicOr(err, kDevBadSeed);
+            if (kCount) set_sizes[i] = 0;
+        }
         const int total = M * L;
         for (int t = lane; t < total; t += kWave) __builtin_nontemporal_store(-1, out_seed + t);
         return;
+    }
+
+    int n_distinct = 0;
+    if (kCount) {
+        distinct_clear(table, slots, lane);
+        wave_sync();
+        n_distinct = distinct_insert(table, slots, (uint32_t)u, lane == 0);
     }
 
     bool bad_graph = false;
@@ -63,6 +83,7 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
                         }
                     }
                     stage[lane * L + s] = cur;
+                    if (kCount) n_distinct += distinct_insert(table, slots, (uint32_t)cur, active);
                 }
             }
         }
@@ -72,19 +93,37 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
         for (int t = lane; t < total; t += kWave) __builtin_nontemporal_store(stage[t], out + t);
         wave_sync();
     }
+    if (kCount && lane == 0) set_sizes[i] = n_distinct;
     raise_error(err, bad_graph, kDevBadGraph);
 }
 
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
-                        int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks, uint32_t* err) {
+                        int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
+                        int32_t* set_sizes, uint32_t* err) {
     if (n_seeds == 0) return hipSuccess;
     const int64_t blocks = (n_seeds + kWalkWavesPerBlock - 1) / kWalkWavesPerBlock;
-    const size_t lds_bytes = (size_t)kWalkWavesPerBlock * kWave * (m + 1) * sizeof(int32_t);
-    hipLaunchKernelGGL(walk_kernel, dim3((unsigned)blocks), dim3(kWalkWavesPerBlock * kWave),
-                       lds_bytes, stream, row_ptr, col_idx, n_nodes, n_edges, seeds, n_seeds, M,
-                       m, (uint32_t)(rng_seed & 0xFFFFFFFFull), (uint32_t)(rng_seed >> 32), walks,
-                       err);
+    const uint32_t key0 = (uint32_t)(rng_seed & 0xFFFFFFFFull);
+    const uint32_t key1 = (uint32_t)(rng_seed >> 32);
+    const dim3 grid((unsigned)blocks), block(kWalkWavesPerBlock * kWave);
+    if (set_sizes != nullptr) {
+        const int slots = distinct_slots(1 + M * m);
+        const size_t lds_bytes = (size_t)kWalkWavesPerBlock * (kWave * (m + 1) + slots) * 4;
+        if (lds_bytes > 48 * 1024) {
+            hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(walk_kernel<true>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                (int)lds_bytes);
+            if (rc != hipSuccess) return rc;
+        }
+        hipLaunchKernelGGL(walk_kernel<true>, grid, block, lds_bytes, stream, row_ptr, col_idx,
+                           n_nodes, n_edges, seeds, n_seeds, M, m, key0, key1, walks, set_sizes,
+                           slots, err);
+    } else {
+        const size_t lds_bytes = (size_t)kWalkWavesPerBlock * kWave * (m + 1) * 4;
+        hipLaunchKernelGGL(walk_kernel<false>, grid, block, lds_bytes, stream, row_ptr, col_idx,
+                           n_nodes, n_edges, seeds, n_seeds, M, m, key0, key1, walks, set_sizes, 0,
+                           err);
+    }
     return hipGetLastError();
 }
 

@@ -56,6 +56,7 @@ def test_header_constants_match_binding():
     assert val["SUREL_DEV_SET_TOO_LARGE"] == binding.DEV_SET_TOO_LARGE
     assert val["SUREL_DEV_CAPACITY"] == binding.DEV_CAPACITY
     assert val["SUREL_DEV_BAD_TABLE"] == binding.DEV_BAD_TABLE
+    assert val["SUREL_DEV_BAD_SIZES"] == binding.DEV_BAD_SIZES
     assert val["SUREL_MAX_NODES"] == binding.MAX_NODES
     assert val["SUREL_MAX_STEPS"] == binding.MAX_STEPS
     assert val["SUREL_MAX_WALKS"] == binding.MAX_WALKS
@@ -81,10 +82,10 @@ NULL = None
 
 def walks_args(**kw):
     a = dict(ctx=NULL, row_ptr=P, col_idx=P, n_nodes=100, n_edges=500, seeds=P, n_seeds=10,
-             M=50, m=4, rng_seed=0, walks=P)
+             M=50, m=4, rng_seed=0, walks=P, sizes=NULL)
     a.update(kw)
     return [a[k] for k in ("ctx", "row_ptr", "col_idx", "n_nodes", "n_edges", "seeds", "n_seeds",
-                           "M", "m", "rng_seed", "walks")]
+                           "M", "m", "rng_seed", "walks", "sizes")]
 
 
 @pytest.mark.parametrize("kw,want", [
@@ -104,17 +105,20 @@ def walks_args(**kw):
     (dict(seeds=NULL), binding.E_NULL),
     (dict(walks=NULL), binding.E_NULL),
     (dict(seeds=NULL, walks=NULL, n_seeds=0), binding.E_CTX),
+    (dict(sizes=P), binding.E_CTX),                   # set sizes requested, shape fits
+    (dict(sizes=P, M=410, m=4), binding.E_RANGE),     # set sizes need M*(m+1) <= 2048
+    (dict(M=410, m=4), binding.E_CTX),                # without them any M works
 ])
 def test_sample_walks_argument_checks(lib, kw, want):
     assert lib.surel_sample_walks(*walks_args(**kw)) == want
 
 
 def rpe_args(**kw):
-    a = dict(ctx=NULL, walks=P, n_seeds=10, M=50, m=4, n_nodes=100, cap_rows=1000, off=P, ids=P,
-             cnt=P, h_rows=NULL)
+    a = dict(ctx=NULL, walks=P, n_seeds=10, M=50, m=4, n_nodes=100, sizes=NULL, cap_rows=1000,
+             off=P, ids=P, cnt=P, h_rows=NULL)
     a.update(kw)
-    return [a[k] for k in ("ctx", "walks", "n_seeds", "M", "m", "n_nodes", "cap_rows", "off",
-                           "ids", "cnt", "h_rows")]
+    return [a[k] for k in ("ctx", "walks", "n_seeds", "M", "m", "n_nodes", "sizes", "cap_rows",
+                           "off", "ids", "cnt", "h_rows")]
 
 
 @pytest.mark.parametrize("kw,want", [
@@ -133,6 +137,7 @@ def rpe_args(**kw):
     (dict(ids=NULL), binding.E_NULL),             # ids and cnt go together
     (dict(cnt=NULL), binding.E_NULL),
     (dict(ids=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),   # counting call
+    (dict(sizes=P), binding.E_CTX),                          # caller-provided set sizes
 ])
 def test_build_rpe_argument_checks(lib, kw, want):
     assert lib.surel_build_rpe(*rpe_args(**kw)) == want

@@ -37,12 +37,17 @@ def host_u16(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def gpu_pipeline(ctx, rp, ci, seeds, M, m, rng_seed, queries=None):
+def gpu_pipeline(ctx, rp, ci, seeds, M, m, rng_seed, queries=None, with_sizes=False):
+    """walks -> RPE -> join on the GPU.  ``with_sizes``: the walk kernel reports |V_u| and
+    build_rpe lays the table out from that; otherwise build_rpe counts by itself."""
     d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(np.asarray(seeds, dtype=np.int32))
     n_nodes = rp.size - 1
-    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, rng_seed)
-    off, ids, cnt = binding.build_rpe(ctx, walks, n_nodes)
-    out = {"walks": walks, "rpe": (off, ids, cnt)}
+    sizes = None
+    if with_sizes:
+        sizes = torch.full((d_seeds.numel(),), -1, dtype=torch.int32, device="cuda")
+    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, rng_seed, set_sizes=sizes)
+    off, ids, cnt = binding.build_rpe(ctx, walks, n_nodes, set_sizes=sizes)
+    out = {"walks": walks, "rpe": (off, ids, cnt), "sizes": sizes}
     if queries is not None:
         d_q = dev(np.asarray(queries, dtype=np.int32))
         out["join"] = binding.join_queries(ctx, off, ids, cnt, d_q, max_set=1 + M * m)
@@ -59,13 +64,17 @@ def assert_table_equal(got, want, what):
 
 
 def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
-    out = gpu_pipeline(ctx, rp, ci, seeds, M, m, rng_seed, queries)
     w = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed)
-    assert np.array_equal(out["walks"].cpu().numpy(), w), "walks differ"
     table = oracle.build_rpe(w)
-    assert_table_equal(out["rpe"], table, "rpe")
-    if queries is not None:
-        assert_table_equal(out["join"], oracle.join_queries(*table, queries), "join")
+    joined = oracle.join_queries(*table, queries) if queries is not None else None
+    for with_sizes in (False, True):
+        out = gpu_pipeline(ctx, rp, ci, seeds, M, m, rng_seed, queries, with_sizes)
+        assert np.array_equal(out["walks"].cpu().numpy(), w), "walks differ"
+        if with_sizes:
+            assert np.array_equal(out["sizes"].cpu().numpy(), np.diff(table[0])), "set sizes"
+        assert_table_equal(out["rpe"], table, f"rpe (sizes from walks: {with_sizes})")
+        if queries is not None:
+            assert_table_equal(out["join"], joined, "join")
     return out
 
 
@@ -204,6 +213,29 @@ def test_bad_walk_entry_is_flagged(ctx):
     assert ctx.check() == binding.DEV_BAD_WALK
 
 
+def test_wrong_set_sizes_are_flagged_and_do_not_overlap(ctx):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(16, dtype=np.int32)
+    sizes = torch.empty(16, dtype=torch.int32, device="cuda")
+    walks = binding.sample_walks(ctx, dev(rp), dev(ci), dev(seeds), wl.M, wl.m, 0, set_sizes=sizes)
+    want_off, want_ids, want_cnt = oracle.build_rpe(walks.cpu().numpy())
+    sizes[5] += 3                                         # a size that is not this seed's
+    total = int(want_off[-1]) + 3
+    off = torch.empty(17, dtype=torch.int64, device="cuda")
+    ids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((total, wl.m + 1), dtype=torch.int16, device="cuda").view(torch.uint16)
+    rc, rows = binding.build_rpe_raw(ctx, walks, wl.n_nodes, total, off, ids, cnt,
+                                     set_sizes=sizes)
+    assert rc == binding.OK and rows == total
+    assert ctx.check() == binding.DEV_BAD_SIZES
+    ids_h = ids.cpu().numpy()
+    lo, hi = int(want_off[5]), int(want_off[6]) + 3
+    assert (ids_h[lo:hi] == -7).all()                      # the mismatched seed wrote nothing
+    assert np.array_equal(ids_h[:lo], want_ids[:lo])       # the others are where sizes put them
+    assert np.array_equal(ids_h[hi:], want_ids[int(want_off[6]):])
+
+
 def test_rpe_capacity_overflow_is_reported_and_nothing_is_written_past_it(ctx):
     wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
     rp, ci = synth.make_graph(wl)
@@ -300,9 +332,15 @@ def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
     print(f"[{name}] graph ready: N={N} E2={ci.size} M={M} m={m} queries={queries.shape}",
           flush=True)
 
-    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed)
-    off, ids, cnt = binding.build_rpe(ctx, walks, N, cap_rows=binding.rpe_rows_bound(N, M, m))
+    sizes = torch.empty(N, dtype=torch.int32, device="cuda")
+    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, set_sizes=sizes)
+    off, ids, cnt = binding.build_rpe(ctx, walks, N, cap_rows=binding.rpe_rows_bound(N, M, m),
+                                      set_sizes=sizes)
     assert ctx.check() == 0
+    # the RPE builder's own counting pass gives the same layout
+    off2 = torch.empty_like(off)
+    rc, rows2 = binding.build_rpe_raw(ctx, walks, N, 0, off2, None, None)
+    assert rc == binding.OK and torch.equal(off, off2) and rows2 == int(off[-1])
     R = int(off[-1])
     print(f"[{name}] walks + rpe done: R={R} rows", flush=True)
 
