@@ -28,6 +28,9 @@
  *     clamped, a bit is set in the sticky error word, and surel_check reports it.
  *   - No function throws, prints, or touches errno.
  *
+ *   - The uint16 count arrays (d_rpe_cnt, d_join_cnt) must start on a 4-byte boundary
+ *     (SUREL_E_RANGE otherwise): they are moved as 32-bit words wherever possible.
+ *
  * Layouts (row-major, densely packed, no padding)
  *   CSR      d_row_ptr int32[n_nodes+1], d_col_idx int32[n_edges]; entries of a row are the
  *            neighbours of that node.  The walk treats every entry of a row as equally

@@ -46,6 +46,9 @@ struct DeviceGuard {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// The uint16 count arrays are moved as 32-bit words wherever possible.
+bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+
 // Brackets the launches made during its lifetime with two events on the context's stream
 // when profiling is on; does nothing otherwise.
 class KernelSpan {
@@ -245,6 +248,7 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
     if (cap_rows < 0) return SUREL_E_RANGE;
     if (!d_rpe_off || (n_seeds > 0 && !d_walks)) return SUREL_E_NULL;
     if ((d_rpe_ids == nullptr) != (d_rpe_cnt == nullptr)) return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
     if (!ctx) return SUREL_E_CTX;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
@@ -295,6 +299,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
     if (n_queries > 0 && (!d_queries || !d_rpe_off || !d_rpe_ids)) return SUREL_E_NULL;
     if ((d_join_ids == nullptr) != (d_join_cnt == nullptr)) return SUREL_E_NULL;
     if (n_queries > 0 && d_join_ids && !d_rpe_cnt) return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt) || misaligned4(d_join_cnt)) return SUREL_E_RANGE;
     if (!ctx) return SUREL_E_CTX;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
@@ -321,6 +326,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
         hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
                                  n_blocks, m, max_set, d_queries, n_queries, k, nullptr, d_join_off,
                                  cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
+        if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
         if (hrc != hipSuccess) return SUREL_E_HIP;
     }
     if (h_rows) {

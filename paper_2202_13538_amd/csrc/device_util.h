@@ -88,6 +88,27 @@ __device__ __forceinline__ int32_t wave_incl_max(int32_t v) {
     return v;
 }
 
+// Copies n 32-bit words from global memory to LDS with the whole wave.  Loads are issued U
+// at a time before any of them is waited for, so a copy costs ceil(n / (64*U)) memory round
+// trips instead of one per 64 words.
+template <int U>
+__device__ __forceinline__ void stage_words(uint32_t* dst, const uint32_t* __restrict__ src, int n,
+                                            int lane) {
+    for (int t0 = 0; t0 < n; t0 += kWave * U) {
+        uint32_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * kWave + lane;
+            v[u] = t < n ? src[t] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * kWave + lane;
+            if (t < n) dst[t] = v[u];
+        }
+    }
+}
+
 // Philox-4x32 with 10 rounds (Salmon et al., SC'11): counter c[0..3], key (k0, k1).
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t out[4]) {

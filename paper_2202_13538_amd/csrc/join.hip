@@ -3,24 +3,28 @@
 // vectors in tuple order, zeros where the node is absent from a set.
 //
 // Two launches of one kernel: the first only counts every query's union rows, an exclusive
-// scan turns the counts into join_off, the second writes the rows.  One wavefront per query.
-// The K sorted id lists are staged in LDS.  A node's row
-// in the union is owned by the first list that contains it, and its position is a sum of
-// ranks:
-//   position(x) = #{a in list 0 : a < x} + sum over j >= 1 of #{b in list j : b < x, b not in
-//                 an earlier list},
-// each term being a lower bound in LDS plus a lookup in a per-list prefix count of "new"
-// elements.  This needs no serial merge loop and extends from pairs to triples unchanged.
-// Count vectors are then moved 64 union rows at a time: a lane copies
-// one (row, list) vector from the table into an LDS tile, and the tile is streamed out as
-// whole dwords.
+// scan turns the counts into join_off, the second writes the rows.  One wavefront per query;
+// the K sorted id lists are staged in LDS.
+//
+// Which union row a node lands in, and which table rows feed it ("sources"):
+//   - pairs: a merge path.  Lane l owns merged positions [l*VT, (l+1)*VT): a binary search on
+//     its diagonal finds where it starts in both lists, then it merges VT steps serially,
+//     list 0 first on ties, so an equal pair is one row with two sources.
+//   - triples: ranks.  A row is owned by the first list that holds its node; its position is
+//     #{a in list 0 : a < x} + sum over j >= 1 of #{b in list j : b < x, b in no earlier list},
+//     each term a lower bound in LDS plus a lookup in a prefix count of "new" elements.
+// Count vectors: 64 union rows at a time, a lane moves one (row, list) vector from the table
+// (or zeros) into an LDS tile laid out like the output, and the tile is streamed out as
+// whole dwords.  The kernel keeps its LDS footprint small on purpose: with the vectors read
+// in place it is the number of waves in flight, not LDS staging, that hides the latency.
 #include "device_util.h"
 #include "kernels.h"
 
 namespace surel {
 
 constexpr uint16_t kNoSrc = 0xFFFFu;
-constexpr int kJoinChunkRows = 64;  // union rows staged in LDS per output tile
+constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
+constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {
@@ -38,17 +42,189 @@ __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint
     return lo;
 }
 
-// LDS words one wave needs for tuples of K blocks of at most max_set rows with L counts.
-__host__ __device__ constexpr int join_lds_words(int K, int max_set, int L) {
-    // ids: K*max_set uint32; new-prefix: (K-1)*(max_set+1) uint16; src: K*(K*max_set) uint16;
-    // output tile: kJoinChunkRows*K*L uint16
-    return K * max_set + ((K - 1) * (max_set + 1) + 1) / 2 + (K * K * max_set + 1) / 2 +
-           (kJoinChunkRows * K * L + 1) / 2;
+// Per-wave LDS layout, in 32-bit words.
+struct JoinLds {
+    int ids;      // [K][max_set] uint32
+    int new_pre;  // [K-1][max_set+1] uint16 (triples only)
+    int src;      // [K][K*max_set] uint16: table row of list j that feeds union row r, or kNoSrc
+    int tile;     // [kJoinChunkRows][K][L] uint16 (fill only)
+    int total;
+};
+
+__host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L, bool fill) {
+    JoinLds o{};
+    o.ids = 0;
+    o.new_pre = o.ids + K * max_set;
+    o.src = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
+    o.tile = o.src + (fill ? (K * K * max_set + 1) / 2 : 0);
+    o.total = o.tile + (fill ? (kJoinChunkRows * K * L + 1) / 2 : 0);
+    return o;
 }
 
-// WPB = waves per workgroup: as many as the LDS a wave needs allows.  kFill = false: write
-// counts[q] only; kFill = true: join_off is complete, write the rows.
-template <int K, int WPB, bool kFill>
+// Pairs: union size and (when kFill) the sources of every union row, by merge path.
+template <bool kFill>
+__device__ __forceinline__ int union_pair_merge_path(const uint32_t* A, int nA, const uint32_t* B,
+                                                     int nB, uint16_t* src, int src_stride,
+                                                     int lane) {
+    const int T = nA + nB;
+    const int VT = (T + kWave - 1) / kWave;
+    const int d0 = min(lane * VT, T);
+    const int d1 = min(d0 + VT, T);
+    // split of the first d0 merged elements: a0 from A (ties go to A first), d0 - a0 from B
+    int lo = max(0, d0 - nB);
+    int hi = min(d0, nA);
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (A[mid] <= B[d0 - 1 - mid]) {
+            lo = mid + 1;
+        } else {
+            hi = mid;
+        }
+    }
+    const int a0 = lo;
+    const int b0 = d0 - lo;
+
+    // pass 1: rows this lane emits.  A B element equal to the last A element taken is the
+    // same node (ids are distinct inside a list) and adds no row.
+    int n_emit = 0;
+    {
+        int a = a0, b = b0;
+        uint32_t last_a = a > 0 ? A[a - 1] : kNoId;
+        for (int d = d0; d < d1; ++d) {
+            const uint32_t va = a < nA ? A[a] : kNoId;
+            const uint32_t vb = b < nB ? B[b] : kNoId;
+            const bool take_a = (b >= nB) || (a < nA && va <= vb);
+            if (take_a) {
+                n_emit += 1;
+                last_a = va;
+                a += 1;
+            } else {
+                n_emit += (vb != last_a) ? 1 : 0;
+                b += 1;
+            }
+        }
+    }
+    const int incl = (int)wave_incl_sum((uint32_t)n_emit);
+    const int n_out = (int)wave_bcast_u32((uint32_t)incl, kWave - 1);
+    if (kFill) {
+        int row = incl - n_emit;
+        int a = a0, b = b0;
+        uint32_t last_a = a > 0 ? A[a - 1] : kNoId;
+        for (int d = d0; d < d1; ++d) {
+            const uint32_t va = a < nA ? A[a] : kNoId;
+            const uint32_t vb = b < nB ? B[b] : kNoId;
+            const bool take_a = (b >= nB) || (a < nA && va <= vb);
+            if (take_a) {
+                src[row] = (uint16_t)a;
+                src[src_stride + row] = (b < nB && vb == va) ? (uint16_t)b : kNoSrc;
+                row += 1;
+                last_a = va;
+                a += 1;
+            } else {
+                if (vb != last_a) {
+                    src[row] = kNoSrc;
+                    src[src_stride + row] = (uint16_t)b;
+                    row += 1;
+                }
+                b += 1;
+            }
+        }
+    }
+    return n_out;
+}
+
+// Any K: union size and (when kFill) the sources of every union row, by ranks.
+template <int K, bool kFill>
+__device__ __forceinline__ int union_ranked(const uint32_t* ids_lds, const int (&n)[K], int max_set,
+                                            uint16_t* new_pre, uint16_t* src, int src_stride,
+                                            int lane) {
+    // per list j >= 1: exclusive prefix count of elements that no earlier list contains
+    int n_out = n[0];
+#pragma unroll
+    for (int j = 1; j < K; ++j) {
+        uint16_t* pre = new_pre + (j - 1) * (max_set + 1);
+        int carry = 0;
+        for (int t0 = 0; t0 < n[j]; t0 += kWave) {
+            const int t = t0 + lane;
+            bool is_new = false;
+            if (t < n[j]) {
+                const uint32_t x = ids_lds[j * max_set + t];
+                is_new = true;
+#pragma unroll
+                for (int jj = 0; jj < j; ++jj) {
+                    const uint32_t* other = ids_lds + jj * max_set;
+                    const int p = lower_bound_lds(other, n[jj], x);
+                    if (p < n[jj] && other[p] == x) is_new = false;
+                }
+            }
+            const uint64_t mask = __ballot(is_new);
+            const int before = (int)__builtin_amdgcn_mbcnt_hi(
+                (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (t < n[j]) pre[t] = (uint16_t)(carry + before);
+            carry += __popcll(mask);
+        }
+        if (lane == 0) pre[n[j]] = (uint16_t)carry;
+        n_out += carry;
+    }
+    if (!kFill || n_out == 0) return n_out;
+    wave_sync();
+    // every union row is written by the first list that holds its node
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        const uint16_t* pre_j = new_pre + (j > 0 ? j - 1 : 0) * (max_set + 1);  // j >= 1 only
+        for (int t = lane; t < n[j]; t += kWave) {
+            const uint32_t x = ids_lds[j * max_set + t];
+            if (j > 0 && pre_j[t + 1] == pre_j[t]) continue;  // owned by an earlier list
+            int pos = 0;
+            uint16_t s_idx[K];
+#pragma unroll
+            for (int jj = 0; jj < K; ++jj) {
+                if (jj == j) {
+                    pos += (j == 0) ? t : (int)pre_j[t];
+                    s_idx[jj] = (uint16_t)t;
+                } else {
+                    const uint32_t* other = ids_lds + jj * max_set;
+                    const int p = lower_bound_lds(other, n[jj], x);
+                    pos += (jj == 0) ? p : (int)new_pre[(jj - 1) * (max_set + 1) + p];
+                    const bool present = jj > j && p < n[jj] && other[p] == x;
+                    s_idx[jj] = present ? (uint16_t)p : kNoSrc;
+                }
+            }
+#pragma unroll
+            for (int jj = 0; jj < K; ++jj) src[jj * src_stride + pos] = s_idx[jj];
+        }
+    }
+    return n_out;
+}
+
+// One count vector of LT (compile time) or L (LT == 0) entries from the table into LDS.  With
+// LT known the loads are issued together, before the first of them is waited for.
+template <int LT>
+__device__ __forceinline__ void copy_vector(uint16_t* dst, const uint16_t* from, int L) {
+    if constexpr (LT > 0) {
+        uint16_t v[LT];
+#pragma unroll
+        for (int s = 0; s < LT; ++s) v[s] = from[s];
+#pragma unroll
+        for (int s = 0; s < LT; ++s) dst[s] = v[s];
+    } else {
+        for (int s = 0; s < L; ++s) dst[s] = from[s];
+    }
+}
+template <int LT>
+__device__ __forceinline__ void zero_vector(uint16_t* dst, int L) {
+    if constexpr (LT > 0) {
+#pragma unroll
+        for (int s = 0; s < LT; ++s) dst[s] = 0;
+    } else {
+        for (int s = 0; s < L; ++s) dst[s] = 0;
+    }
+}
+
+// K = tuple size, WPB = waves per workgroup (as many as the LDS a wave needs allows),
+// kFill = false: write counts[q] only; kFill = true: join_off is complete, write the rows.
+// LT = m+1 at compile time for the common walk lengths, 0 = any.
+template <int K, int WPB, bool kFill, int LT>
 __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids,
     const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
@@ -61,120 +237,62 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t q = (int64_t)blockIdx.x * WPB + wave;
     if (q >= n_queries) return;  // whole waves leave; no block-wide barrier is used below
-    constexpr bool has_query = true;
-    constexpr bool fill = kFill;
 
-    const int L = m + 1;
-    uint32_t* ids_lds = lds32 + wave * join_lds_words(K, max_set, L);          // [K][max_set]
-    uint16_t* new_pre = reinterpret_cast<uint16_t*>(ids_lds + K * max_set);     // [K-1][max_set+1]
-    uint32_t* src32 = ids_lds + K * max_set + ((K - 1) * (max_set + 1) + 1) / 2;
-    uint16_t* src = reinterpret_cast<uint16_t*>(src32);                         // [K][K*max_set]
-    uint32_t* tile32 = src32 + (K * K * max_set + 1) / 2;
-    uint16_t* tile = reinterpret_cast<uint16_t*>(tile32);                       // [64][K][L]
+    const int L = LT > 0 ? LT : m + 1;
+    const JoinLds lay = join_lds_layout(K, max_set, L, kFill);
+    uint32_t* base = lds32 + wave * lay.total;
+    uint32_t* ids_lds = base + lay.ids;
+    uint16_t* new_pre = reinterpret_cast<uint16_t*>(base + lay.new_pre);
+    uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
+    uint32_t* tile32 = base + lay.tile;
+    uint16_t* tile = reinterpret_cast<uint16_t*>(tile32);
     const int src_stride = K * max_set;
 
+    // the K blocks of this query (wave-uniform)
     int64_t lo[K];
     int n[K];
-    int n_out = 0;
+    uint32_t problem = 0;
 #pragma unroll
     for (int j = 0; j < K; ++j) {
+        const int32_t b = queries[q * K + j];
         lo[j] = 0;
         n[j] = 0;
+        if (b < 0 || (int64_t)b >= n_blocks) {
+            problem |= kDevBadQuery;
+        } else {
+            const int64_t a = rpe_off[b];
+            const int64_t len = rpe_off[b + 1] - a;
+            if (a < 0 || len < 0) {
+                problem |= kDevBadTable;
+            } else if (len > (int64_t)max_set) {
+                problem |= kDevSetTooLarge;
+            } else {
+                lo[j] = a;
+                n[j] = (int)len;
+            }
+        }
+    }
+    if (problem != 0) {
+        if (lane == 0) {
+            atomicOr(err, problem);
+            if (!kFill) counts[q] = 0;  // the query yields no rows
+        }
+        return;
     }
 
-    if (has_query) {
-        // the K blocks of this query (wave-uniform)
-        uint32_t problem = 0;
+    // stage the id lists
 #pragma unroll
-        for (int j = 0; j < K; ++j) {
-            const int32_t b = queries[q * K + j];
-            if (b < 0 || (int64_t)b >= n_blocks) {
-                problem |= kDevBadQuery;
-            } else {
-                const int64_t a = rpe_off[b];
-                const int64_t len = rpe_off[b + 1] - a;
-                if (a < 0 || len < 0) {
-                    problem |= kDevBadTable;
-                } else if (len > (int64_t)max_set) {
-                    problem |= kDevSetTooLarge;
-                } else {
-                    lo[j] = a;
-                    n[j] = (int)len;
-                }
-            }
-        }
-        if (problem != 0) {
-            if (lane == 0) atomicOr(err, problem);
-#pragma unroll
-            for (int j = 0; j < K; ++j) n[j] = 0;  // the query yields no rows
-        }
+    for (int j = 0; j < K; ++j)
+        stage_words<8>(ids_lds + j * max_set, reinterpret_cast<const uint32_t*>(rpe_ids + lo[j]),
+                       n[j], lane);
+    wave_sync();
 
-        // stage the id lists
-#pragma unroll
-        for (int j = 0; j < K; ++j) {
-            for (int t = lane; t < n[j]; t += kWave)
-                ids_lds[j * max_set + t] = (uint32_t)rpe_ids[lo[j] + t];
-        }
-        wave_sync();
-
-        // per list j >= 1: exclusive prefix count of elements that no earlier list contains
-        n_out = n[0];
-#pragma unroll
-        for (int j = 1; j < K; ++j) {
-            uint16_t* pre = new_pre + (j - 1) * (max_set + 1);
-            int carry = 0;
-            for (int t0 = 0; t0 < n[j]; t0 += kWave) {
-                const int t = t0 + lane;
-                bool is_new = false;
-                if (t < n[j]) {
-                    const uint32_t x = ids_lds[j * max_set + t];
-                    is_new = true;
-#pragma unroll
-                    for (int jj = 0; jj < j; ++jj) {
-                        const uint32_t* other = ids_lds + jj * max_set;
-                        const int p = lower_bound_lds(other, n[jj], x);
-                        if (p < n[jj] && other[p] == x) is_new = false;
-                    }
-                }
-                const uint64_t mask = __ballot(is_new);
-                const int before = (int)__builtin_amdgcn_mbcnt_hi(
-                    (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                if (t < n[j]) pre[t] = (uint16_t)(carry + before);
-                carry += __popcll(mask);
-            }
-            if (lane == 0) pre[n[j]] = (uint16_t)carry;
-            n_out += carry;
-        }
-
-        if (fill && n_out > 0) {
-            wave_sync();
-            // every union row is written by the first list that holds its node
-#pragma unroll
-            for (int j = 0; j < K; ++j) {
-                const uint16_t* pre_j = new_pre + (j > 0 ? j - 1 : 0) * (max_set + 1);  // j >= 1 only
-                for (int t = lane; t < n[j]; t += kWave) {
-                    const uint32_t x = ids_lds[j * max_set + t];
-                    if (j > 0 && pre_j[t + 1] == pre_j[t]) continue;  // owned by an earlier list
-                    int pos = 0;
-                    uint16_t s_idx[K];
-#pragma unroll
-                    for (int jj = 0; jj < K; ++jj) {
-                        if (jj == j) {
-                            pos += (j == 0) ? t : (int)pre_j[t];
-                            s_idx[jj] = (uint16_t)t;
-                        } else {
-                            const uint32_t* other = ids_lds + jj * max_set;
-                            const int p = lower_bound_lds(other, n[jj], x);
-                            pos += (jj == 0) ? p : (int)new_pre[(jj - 1) * (max_set + 1) + p];
-                            const bool present = jj > j && p < n[jj] && other[p] == x;
-                            s_idx[jj] = present ? (uint16_t)p : kNoSrc;
-                        }
-                    }
-#pragma unroll
-                    for (int jj = 0; jj < K; ++jj) src[jj * src_stride + pos] = s_idx[jj];
-                }
-            }
-        }
+    int n_out;
+    if constexpr (K == 2) {
+        n_out = union_pair_merge_path<kFill>(ids_lds, n[0], ids_lds + max_set, n[1], src,
+                                             src_stride, lane);
+    } else {
+        n_out = union_ranked<K, kFill>(ids_lds, n, max_set, new_pre, src, src_stride, lane);
     }
 
     if (!kFill) {
@@ -204,27 +322,26 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
             out_ids[off + r0 + lane] = (int32_t)id;
         }
 
-        // one lane per (row, list): copy that list's count vector, or zeros, into the tile
+        // one lane per (row, list): that list's count vector, or zeros, into the tile
         for (int t = lane; t < rows * K; t += kWave) {
             const int row = t / K;
             const int j = t - row * K;
             const uint16_t sj = src[j * src_stride + r0 + row];
-            int64_t base = lo[0];
             int len = n[0];
+            int64_t first = lo[0];
 #pragma unroll
             for (int jj = 1; jj < K; ++jj) {
                 if (j == jj) {
-                    base = lo[jj];
                     len = n[jj];
+                    first = lo[jj];
                 }
             }
             uint16_t* dst = tile + t * L;
-            // kNoSrc is >= any len; the bound also keeps a malformed table from reading outside
+            // kNoSrc is >= any len; the bound also covers a malformed (unsorted) table
             if ((int)sj < len) {
-                const uint16_t* from = rpe_cnt + (base + sj) * L;
-                for (int s = 0; s < L; ++s) dst[s] = from[s];
+                copy_vector<LT>(dst, rpe_cnt + (first + sj) * L, L);
             } else {
-                for (int s = 0; s < L; ++s) dst[s] = 0;
+                zero_vector<LT>(dst, L);
             }
         }
         wave_sync();
@@ -248,48 +365,48 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     }
 }
 
-template <int K, int WPB>
-static hipError_t launch_join_kw(hipStream_t stream, const int64_t* rpe_off,
-                                 const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
-                                 int32_t m, int32_t max_set, const int32_t* queries,
-                                 int64_t n_queries, int32_t* counts, const int64_t* join_off,
-                                 int64_t cap_rows, int32_t* out_ids, uint16_t* out_cnt,
-                                 uint32_t* err) {
-    const size_t lds_bytes = (size_t)WPB * join_lds_words(K, max_set, m + 1) * 4;
-    const void* fn = counts ? reinterpret_cast<const void*>(join_kernel<K, WPB, false>)
-                            : reinterpret_cast<const void*>(join_kernel<K, WPB, true>);
+#define SUREL_JOIN_PARAMS                                                                         \
+    hipStream_t stream, const int64_t *rpe_off, const int32_t *rpe_ids, const uint16_t *rpe_cnt,  \
+        int64_t n_blocks, int32_t m, int32_t max_set, const int32_t *queries, int64_t n_queries,  \
+        int32_t *counts, const int64_t *join_off, int64_t cap_rows, int32_t *out_ids,             \
+        uint16_t *out_cnt, uint32_t *err
+#define SUREL_JOIN_ARGS                                                                          \
+    stream, rpe_off, rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off, \
+        cap_rows, out_ids, out_cnt, err
+
+template <int K, int WPB, bool kFill, int LT>
+static hipError_t launch_join_cfg(SUREL_JOIN_PARAMS) {
+    const size_t lds_bytes = (size_t)WPB * join_lds_layout(K, max_set, m + 1, kFill).total * 4;
     if (lds_bytes > 48 * 1024) {
-        hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)lds_bytes);
+        hipError_t rc = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (rc != hipSuccess) return rc;
     }
     const dim3 grid((unsigned)((n_queries + WPB - 1) / WPB)), block(WPB * kWave);
-    if (counts) {
-        hipLaunchKernelGGL((join_kernel<K, WPB, false>), grid, block, lds_bytes, stream, rpe_off,
-                           rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts,
-                           join_off, cap_rows, out_ids, out_cnt, err);
-    } else {
-        hipLaunchKernelGGL((join_kernel<K, WPB, true>), grid, block, lds_bytes, stream, rpe_off,
-                           rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts,
-                           join_off, cap_rows, out_ids, out_cnt, err);
-    }
+    hipLaunchKernelGGL((join_kernel<K, WPB, kFill, LT>), grid, block, lds_bytes, stream, rpe_off,
+                       rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off,
+                       cap_rows, out_ids, out_cnt, err);
     return hipGetLastError();
+}
+
+template <int K, int WPB, bool kFill>
+static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
+    if (kFill && m + 1 == 5) return launch_join_cfg<K, WPB, kFill, 5>(SUREL_JOIN_ARGS);
+    if (kFill && m + 1 == 4) return launch_join_cfg<K, WPB, kFill, 4>(SUREL_JOIN_ARGS);
+    return launch_join_cfg<K, WPB, kFill, 0>(SUREL_JOIN_ARGS);
 }
 
 // counts != nullptr: counting launch (writes counts[q]); else: writing launch.
 template <int K>
-static hipError_t launch_join_k(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
-                                const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
-                                int32_t m, int32_t max_set, const int32_t* queries,
-                                int64_t n_queries, int32_t* counts, const int64_t* join_off,
-                                int64_t cap_rows, int32_t* out_ids, uint16_t* out_cnt,
-                                uint32_t* err) {
-    const size_t per_wave = (size_t)join_lds_words(K, max_set, m + 1) * 4;
-#define SUREL_JOIN_CASE(W_)                                                                    \
-    if (per_wave * (W_) <= (size_t)max_lds_bytes)                                              \
-        return launch_join_kw<K, W_>(stream, rpe_off, rpe_ids, rpe_cnt, n_blocks, m, max_set,  \
-                                     queries, n_queries, counts, join_off, cap_rows, out_ids,  \
-                                     out_cnt, err);
+static hipError_t launch_join_k(int max_lds_bytes, SUREL_JOIN_PARAMS) {
+    const bool fill = counts == nullptr;
+    const size_t per_wave = (size_t)join_lds_layout(K, max_set, m + 1, fill).total * 4;
+#define SUREL_JOIN_CASE(W_)                                                \
+    if (per_wave * (W_) <= (size_t)max_lds_bytes) {                        \
+        if (fill) return launch_join_kwf<K, W_, true>(SUREL_JOIN_ARGS);    \
+        return launch_join_kwf<K, W_, false>(SUREL_JOIN_ARGS);             \
+    }
     SUREL_JOIN_CASE(4)
     SUREL_JOIN_CASE(2)
     SUREL_JOIN_CASE(1)
@@ -303,14 +420,8 @@ hipError_t launch_join(hipStream_t stream, int max_lds_bytes, const int64_t* rpe
                        int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
                        int32_t* out_ids, uint16_t* out_cnt, uint32_t* err) {
     if (n_queries == 0) return hipSuccess;
-    if (k == 2)
-        return launch_join_k<2>(stream, max_lds_bytes, rpe_off, rpe_ids, rpe_cnt, n_blocks, m,
-                                max_set, queries, n_queries, counts, join_off, cap_rows, out_ids,
-                                out_cnt, err);
-    if (k == 3)
-        return launch_join_k<3>(stream, max_lds_bytes, rpe_off, rpe_ids, rpe_cnt, n_blocks, m,
-                                max_set, queries, n_queries, counts, join_off, cap_rows, out_ids,
-                                out_cnt, err);
+    if (k == 2) return launch_join_k<2>(max_lds_bytes, SUREL_JOIN_ARGS);
+    if (k == 3) return launch_join_k<3>(max_lds_bytes, SUREL_JOIN_ARGS);
     return hipErrorInvalidValue;
 }
 

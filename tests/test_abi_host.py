@@ -138,6 +138,7 @@ def rpe_args(**kw):
     (dict(cnt=NULL), binding.E_NULL),
     (dict(ids=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),   # counting call
     (dict(sizes=P), binding.E_CTX),                          # caller-provided set sizes
+    (dict(cnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),    # counts must be 4-byte aligned
 ])
 def test_build_rpe_argument_checks(lib, kw, want):
     assert lib.surel_build_rpe(*rpe_args(**kw)) == want
@@ -172,6 +173,8 @@ def join_args(**kw):
     (dict(jids=NULL), binding.E_NULL),
     (dict(jids=NULL, jcnt=NULL, cap_rows=0), binding.E_CTX),
     (dict(jids=NULL, jcnt=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),  # counting needs no counts
+    (dict(cnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
+    (dict(jcnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
 ])
 def test_join_queries_argument_checks(lib, kw, want):
     assert lib.surel_join_queries(*join_args(**kw)) == want
