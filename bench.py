@@ -98,6 +98,10 @@ def main() -> int:
     ap.add_argument("--cpu-seeds", type=int, default=1 << 17)
     ap.add_argument("--cpu-queries", type=int, default=1 << 14)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run three plain 1 GiB read + 1 GiB write "
+                         "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
+                         "/ WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build is the one-GPU hot path; --gpus must be 1 "
@@ -223,6 +227,13 @@ def main() -> int:
         "pipeline_hbm_frac": round(pipeline_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": roofline,
     }
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.add(a, 1, out=b)        # an elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     if not args.no_cpu:
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(wl, rp, ci, queries, args.cpu_seeds, args.cpu_queries)
