@@ -15,8 +15,10 @@ struct surel_ctx {
     int max_lds_bytes = 0;
     uint32_t* d_err = nullptr;    // sticky device error word
     int64_t* h_pinned = nullptr;  // 2 x int64 of pinned host memory for small read-backs
-    void* d_ws = nullptr;         // grow-only workspace
+    void* d_ws = nullptr;         // grow-only workspace: row counts + scan partials
     size_t ws_bytes = 0;
+    void* d_rec = nullptr;        // grow-only workspace: per-edge neighbour records of the walk
+    size_t rec_bytes = 0;
     // optional per-kernel timing (surel_profile_*)
     struct Span {
         int kernel;
@@ -196,6 +198,7 @@ void surel_destroy(surel_ctx* ctx) {
     }
     for (hipEvent_t e : ctx->free_events) (void)hipEventDestroy(e);
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+    if (ctx->d_rec) (void)hipFree(ctx->d_rec);
     if (ctx->d_err) (void)hipFree(ctx->d_err);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     delete ctx;
@@ -232,10 +235,27 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     if (n_seeds == 0) return SUREL_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
+    void* records = nullptr;
+    if (surel::walks_want_records(n_edges, n_seeds, M, m)) {
+        const size_t need = (size_t)n_edges * 16;
+        if (need > ctx->rec_bytes) {
+            if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+            if (ctx->d_rec) (void)hipFree(ctx->d_rec);
+            ctx->d_rec = nullptr;
+            ctx->rec_bytes = 0;
+            // no room for the records is not an error: the walk then reads the CSR directly
+            if (hipMalloc(&ctx->d_rec, need) == hipSuccess) {
+                ctx->rec_bytes = need;
+            } else {
+                (void)hipGetLastError();
+            }
+        }
+        if (ctx->rec_bytes >= need) records = ctx->d_rec;
+    }
     KernelSpan span(ctx, SUREL_K_WALK);
     hipError_t rc = surel::launch_walks(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
                                         d_seeds, n_seeds, M, m, rng_seed, d_walks, d_set_sizes,
-                                        ctx->d_err);
+                                        records, ctx->d_err);
     return rc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
 }
 

@@ -7,11 +7,14 @@
 namespace surel {
 
 // walk.hip.  set_sizes (optional): int32[n_seeds], receives the number of distinct nodes of
-// every seed's walks; needs 1 + M*m <= 2048.
+// every seed's walks; needs 1 + M*m <= 2048.  edge_records (optional): device scratch of
+// 16 * n_edges bytes; when given, the CSR is first expanded into per-edge neighbour records
+// (worth it when walks_want_records says so).
+bool walks_want_records(int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m);
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
-                        int32_t* set_sizes, uint32_t* err);
+                        int32_t* set_sizes, void* edge_records, uint32_t* err);
 
 // rpe.hip.  launch_rpe_count: set_sizes[i] = distinct nodes in walks[i].  launch_rpe_fill:
 // writes the rows of every seed at rpe_off[i] (seeds whose block would pass cap_rows, or whose

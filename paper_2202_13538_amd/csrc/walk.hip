@@ -6,6 +6,13 @@
 // non-temporal stores: they are not read again by this kernel and should not push the
 // graph out of the caches that serve the neighbour gathers.
 //
+// Neighbour records.  A step needs the chosen neighbour's id and then that neighbour's own
+// row (start, degree) for the next step: two dependent gathers that each miss the L2 and
+// pull a whole cache line for a few bytes, which is what bounds this kernel.  When the job
+// is large next to the graph, a small kernel first expands the CSR into one 16-byte record
+// per edge entry, (neighbour id, its row start, its degree), so that every step after the
+// first is a single gather.  Both forms make exactly the same walks.
+//
 // Optionally the kernel also reports |V_u|, the number of distinct nodes of each seed's
 // walks (Algorithm 1: V_u = set(W_u)), through an LDS hash set fed while the walkers move.
 // The kernel waits on memory nearly all the time, so this costs little, and it saves the
@@ -18,12 +25,30 @@ namespace surel {
 
 constexpr int kWalkWavesPerBlock = 4;
 
-template <bool kCount>
+// rec[e] = (col_idx[e], row_ptr[col_idx[e]], degree of col_idx[e], 0); an entry that names no
+// node, or whose row is malformed, gets id -1 (the walker will stay in place and flag it).
+__global__ void edge_record_kernel(const int32_t* __restrict__ row_ptr,
+                                   const int32_t* __restrict__ col_idx, int32_t n_nodes,
+                                   int64_t n_edges, int4* __restrict__ rec) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_edges) return;
+    const int32_t t = col_idx[e];
+    int4 r = make_int4(-1, 0, 0, 0);
+    if ((uint32_t)t < (uint32_t)n_nodes) {
+        const int32_t lo = row_ptr[t];
+        const int32_t hi = row_ptr[t + 1];
+        if (lo >= 0 && hi >= lo && (int64_t)hi <= n_edges) r = make_int4(t, lo, hi - lo, 0);
+    }
+    rec[e] = r;
+}
+
+template <bool kCount, bool kRec>
 __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
-    const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int32_t n_nodes,
-    int64_t n_edges, const int32_t* __restrict__ seeds, int64_t n_seeds, int32_t M, int32_t m,
-    uint32_t key0, uint32_t key1, int32_t* __restrict__ walks, int32_t* __restrict__ set_sizes,
-    int32_t slots, uint32_t* __restrict__ err) {
+    const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+    const int4* __restrict__ rec, int32_t n_nodes, int64_t n_edges,
+    const int32_t* __restrict__ seeds, int64_t n_seeds, int32_t M, int32_t m, uint32_t key0,
+    uint32_t key1, int32_t* __restrict__ walks, int32_t* __restrict__ set_sizes, int32_t slots,
+    uint32_t* __restrict__ err) {
     extern __shared__ int32_t lds[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -55,10 +80,19 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
     }
 
     bool bad_graph = false;
+    // the seed's own row (wave-uniform); a malformed row counts as degree 0
+    int32_t u_lo = row_ptr[u];
+    int32_t u_deg = row_ptr[u + 1] - u_lo;
+    if (u_lo < 0 || u_deg < 0 || (int64_t)u_lo + u_deg > n_edges) {
+        bad_graph = true;
+        u_deg = 0;
+    }
     for (int w0 = 0; w0 < M; w0 += kWave) {
         const int w = w0 + lane;
         const bool active = w < M;
         int32_t cur = u;
+        int32_t cur_lo = u_lo;     // row of `cur` (kRec only)
+        int32_t cur_deg = u_deg;
         stage[lane * L] = u;
         for (int s0 = 1; s0 <= m; s0 += 4) {
             uint32_t r[4];
@@ -67,7 +101,18 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
             for (int j = 0; j < 4; ++j) {
                 const int s = s0 + j;
                 if (s <= m) {
-                    if (active) {
+                    if (kRec) {
+                        if (active && cur_deg > 0) {
+                            const int4 nb = rec[(int64_t)cur_lo + (int64_t)(r[j] % (uint32_t)cur_deg)];
+                            if (nb.x < 0) {
+                                bad_graph = true;
+                            } else {
+                                cur = nb.x;
+                                cur_lo = nb.y;
+                                cur_deg = nb.z;
+                            }
+                        }
+                    } else if (active) {
                         const int32_t lo = row_ptr[cur];
                         const int32_t hi = row_ptr[cur + 1];
                         if (lo < 0 || hi < lo || (int64_t)hi > n_edges) {
@@ -97,34 +142,57 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
     raise_error(err, bad_graph, kDevBadGraph);
 }
 
+bool walks_want_records(int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m) {
+    // the expansion reads every edge entry once; it pays off when the steps after the first
+    // outnumber the edge entries several times
+    return m >= 2 && n_edges > 0 && n_seeds * (int64_t)M * (m - 1) >= 4 * n_edges;
+}
+
+template <bool kCount, bool kRec>
+static hipError_t launch_walks_cfg(hipStream_t stream, const int32_t* row_ptr,
+                                   const int32_t* col_idx, const int4* rec, int32_t n_nodes,
+                                   int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
+                                   int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
+                                   int32_t* set_sizes, uint32_t* err) {
+    const int64_t blocks = (n_seeds + kWalkWavesPerBlock - 1) / kWalkWavesPerBlock;
+    const int slots = kCount ? distinct_slots(1 + M * m) : 0;
+    const size_t lds_bytes = (size_t)kWalkWavesPerBlock * (kWave * (m + 1) + slots) * 4;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t rc = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(walk_kernel<kCount, kRec>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (rc != hipSuccess) return rc;
+    }
+    hipLaunchKernelGGL((walk_kernel<kCount, kRec>), dim3((unsigned)blocks),
+                       dim3(kWalkWavesPerBlock * kWave), lds_bytes, stream, row_ptr, col_idx, rec,
+                       n_nodes, n_edges, seeds, n_seeds, M, m,
+                       (uint32_t)(rng_seed & 0xFFFFFFFFull), (uint32_t)(rng_seed >> 32), walks,
+                       set_sizes, slots, err);
+    return hipGetLastError();
+}
+
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
-                        int32_t* set_sizes, uint32_t* err) {
+                        int32_t* set_sizes, void* edge_records, uint32_t* err) {
     if (n_seeds == 0) return hipSuccess;
-    const int64_t blocks = (n_seeds + kWalkWavesPerBlock - 1) / kWalkWavesPerBlock;
-    const uint32_t key0 = (uint32_t)(rng_seed & 0xFFFFFFFFull);
-    const uint32_t key1 = (uint32_t)(rng_seed >> 32);
-    const dim3 grid((unsigned)blocks), block(kWalkWavesPerBlock * kWave);
-    if (set_sizes != nullptr) {
-        const int slots = distinct_slots(1 + M * m);
-        const size_t lds_bytes = (size_t)kWalkWavesPerBlock * (kWave * (m + 1) + slots) * 4;
-        if (lds_bytes > 48 * 1024) {
-            hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(walk_kernel<true>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                (int)lds_bytes);
-            if (rc != hipSuccess) return rc;
-        }
-        hipLaunchKernelGGL(walk_kernel<true>, grid, block, lds_bytes, stream, row_ptr, col_idx,
-                           n_nodes, n_edges, seeds, n_seeds, M, m, key0, key1, walks, set_sizes,
-                           slots, err);
-    } else {
-        const size_t lds_bytes = (size_t)kWalkWavesPerBlock * kWave * (m + 1) * 4;
-        hipLaunchKernelGGL(walk_kernel<false>, grid, block, lds_bytes, stream, row_ptr, col_idx,
-                           n_nodes, n_edges, seeds, n_seeds, M, m, key0, key1, walks, set_sizes, 0,
-                           err);
+    int4* rec = static_cast<int4*>(edge_records);
+    if (rec != nullptr) {
+        const int threads = 256;
+        hipLaunchKernelGGL(edge_record_kernel, dim3((unsigned)((n_edges + threads - 1) / threads)),
+                           dim3(threads), 0, stream, row_ptr, col_idx, n_nodes, n_edges, rec);
+        if (hipError_t rc = hipGetLastError(); rc != hipSuccess) return rc;
     }
-    return hipGetLastError();
+#define SUREL_WALK_ARGS \
+    stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m, rng_seed, walks, set_sizes, err
+    if (set_sizes != nullptr) {
+        if (rec != nullptr) return launch_walks_cfg<true, true>(SUREL_WALK_ARGS);
+        return launch_walks_cfg<true, false>(SUREL_WALK_ARGS);
+    }
+    if (rec != nullptr) return launch_walks_cfg<false, true>(SUREL_WALK_ARGS);
+    return launch_walks_cfg<false, false>(SUREL_WALK_ARGS);
+#undef SUREL_WALK_ARGS
 }
+
 
 }  // namespace surel
