@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the walk -> RPE -> join hot path on one MI355X.
 
-A step is one pass of the whole path over the workload: sample_walks for every node,
-build_rpe over all walks, join_queries over all query tuples, inputs already resident in
-HBM and output buffers allocated beforehand.  The line printed at the end follows the
+A step is one pass of the whole path over the workload: walks for every node and the RPE
+table of all walks (one fused kernel by default; --unfused runs sample_walks and build_rpe
+as two calls), then join_queries over all query tuples, inputs already resident in HBM and
+output buffers allocated beforehand.  The line printed at the end follows the
 driver's contract; `value` is walk-steps/s through the whole pipeline (the stage rates and
 the HBM-roofline fractions are extra keys of the same line).
 
@@ -29,13 +30,16 @@ def log(msg: str) -> None:
     print(msg, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(N, M, m, k, R, J, in_rows, Q):
-    """Bytes the method itself must move, per stage (one pass)."""
+def algorithmic_bytes(N, M, m, k, R, J, in_rows, Q, fused):
+    """Bytes the method itself must move, per stage (one pass).  The fused kernel never reads
+    the walks back, so that read is not part of its figure."""
     L = m + 1
     walk = N * M * m * 12 + N * M * L * 4 + N * 4
-    rpe = N * M * L * 4 + R * (4 + 2 * L) + (N + 1) * 8
+    rpe_out = R * (4 + 2 * L) + (N + 1) * 8
     join = in_rows * (4 + 2 * L) + Q * k * (4 + 16) + J * (4 + 2 * k * L) + (Q + 1) * 8
-    return {"walk": walk, "rpe": rpe, "join": join}
+    if fused:
+        return {"walk_rpe": walk + rpe_out, "join": join}
+    return {"walk": walk, "rpe": N * M * L * 4 + rpe_out, "join": join}
 
 
 def read_traffic(workload: str):
@@ -98,6 +102,8 @@ def main() -> int:
     ap.add_argument("--cpu-seeds", type=int, default=1 << 17)
     ap.add_argument("--cpu-queries", type=int, default=1 << 14)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--unfused", action="store_true",
+                    help="sample_walks and build_rpe as two calls instead of the fused kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
@@ -158,11 +164,17 @@ def main() -> int:
     in_rows = int((rpe_off[1:] - rpe_off[:-1])[d_q.long()].sum())
     log(f"[bench] R={R} RPE rows, J={J} joined rows, {in_rows} table rows read by the join")
 
+    fused = not args.unfused
+
     def one_step():
-        binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
-                             set_sizes=set_sizes)
-        rc1, r = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
-                                       set_sizes=set_sizes)
+        if fused:
+            rc1, r = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed,
+                                                  walks, cap_r, rpe_off, rpe_ids, rpe_cnt)
+        else:
+            binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
+                                 set_sizes=set_sizes)
+            rc1, r = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
+                                           set_sizes=set_sizes)
         rc2, j = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, J,
                                           join_off, join_ids, join_cnt)
         assert rc1 == binding.OK and rc2 == binding.OK and r == R and j == J
@@ -185,18 +197,22 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     kern = {name: (tot / n if n else 0.0) for name, (tot, n) in prof.items()}   # avg ms / launch
     per_step = {name: tot / args.steps for name, (tot, n) in prof.items()}       # ms / step
-    stage_ms = {
-        "walk": per_step.get("walk", 0.0),
-        "rpe": per_step.get("rpe_count", 0.0) + per_step.get("rpe_fill", 0.0),
-        "join": per_step.get("join_count", 0.0) + per_step.get("join_fill", 0.0),
-    }
-    alg = algorithmic_bytes(N, M, m, k, R, J, in_rows, Q)
+    join_ms = per_step.get("join_count", 0.0) + per_step.get("join_fill", 0.0)
+    if fused:
+        stage_ms = {"walk_rpe": per_step.get("walk_rpe", 0.0), "join": join_ms}
+        walk_ms = rpe_ms = stage_ms["walk_rpe"]     # one kernel makes both outputs
+    else:
+        stage_ms = {"walk": per_step.get("walk", 0.0),
+                    "rpe": per_step.get("rpe_count", 0.0) + per_step.get("rpe_fill", 0.0),
+                    "join": join_ms}
+        walk_ms, rpe_ms = stage_ms["walk"], stage_ms["rpe"]
+    alg = algorithmic_bytes(N, M, m, k, R, J, in_rows, Q, fused)
     pipeline_bytes = sum(alg.values())
     traffic = read_traffic(wl.name)
 
     # roofline of the dominant kernel (largest average launch duration)
     dom = max(kern, key=lambda n: kern[n])
-    dom_stage = dom.split("_")[0]
+    dom_stage = dom if dom in alg else dom.split("_")[0]
     dom_gbs = alg[dom_stage] / (kern[dom] * 1e-3) / 1e9 if kern[dom] > 0 else 0.0
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
@@ -215,10 +231,11 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": wl.name, "graph": wl.graph, "n_nodes": N, "n_edges": wl.n_edges,
-                   "M": M, "m": m, "n_queries": Q, "k": k, "rpe_rows": R, "joined_rows": J},
-        "walk_steps_per_s": N * M * m / (stage_ms["walk"] * 1e-3) if stage_ms["walk"] else None,
-        "rpe_rows_per_s": R / (stage_ms["rpe"] * 1e-3) if stage_ms["rpe"] else None,
-        "joined_rows_per_s": J / (stage_ms["join"] * 1e-3) if stage_ms["join"] else None,
+                   "M": M, "m": m, "n_queries": Q, "k": k, "rpe_rows": R, "joined_rows": J,
+                   "walk_and_rpe": "one fused kernel" if fused else "two calls"},
+        "walk_steps_per_s": N * M * m / (walk_ms * 1e-3) if walk_ms else None,
+        "rpe_rows_per_s": R / (rpe_ms * 1e-3) if rpe_ms else None,
+        "joined_rows_per_s": J / (join_ms * 1e-3) if join_ms else None,
         "stage_ms": {s: round(v, 4) for s, v in stage_ms.items()},
         "kernel_avg_ms": {n: round(v, 4) for n, v in kern.items()},
         "stage_hbm_frac": {s: round(alg[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)

@@ -18,8 +18,9 @@
  *   - All work is enqueued on the context's stream.  A call returns without waiting unless
  *     a non-NULL h_rows is passed (then it waits for its own work and reports the row
  *     total).  Calls on one context must not overlap from several host threads.
- *   - The context owns a grow-only device workspace (per-seed / per-query row counts and
- *     scan partials) and a device error word; nothing else is allocated.
+ *   - The context owns grow-only device workspaces (per-seed / per-query row counts, scan
+ *     partials, the walk's per-edge neighbour records, the fused kernel's look-back words)
+ *     and a device error word; nothing else is allocated.
  *   - Return value: SUREL_OK (0) or a negative SUREL_E_* code.  Arguments are validated on
  *     the host before anything is enqueued, so a call that returns SUREL_E_NULL or
  *     SUREL_E_RANGE has launched nothing.  Problems only visible on the device (a seed or
@@ -72,6 +73,9 @@ extern "C" {
 #define SUREL_DEV_BAD_TABLE     0x40u  /* d_rpe_off is not non-decreasing at a queried block */
 #define SUREL_DEV_BAD_SIZES     0x80u  /* a seed's d_set_sizes entry is not its number of
                                           distinct nodes; that seed's rows are not written   */
+#define SUREL_DEV_STALL         0x100u /* a bounded wait inside surel_sample_walks_rpe ran out
+                                          (see surel_set_spin_limit); its outputs are
+                                          incomplete                                         */
 
 /* limits */
 #define SUREL_MAX_NODES   268435455   /* 2^28 - 1: node id and step share one 32-bit sort key */
@@ -88,7 +92,8 @@ extern "C" {
 #define SUREL_K_JOIN_COUNT  3   /* join: counting launch                              */
 #define SUREL_K_JOIN_FILL   4   /* join: writing launch                               */
 #define SUREL_K_SCAN        5   /* the offset scans (three small launches each)       */
-#define SUREL_K_COUNT       6
+#define SUREL_K_WALK_RPE    6   /* fused walk + RPE kernel (surel_sample_walks_rpe)   */
+#define SUREL_K_COUNT       7
 
 typedef struct surel_ctx surel_ctx;
 
@@ -151,6 +156,21 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
                     int64_t* d_rpe_off, int32_t* d_rpe_ids, uint16_t* d_rpe_cnt,
                     int64_t* h_rows);
 
+/* Sec. 3.2: "the RPE is computed on the fly as walks get sampled" (Algorithm 1, walk and RPE
+ * steps in one pass).  Exactly the results of surel_sample_walks followed by surel_build_rpe
+ * on its walks, from one kernel that never reads the walks back: d_walks as in
+ * surel_sample_walks; cap_rows, d_rpe_off, d_rpe_ids, d_rpe_cnt, h_rows as in surel_build_rpe
+ * (ids / cnt may be NULL together: offsets and total only; the walks are written either way).
+ * Limits: those of both calls (M*(m+1) <= SUREL_MAX_WALK_ENTRIES).  n_seeds = 0 writes
+ * d_rpe_off[0] = 0.
+ * Device-detected: BAD_SEED (that seed's walks are filled with -1 and it gets no rows),
+ * BAD_GRAPH (the walker stays in place for that step), CAPACITY, STALL. */
+int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                           int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                           int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                           int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
+                           int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows);
+
 /* Sec. 3.4, set-union form: for every query q with tuple (b_1..b_k) of table blocks, the
  * ascending union of the blocks' id lists and, per union node x and j < k, block b_j's count
  * vector for x, or m+1 zeros when x is not in block b_j.
@@ -168,6 +188,12 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                        int32_t k, int64_t cap_rows, int64_t* d_join_off,
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
+
+/* Every wait inside the fused kernel of surel_sample_walks_rpe (a wave waiting for an offset,
+ * the offset scan waiting for a row count) gives up after `spins` polls, raises
+ * SUREL_DEV_STALL and lets the kernel end.  The default (2^22 polls, seconds) is never reached
+ * by a healthy run; tests set 0 to see the bounded exit.  Errors: SUREL_E_CTX. */
+int surel_set_spin_limit(surel_ctx* ctx, uint32_t spins);
 
 /* Per-kernel timing for benchmarks.  While enabled, every kernel group the context launches
  * is bracketed by two HIP events on the context's stream (a few microseconds of host work

@@ -17,12 +17,15 @@ LIB_PATH = os.path.join(_PKG_DIR, "libsurel.so")
 OK, E_NULL, E_RANGE, E_HIP, E_CAPACITY, E_CTX, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 DEV_BAD_SEED, DEV_BAD_GRAPH, DEV_BAD_WALK, DEV_BAD_QUERY = 0x01, 0x02, 0x04, 0x08
 DEV_SET_TOO_LARGE, DEV_CAPACITY, DEV_BAD_TABLE, DEV_BAD_SIZES = 0x10, 0x20, 0x40, 0x80
+DEV_STALL = 0x100
 MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
 
-K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_COUNT = range(7)
+(K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_WALK_RPE,
+ K_COUNT) = range(8)
 KERNEL_NAMES = {K_WALK: "walk", K_RPE_COUNT: "rpe_count", K_RPE_FILL: "rpe_fill",
-                K_JOIN_COUNT: "join_count", K_JOIN_FILL: "join_fill", K_SCAN: "scan"}
+                K_JOIN_COUNT: "join_count", K_JOIN_FILL: "join_fill", K_SCAN: "scan",
+                K_WALK_RPE: "walk_rpe"}
 
 _vp = ctypes.c_void_p
 _i32, _i64, _u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
@@ -37,8 +40,12 @@ SIGNATURES = {
                                           _u64, _vp, _vp]),
     "surel_build_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _vp, _vp,
                                        _vp, ctypes.POINTER(_i64)]),
+    "surel_sample_walks_rpe": (ctypes.c_int, [_vp, _vp, _vp, _i32, _i64, _vp, _i64, _i32, _i32,
+                                              _u64, _vp, _i64, _vp, _vp, _vp,
+                                              ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "surel_set_spin_limit": (ctypes.c_int, [_vp, ctypes.c_uint32]),
     "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
     "surel_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
     "surel_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -112,6 +119,11 @@ class Context:
         if rc not in (OK, E_DEVICE):
             raise SurelError(rc, "surel_check")
         return flags.value
+
+    def set_spin_limit(self, spins: int) -> None:
+        rc = load().surel_set_spin_limit(self._h, spins)
+        if rc != OK:
+            raise SurelError(rc, "surel_set_spin_limit")
 
     def profile(self, on: bool) -> None:
         rc = load().surel_profile_enable(self._h, 1 if on else 0)
@@ -205,6 +217,42 @@ def build_rpe(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int | N
     if rc != OK:
         raise SurelError(rc, "surel_build_rpe")
     return off, ids[:rows], cnt[:rows]
+
+
+def sample_walks_rpe_raw(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                         seeds: torch.Tensor, M: int, m: int, rng_seed: int, walks: torch.Tensor,
+                         cap_rows: int, rpe_off: torch.Tensor, rpe_ids: torch.Tensor | None,
+                         rpe_cnt: torch.Tensor | None, want_rows: bool = True):
+    """One call of surel_sample_walks_rpe into caller buffers.  Returns (status, rows or None)."""
+    n_seeds = seeds.numel()
+    if walks.numel() != n_seeds * M * (m + 1):
+        raise ValueError("walks has the wrong size")
+    rows = _i64(-1)
+    rc = load().surel_sample_walks_rpe(
+        ctx.handle, _ptr(row_ptr, torch.int32, "row_ptr"), _ptr(col_idx, torch.int32, "col_idx"),
+        row_ptr.numel() - 1, col_idx.numel(), _ptr(seeds, torch.int32, "seeds"), n_seeds, M, m,
+        _u64(rng_seed), _ptr(walks, torch.int32, "walks"), cap_rows,
+        _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), ctypes.byref(rows) if want_rows else None)
+    return rc, (rows.value if want_rows else None)
+
+
+def sample_walks_rpe(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                     seeds: torch.Tensor, M: int, m: int, rng_seed: int = 0):
+    """(walks, rpe_off, rpe_ids, rpe_cnt) from the fused kernel; the table is allocated at the
+    ``rpe_rows_bound`` size and returned as views of its first R rows."""
+    n_seeds = seeds.numel()
+    dev = row_ptr.device
+    walks = torch.empty((n_seeds, M, m + 1), dtype=torch.int32, device=dev)
+    cap_rows = rpe_rows_bound(n_seeds, M, m)
+    off = torch.empty(n_seeds + 1, dtype=torch.int64, device=dev)
+    ids = torch.empty(cap_rows, dtype=torch.int32, device=dev)
+    cnt = torch.empty((cap_rows, m + 1), dtype=torch.uint16, device=dev)
+    rc, rows = sample_walks_rpe_raw(ctx, row_ptr, col_idx, seeds, M, m, rng_seed, walks, cap_rows,
+                                    off, ids, cnt)
+    if rc != OK:
+        raise SurelError(rc, "surel_sample_walks_rpe")
+    return walks, off, ids[:rows], cnt[:rows]
 
 
 def join_queries_raw(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,

@@ -13,12 +13,16 @@ struct surel_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     int max_lds_bytes = 0;
+    int n_cu = 0;                 // compute units of the device
+    uint32_t spin_limit = 1u << 22;  // bound of every wait inside the fused walk + RPE kernel
     uint32_t* d_err = nullptr;    // sticky device error word
     int64_t* h_pinned = nullptr;  // 2 x int64 of pinned host memory for small read-backs
     void* d_ws = nullptr;         // grow-only workspace: row counts + scan partials
     size_t ws_bytes = 0;
     void* d_rec = nullptr;        // grow-only workspace: per-edge neighbour records of the walk
     size_t rec_bytes = 0;
+    void* d_lb = nullptr;         // grow-only workspace: look-back words of the fused kernel
+    size_t lb_bytes = 0;
     // optional per-kernel timing (surel_profile_*)
     struct Span {
         int kernel;
@@ -144,6 +148,29 @@ int read_total(surel_ctx* ctx, const int64_t* d_off, int64_t n, int64_t* h_rows)
     return SUREL_OK;
 }
 
+// Room for the walk's per-edge neighbour records when the job is large enough to want them.
+// *records stays null when it is not, or when the device has no room (not an error: the walk
+// then reads the CSR directly).
+int edge_record_space(surel_ctx* ctx, int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m,
+                      void** records) {
+    *records = nullptr;
+    if (!surel::walks_want_records(n_edges, n_seeds, M, m)) return SUREL_OK;
+    const size_t need = (size_t)n_edges * 16;
+    if (need > ctx->rec_bytes) {
+        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+        if (ctx->d_rec) (void)hipFree(ctx->d_rec);
+        ctx->d_rec = nullptr;
+        ctx->rec_bytes = 0;
+        if (hipMalloc(&ctx->d_rec, need) == hipSuccess) {
+            ctx->rec_bytes = need;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    if (ctx->rec_bytes >= need) *records = ctx->d_rec;
+    return SUREL_OK;
+}
+
 int check_walk_shape(int32_t n_nodes, int64_t n_seeds, int32_t M, int32_t m) {
     if (n_nodes < 1 || n_nodes > SUREL_MAX_NODES) return SUREL_E_RANGE;
     if (n_seeds < 0 || n_seeds > 0x7FFFFFFFll) return SUREL_E_RANGE;
@@ -172,6 +199,8 @@ int surel_create(surel_ctx** out, int device, void* hip_stream) {
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     bool ok = hipDeviceGetAttribute(&ctx->max_lds_bytes, hipDeviceAttributeMaxSharedMemoryPerBlock,
                                     device) == hipSuccess;
+    ok = ok && hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount,
+                                     device) == hipSuccess && ctx->n_cu > 0;
     ok = ok && hipMalloc(reinterpret_cast<void**>(&ctx->d_err), 256) == hipSuccess;
     ok = ok && hipMemsetAsync(ctx->d_err, 0, 256, ctx->stream) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 2 * sizeof(int64_t),
@@ -199,6 +228,7 @@ void surel_destroy(surel_ctx* ctx) {
     for (hipEvent_t e : ctx->free_events) (void)hipEventDestroy(e);
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
     if (ctx->d_rec) (void)hipFree(ctx->d_rec);
+    if (ctx->d_lb) (void)hipFree(ctx->d_lb);
     if (ctx->d_err) (void)hipFree(ctx->d_err);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     delete ctx;
@@ -236,22 +266,7 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
     void* records = nullptr;
-    if (surel::walks_want_records(n_edges, n_seeds, M, m)) {
-        const size_t need = (size_t)n_edges * 16;
-        if (need > ctx->rec_bytes) {
-            if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
-            if (ctx->d_rec) (void)hipFree(ctx->d_rec);
-            ctx->d_rec = nullptr;
-            ctx->rec_bytes = 0;
-            // no room for the records is not an error: the walk then reads the CSR directly
-            if (hipMalloc(&ctx->d_rec, need) == hipSuccess) {
-                ctx->rec_bytes = need;
-            } else {
-                (void)hipGetLastError();
-            }
-        }
-        if (ctx->rec_bytes >= need) records = ctx->d_rec;
-    }
+    if (int rc = edge_record_space(ctx, n_edges, n_seeds, M, m, &records)) return rc;
     KernelSpan span(ctx, SUREL_K_WALK);
     hipError_t rc = surel::launch_walks(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
                                         d_seeds, n_seeds, M, m, rng_seed, d_walks, d_set_sizes,
@@ -295,6 +310,55 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
         hrc = surel::launch_rpe_fill(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m,
                                      n_nodes, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt,
                                      ctx->d_err);
+        if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+        if (hrc != hipSuccess) return SUREL_E_HIP;
+    }
+    if (h_rows) {
+        if (int rc = read_total(ctx, d_rpe_off, n_seeds, h_rows)) return rc;
+        if (d_rpe_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
+    }
+    return SUREL_OK;
+}
+
+int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                           int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                           int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                           int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
+                           int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows) {
+    if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
+    if (n_edges < 0 || n_edges > 0x7FFFFFFFll) return SUREL_E_RANGE;
+    if ((int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
+    if (cap_rows < 0) return SUREL_E_RANGE;
+    if (!d_row_ptr || (n_edges > 0 && !d_col_idx) || !d_rpe_off) return SUREL_E_NULL;
+    if (n_seeds > 0 && (!d_seeds || !d_walks)) return SUREL_E_NULL;
+    if ((d_rpe_ids == nullptr) != (d_rpe_cnt == nullptr)) return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (n_seeds == 0) {
+        if (hipMemsetAsync(d_rpe_off, 0, sizeof(int64_t), ctx->stream) != hipSuccess)
+            return SUREL_E_HIP;
+        if (h_rows) return read_total(ctx, d_rpe_off, 0, h_rows);
+        return SUREL_OK;
+    }
+    void* records = nullptr;
+    if (int rc = edge_record_space(ctx, n_edges, n_seeds, M, m, &records)) return rc;
+    const size_t lb_need = (size_t)surel::walk_rpe_lookback_words(n_seeds) * sizeof(uint64_t);
+    if (lb_need > ctx->lb_bytes) {
+        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+        if (ctx->d_lb) (void)hipFree(ctx->d_lb);
+        ctx->d_lb = nullptr;
+        ctx->lb_bytes = 0;
+        if (hipMalloc(&ctx->d_lb, lb_need) != hipSuccess) return SUREL_E_HIP;
+        ctx->lb_bytes = lb_need;
+    }
+    {
+        KernelSpan span(ctx, SUREL_K_WALK_RPE);
+        hipError_t hrc = surel::launch_walk_rpe(
+            ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_row_ptr, d_col_idx, n_nodes, n_edges,
+            d_seeds, n_seeds, M, m, rng_seed, d_walks, cap_rows, d_rpe_off, d_rpe_ids, d_rpe_cnt,
+            records, static_cast<uint64_t*>(ctx->d_lb), ctx->spin_limit, ctx->d_err);
         if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
         if (hrc != hipSuccess) return SUREL_E_HIP;
     }
@@ -353,6 +417,12 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
         if (int rc = read_total(ctx, d_join_off, n_queries, h_rows)) return rc;
         if (d_join_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
     }
+    return SUREL_OK;
+}
+
+int surel_set_spin_limit(surel_ctx* ctx, uint32_t spins) {
+    if (!ctx) return SUREL_E_CTX;
+    ctx->spin_limit = spins;
     return SUREL_OK;
 }
 

@@ -17,6 +17,7 @@ constexpr uint32_t kDevSetTooLarge = 0x10u;
 constexpr uint32_t kDevCapacity = 0x20u;
 constexpr uint32_t kDevBadTable = 0x40u;
 constexpr uint32_t kDevBadSizes = 0x80u;
+constexpr uint32_t kDevStall = 0x100u;
 
 __device__ __forceinline__ int lane_id() {
     return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));

@@ -16,6 +16,24 @@ hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
                         int32_t* set_sizes, void* edge_records, uint32_t* err);
 
+// Expands the CSR into edge_records (16 * n_edges bytes), see walk.hip.
+hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
+                               int32_t n_nodes, int64_t n_edges, void* edge_records);
+
+// walk_rpe.hip.  Walks and the RPE table in one persistent kernel: writes walks,
+// rpe_off[0..n_seeds] and (unless ids is null) the rows.  lb: device scratch of
+// walk_rpe_lookback_words(n_seeds) 64-bit words (cleared by the launch itself).  n_cu: compute
+// units of the device.  spin_limit bounds every wait inside the kernel (kDevStall when one runs
+// out).  Needs M*(m+1) <= 2048 and n_seeds >= 1.
+// hipErrorInvalidValue = the shape does not fit the device's LDS.
+int64_t walk_rpe_lookback_words(int64_t n_seeds);
+hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* row_ptr,
+                           const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
+                           const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
+                           uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
+                           int32_t* ids, uint16_t* cnt, void* edge_records, uint64_t* lb,
+                           uint32_t spin_limit, uint32_t* err);
+
 // rpe.hip.  launch_rpe_count: set_sizes[i] = distinct nodes in walks[i].  launch_rpe_fill:
 // writes the rows of every seed at rpe_off[i] (seeds whose block would pass cap_rows, or whose
 // row count differs from rpe_off[i+1]-rpe_off[i], are skipped and flagged).

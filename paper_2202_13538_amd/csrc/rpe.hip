@@ -10,89 +10,11 @@
 // rows.  Rows are assembled in LDS and streamed out contiguously at the seed's offset.
 #include "device_util.h"
 #include "distinct.h"
+#include "rpe_rows.h"
+#include "wave_sort.h"
 #include "kernels.h"
 
 namespace surel {
-
-constexpr uint32_t kPadKey = 0xFFFFFFFFu;
-
-// Compare-exchange with the lane `lane ^ MASK`: the lower lane of a pair keeps the smaller
-// key.  `y < x` decides for a lower lane, its negation for an upper one (equal keys need
-// no exchange, so either answer is right for them).
-template <int MASK>
-__device__ __forceinline__ uint32_t exchange(uint32_t x, uint32_t y, bool upper) {
-    const bool take = (y < x) != upper;
-    return take ? y : x;
-}
-
-// Sorts the 64*E keys of a wave ascending.  Sort position p = lane*E + r (lane-blocked).
-// Bitonic merge sort written with ascending comparators only: a merge of two sorted runs
-// starts with a mirror step (p against p ^ (k-1)) and continues with half-cleaners
-// (p against p ^ j, j = k/4 .. 1).  Strides below E stay inside a lane (register to
-// register); the others exchange registers between lanes.
-template <int E, int K>
-__device__ __forceinline__ void sort_merge_level(uint32_t (&x)[E], int lane) {
-    if constexpr (K <= E) {
-#pragma unroll
-        for (int r = 0; r < E; ++r) {
-            const int q = r ^ (K - 1);
-            if (q > r) {
-                const uint32_t a = min(x[r], x[q]);
-                const uint32_t b = max(x[r], x[q]);
-                x[r] = a;
-                x[q] = b;
-            }
-        }
-    } else {
-        constexpr int kLaneMask = K / E - 1;
-        const bool upper = (lane & (K / (2 * E))) != 0;
-        uint32_t y[E];
-#pragma unroll
-        for (int r = 0; r < E; ++r) y[r] = lane_xor<kLaneMask>(x[E - 1 - r], lane);
-#pragma unroll
-        for (int r = 0; r < E; ++r) x[r] = exchange<kLaneMask>(x[r], y[r], upper);
-    }
-}
-
-template <int E, int J>
-__device__ __forceinline__ void sort_half_cleaner(uint32_t (&x)[E], int lane) {
-    if constexpr (J >= 1) {
-        if constexpr (J < E) {
-#pragma unroll
-            for (int r = 0; r < E; ++r) {
-                if ((r & J) == 0) {
-                    const uint32_t a = min(x[r], x[r | J]);
-                    const uint32_t b = max(x[r], x[r | J]);
-                    x[r] = a;
-                    x[r | J] = b;
-                }
-            }
-        } else {
-            constexpr int kLaneMask = J / E;
-            const bool upper = (lane & kLaneMask) != 0;
-#pragma unroll
-            for (int r = 0; r < E; ++r) {
-                const uint32_t y = lane_xor<kLaneMask>(x[r], lane);
-                x[r] = exchange<kLaneMask>(x[r], y, upper);
-            }
-        }
-        sort_half_cleaner<E, J / 2>(x, lane);
-    }
-}
-
-template <int E, int K>
-__device__ __forceinline__ void sort_levels(uint32_t (&x)[E], int lane) {
-    if constexpr (K <= kWave * E) {
-        sort_merge_level<E, K>(x, lane);
-        sort_half_cleaner<E, K / 4>(x, lane);
-        sort_levels<E, K * 2>(x, lane);
-    }
-}
-
-template <int E>
-__device__ __forceinline__ void wave_sort(uint32_t (&x)[E], int lane) {
-    sort_levels<E, 2>(x, lane);
-}
 
 constexpr int kRpeWaves = 4;  // waves (seeds) per workgroup
 
@@ -145,7 +67,6 @@ __global__ __launch_bounds__(kWaves* kWave) void rpe_fill_kernel(
     // per-wave LDS: P ids (uint32), then P*L counts (uint16)
     uint32_t* ids_lds = lds32 + wave * (P + (P * L) / 2);
     uint32_t* cnt_lds32 = ids_lds + P;
-    uint16_t* cnt_lds = reinterpret_cast<uint16_t*>(cnt_lds32);
 
     const int64_t off = rpe_off[i];
     const int64_t given_rows = rpe_off[i + 1] - off;
@@ -173,88 +94,19 @@ __global__ __launch_bounds__(kWaves* kWave) void rpe_fill_kernel(
 
     wave_sort<E>(x, lane);
 
-    // keys before this lane's first and after its last (pad where there is none: a pad key
-    // differs from every valid key in both id and position)
-    uint32_t before = (uint32_t)__shfl_up((int)x[E - 1], 1, kWave);
-    uint32_t after = (uint32_t)__shfl_down((int)x[0], 1, kWave);
-    if (lane == 0) before = kPadKey;
-    if (lane == kWave - 1) after = kPadKey;
-
-    // rows: one per distinct id
-    uint32_t n_head = 0;
-    int32_t last_start = -1;  // sort position of the last key-run start inside this lane
-    {
-        uint32_t prev = before;
-#pragma unroll
-        for (int r = 0; r < E; ++r) {
-            const bool valid = x[r] != kPadKey;
-            n_head += (valid && (x[r] >> 4) != (prev >> 4)) ? 1u : 0u;
-            if (valid && x[r] != prev) last_start = lane * E + r;
-            prev = x[r];
-        }
-    }
-    const uint32_t incl = wave_incl_sum(n_head);
-    const int32_t n_rows = (int32_t)wave_bcast_u32(incl, kWave - 1);
+    const RpeRowScan sc = rpe_scan_rows<E>(x, lane);
 
     // the layout was made from set sizes; a size that does not match the walks (sizes passed
     // in for other walks) must not make blocks overlap
-    if ((int64_t)n_rows != given_rows) {
+    if ((int64_t)sc.n_rows != given_rows) {
         if (lane == 0) atomicOr(err, kDevBadSizes);
         return;
     }
-    if (off + n_rows > cap_rows) {
+    if (off + sc.n_rows > cap_rows) {
         if (lane == 0) atomicOr(err, kDevCapacity);
         return;
     }
-
-    // start of the key run that is open when this lane begins
-    int32_t run_start = __shfl_up(wave_incl_max(last_start), 1, kWave);
-    if (lane == 0) run_start = -1;
-
-    const int n_cnt = n_rows * L;
-    for (int t = lane; t < (n_cnt + 1) / 2; t += kWave) cnt_lds32[t] = 0u;
-    wave_sync();
-    {
-        uint32_t prev = before;
-        int32_t row = (int32_t)(incl - n_head) - 1;  // row of the last key before this lane
-#pragma unroll
-        for (int r = 0; r < E; ++r) {
-            const uint32_t key = x[r];
-            const uint32_t next = (r + 1 < E) ? x[(r + 1 < E) ? r + 1 : r] : after;
-            const bool valid = key != kPadKey;
-            const int32_t e = lane * E + r;
-            if (valid && (key >> 4) != (prev >> 4)) {
-                row += 1;
-                ids_lds[row] = key >> 4;
-            }
-            if (valid && key != prev) run_start = e;
-            if (valid && key != next)
-                cnt_lds[row * L + (int)(key & 15u)] = (uint16_t)(e - run_start + 1);
-            prev = key;
-        }
-    }
-    wave_sync();
-
-    // stream the block out: ids as dwords, counts as dwords where the destination allows
-    int32_t* out_ids = ids + off;
-    for (int t = lane; t < n_rows; t += kWave) out_ids[t] = (int32_t)ids_lds[t];
-
-    const int64_t d0 = off * L;  // first destination element (uint16 units)
-    const int head = (int)(d0 & 1);
-    uint16_t* out_cnt = cnt + d0;
-    if (head && lane == 0) out_cnt[0] = cnt_lds[0];
-    const int n_pair = (n_cnt - head) / 2;
-    uint32_t* out32 = reinterpret_cast<uint32_t*>(out_cnt + head);
-    if (head == 0) {
-        for (int t = lane; t < n_pair; t += kWave) out32[t] = cnt_lds32[t];
-    } else {
-        for (int t = lane; t < n_pair; t += kWave) {
-            const uint32_t a = cnt_lds[1 + 2 * t];
-            const uint32_t b = cnt_lds[2 + 2 * t];
-            out32[t] = a | (b << 16);
-        }
-    }
-    if (((n_cnt - head) & 1) && lane == 0) out_cnt[n_cnt - 1] = cnt_lds[n_cnt - 1];
+    rpe_write_rows<E>(x, sc, lane, L, ids_lds, cnt_lds32, off, ids, cnt);
 }
 
 hipError_t launch_rpe_count(hipStream_t stream, const int32_t* walks, int64_t n_seeds, int32_t M,

@@ -1,6 +1,7 @@
 // Walk sampling (Sec. 3.2 "Walk Sampling"; Algorithm 1, walk step).
 //
-// One wavefront per seed; a lane is one walk, ceil(M/64) passes.  A pass keeps its 64
+// One wavefront per seed; a lane moves two walks at a time (two independent gathers in
+// flight per lane), ceil(M/128) passes.  A pass keeps its 128
 // walks in LDS ([walk][position]) and then streams them out as one contiguous block, so
 // the global stores are full-width instead of lane-strided.  Walk rows are written with
 // non-temporal stores: they are not read again by this kernel and should not push the
@@ -20,10 +21,12 @@
 #include "device_util.h"
 #include "distinct.h"
 #include "kernels.h"
+#include "walk_core.h"
 
 namespace surel {
 
 constexpr int kWalkWavesPerBlock = 4;
+constexpr int kWalkChains = 2;  // walks a lane moves at a time
 
 // rec[e] = (col_idx[e], row_ptr[col_idx[e]], degree of col_idx[e], 0); an entry that names no
 // node, or whose row is malformed, gets id -1 (the walker will stay in place and flag it).
@@ -56,9 +59,9 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
     if (i >= n_seeds) return;  // whole waves leave; no block-wide barrier is used below
 
     const int L = m + 1;
-    const int per_wave = kWave * L + (kCount ? slots : 0);
+    const int per_wave = kWalkChains * kWave * L + (kCount ? slots : 0);
     int32_t* stage = lds + wave * per_wave;
-    uint32_t* table = reinterpret_cast<uint32_t*>(stage + kWave * L);
+    uint32_t* table = reinterpret_cast<uint32_t*>(stage + kWalkChains * kWave * L);
     int32_t* out_seed = walks + i * (int64_t)M * L;
 
     const int32_t u = __builtin_amdgcn_readfirstlane(seeds[i]);
@@ -79,61 +82,25 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
         n_distinct = distinct_insert(table, slots, (uint32_t)u, lane == 0);
     }
 
-    bool bad_graph = false;
-    // the seed's own row (wave-uniform); a malformed row counts as degree 0
-    int32_t u_lo = row_ptr[u];
-    int32_t u_deg = row_ptr[u + 1] - u_lo;
-    if (u_lo < 0 || u_deg < 0 || (int64_t)u_lo + u_deg > n_edges) {
-        bad_graph = true;
-        u_deg = 0;
-    }
-    for (int w0 = 0; w0 < M; w0 += kWave) {
-        const int w = w0 + lane;
-        const bool active = w < M;
-        int32_t cur = u;
-        int32_t cur_lo = u_lo;     // row of `cur` (kRec only)
-        int32_t cur_deg = u_deg;
-        stage[lane * L] = u;
-        for (int s0 = 1; s0 <= m; s0 += 4) {
-            uint32_t r[4];
-            philox4x32_10((uint32_t)u, (uint32_t)w, (uint32_t)((s0 - 1) >> 2), 0u, key0, key1, r);
+    const WalkGraph g{row_ptr, col_idx, rec, n_nodes, n_edges};
+    int32_t u_lo, u_deg;
+    bool bad_graph = seed_row(g, u, &u_lo, &u_deg);
+    for (int w0 = 0; w0 < M; w0 += kWalkChains * kWave) {
+        int w[kWalkChains];
+        bool active[kWalkChains];
+        int32_t* row[kWalkChains];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int s = s0 + j;
-                if (s <= m) {
-                    if (kRec) {
-                        if (active && cur_deg > 0) {
-                            const int4 nb = rec[(int64_t)cur_lo + (int64_t)(r[j] % (uint32_t)cur_deg)];
-                            if (nb.x < 0) {
-                                bad_graph = true;
-                            } else {
-                                cur = nb.x;
-                                cur_lo = nb.y;
-                                cur_deg = nb.z;
-                            }
-                        }
-                    } else if (active) {
-                        const int32_t lo = row_ptr[cur];
-                        const int32_t hi = row_ptr[cur + 1];
-                        if (lo < 0 || hi < lo || (int64_t)hi > n_edges) {
-                            bad_graph = true;
-                        } else if (hi > lo) {
-                            const uint32_t deg = (uint32_t)(hi - lo);
-                            const int32_t nxt = col_idx[(int64_t)lo + (int64_t)(r[j] % deg)];
-                            if ((uint32_t)nxt >= (uint32_t)n_nodes) {
-                                bad_graph = true;
-                            } else {
-                                cur = nxt;
-                            }
-                        }
-                    }
-                    stage[lane * L + s] = cur;
-                    if (kCount) n_distinct += distinct_insert(table, slots, (uint32_t)cur, active);
-                }
-            }
+        for (int c = 0; c < kWalkChains; ++c) {
+            w[c] = w0 + c * kWave + lane;
+            active[c] = w[c] < M;
+            row[c] = stage + (c * kWave + lane) * L;
         }
+        bad_graph |= walk_many<kRec, kWalkChains>(
+            g, u, u_lo, u_deg, w, active, m, key0, key1, row, [&](int c, int32_t node) {
+                if (kCount) n_distinct += distinct_insert(table, slots, (uint32_t)node, active[c]);
+            });
         wave_sync();
-        const int total = min(kWave, M - w0) * L;
+        const int total = min(kWalkChains * kWave, M - w0) * L;
         int32_t* out = out_seed + (int64_t)w0 * L;
         for (int t = lane; t < total; t += kWave) __builtin_nontemporal_store(stage[t], out + t);
         wave_sync();
@@ -156,7 +123,7 @@ static hipError_t launch_walks_cfg(hipStream_t stream, const int32_t* row_ptr,
                                    int32_t* set_sizes, uint32_t* err) {
     const int64_t blocks = (n_seeds + kWalkWavesPerBlock - 1) / kWalkWavesPerBlock;
     const int slots = kCount ? distinct_slots(1 + M * m) : 0;
-    const size_t lds_bytes = (size_t)kWalkWavesPerBlock * (kWave * (m + 1) + slots) * 4;
+    const size_t lds_bytes = (size_t)kWalkWavesPerBlock * (kWalkChains * kWave * (m + 1) + slots) * 4;
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(
             reinterpret_cast<const void*>(walk_kernel<kCount, kRec>),
@@ -171,6 +138,16 @@ static hipError_t launch_walks_cfg(hipStream_t stream, const int32_t* row_ptr,
     return hipGetLastError();
 }
 
+hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
+                               int32_t n_nodes, int64_t n_edges, void* edge_records) {
+    if (n_edges <= 0) return hipSuccess;
+    const int threads = 256;
+    hipLaunchKernelGGL(edge_record_kernel, dim3((unsigned)((n_edges + threads - 1) / threads)),
+                       dim3(threads), 0, stream, row_ptr, col_idx, n_nodes, n_edges,
+                       static_cast<int4*>(edge_records));
+    return hipGetLastError();
+}
+
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
@@ -178,10 +155,8 @@ hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_
     if (n_seeds == 0) return hipSuccess;
     int4* rec = static_cast<int4*>(edge_records);
     if (rec != nullptr) {
-        const int threads = 256;
-        hipLaunchKernelGGL(edge_record_kernel, dim3((unsigned)((n_edges + threads - 1) / threads)),
-                           dim3(threads), 0, stream, row_ptr, col_idx, n_nodes, n_edges, rec);
-        if (hipError_t rc = hipGetLastError(); rc != hipSuccess) return rc;
+        hipError_t rc = launch_edge_records(stream, row_ptr, col_idx, n_nodes, n_edges, rec);
+        if (rc != hipSuccess) return rc;
     }
 #define SUREL_WALK_ARGS \
     stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m, rng_seed, walks, set_sizes, err

@@ -144,6 +144,41 @@ def test_build_rpe_argument_checks(lib, kw, want):
     assert lib.surel_build_rpe(*rpe_args(**kw)) == want
 
 
+def fused_args(**kw):
+    a = dict(ctx=NULL, row_ptr=P, col_idx=P, n_nodes=100, n_edges=500, seeds=P, n_seeds=10,
+             M=50, m=4, rng_seed=0, walks=P, cap_rows=1000, off=P, ids=P, cnt=P, h_rows=NULL)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "row_ptr", "col_idx", "n_nodes", "n_edges", "seeds", "n_seeds",
+                           "M", "m", "rng_seed", "walks", "cap_rows", "off", "ids", "cnt",
+                           "h_rows")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(n_edges=-1), binding.E_RANGE),
+    (dict(n_seeds=-1), binding.E_RANGE),
+    (dict(M=0), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(M=400, m=4), binding.E_CTX),
+    (dict(M=410, m=4), binding.E_RANGE),          # the fused kernel sorts M*(m+1) keys per seed
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(row_ptr=NULL), binding.E_NULL),
+    (dict(col_idx=NULL), binding.E_NULL),
+    (dict(col_idx=NULL, n_edges=0), binding.E_CTX),
+    (dict(seeds=NULL), binding.E_NULL),
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(off=NULL, seeds=NULL, walks=NULL, n_seeds=0), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(cnt=NULL), binding.E_NULL),
+    (dict(ids=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),
+    (dict(cnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
+])
+def test_sample_walks_rpe_argument_checks(lib, kw, want):
+    assert lib.surel_sample_walks_rpe(*fused_args(**kw)) == want
+
+
 def join_args(**kw):
     a = dict(ctx=NULL, off=P, ids=P, cnt=P, n_blocks=100, m=4, max_set=201, queries=P, n_q=10,
              k=2, cap_rows=1000, joff=P, jids=P, jcnt=P, h_rows=NULL)

@@ -75,6 +75,13 @@ def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
         assert_table_equal(out["rpe"], table, f"rpe (sizes from walks: {with_sizes})")
         if queries is not None:
             assert_table_equal(out["join"], joined, "join")
+    # the fused walk + RPE kernel gives the same walks and the same table
+    d_seeds = dev(np.asarray(seeds, dtype=np.int32))
+    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, dev(rp), dev(ci), d_seeds, M, m,
+                                                            rng_seed)
+    assert ctx.check() == 0
+    assert np.array_equal(f_walks.cpu().numpy(), w), "fused: walks differ"
+    assert_table_equal((f_off, f_ids, f_cnt), table, "fused rpe")
     return out
 
 
@@ -260,6 +267,89 @@ def test_rpe_capacity_overflow_is_reported_and_nothing_is_written_past_it(ctx):
     assert np.array_equal(cnt_h[:last], want_cnt[:last])
 
 
+def test_fused_bad_seed_capacity_and_count_only(ctx):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    M, m, L = wl.M, wl.m, wl.m + 1
+    seeds = np.arange(64, dtype=np.int32)
+    seeds[7] = 1000                                          # not a node
+    seeds[20] = -1
+    good = np.ones(64, dtype=bool)
+    good[[7, 20]] = False
+    w = oracle.sample_walks(rp, ci, seeds[good], M, m, 3)
+    want_off, want_ids, want_cnt = oracle.build_rpe(w)
+    sizes = np.zeros(64, dtype=np.int64)
+    sizes[good] = np.diff(want_off)
+    full_off = np.concatenate([[0], np.cumsum(sizes)])
+    total = int(full_off[-1])
+    d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(seeds)
+    walks = torch.empty((64, M, L), dtype=torch.int32, device="cuda")
+    off = torch.empty(65, dtype=torch.int64, device="cuda")
+    # offsets and total only
+    rc, rows = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, 3, walks, 0, off,
+                                            None, None)
+    assert rc == binding.OK and rows == total
+    assert ctx.check() == binding.DEV_BAD_SEED
+    assert np.array_equal(off.cpu().numpy(), full_off)
+    wh = walks.cpu().numpy()
+    assert (wh[7] == -1).all() and (wh[20] == -1).all() and np.array_equal(wh[good], w)
+    # a table that is too small: complete offsets, nothing written at or past cap_rows
+    cap = total // 2
+    ids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((total, L), 0x7777, dtype=torch.int16, device="cuda").view(torch.uint16)
+    rc, rows = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, 3, walks, cap, off,
+                                            ids, cnt)
+    assert rc == binding.E_CAPACITY and rows == total
+    assert ctx.check() == binding.DEV_BAD_SEED | binding.DEV_CAPACITY
+    assert np.array_equal(off.cpu().numpy(), full_off)
+    ids_h, cnt_h = ids.cpu().numpy(), host_u16(cnt)
+    assert (ids_h[cap:] == -7).all() and (cnt_h[cap:] == 0x7777).all()
+    last = int(full_off[1:][full_off[1:] <= cap].max())
+    assert np.array_equal(ids_h[:last], want_ids[:last])
+    assert np.array_equal(cnt_h[:last], want_cnt[:last])
+    # no seeds at all
+    rc, rows = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds[:0], M, m, 3, walks[:0], 0,
+                                            off[:1], None, None)
+    assert rc == binding.OK and rows == 0 and int(off[0]) == 0
+
+
+def test_fused_kernel_waits_are_bounded(ctx):
+    # with a spin limit of zero every wait inside the fused kernel gives up at once: the kernel
+    # must still end, say so, and write nothing out of place; the default limit then gives the
+    # right table again
+    wl = synth.Workload("t", "rmat", 4096, 30000, 0.0, 50, 4, 0, 2, "uniform", graph_seed=9)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(wl.n_nodes, dtype=np.int32)
+    d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(seeds)
+    M, m, L = wl.M, wl.m, wl.m + 1
+    cap = binding.rpe_rows_bound(seeds.size, M, m)
+    walks = torch.empty((seeds.size, M, L), dtype=torch.int32, device="cuda")
+    off = torch.empty(seeds.size + 1, dtype=torch.int64, device="cuda")
+    ids = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((cap, L), dtype=torch.int16, device="cuda").view(torch.uint16)
+    ctx.set_spin_limit(0)
+    try:
+        rc, _ = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, 0, walks, cap, off,
+                                             ids, cnt, want_rows=False)
+        assert rc == binding.OK
+        flags = ctx.check()
+    finally:
+        ctx.set_spin_limit(1 << 22)
+    assert flags & ~binding.DEV_STALL == 0
+    w = oracle.sample_walks(rp, ci, seeds, M, m, 0)
+    want = oracle.build_rpe(w)
+    if flags == 0:
+        assert_table_equal((off, ids[:int(off[-1])], cnt[:int(off[-1])]), want, "rpe")
+    else:
+        # whatever was written is a correct prefix of the table or untouched memory
+        ids_h = ids.cpu().numpy()[:want[1].size]
+        assert ((ids_h == want[1]) | (ids_h == -7)).all()
+    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, d_seeds, M, m, 0)
+    assert ctx.check() == 0
+    assert np.array_equal(f_walks.cpu().numpy(), w)
+    assert_table_equal((f_off, f_ids, f_cnt), want, "rpe after the limit was restored")
+
+
 def test_join_problems_are_flagged(ctx):
     wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
     rp, ci = synth.make_graph(wl)
@@ -343,6 +433,16 @@ def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
     assert rc == binding.OK and torch.equal(off, off2) and rows2 == int(off[-1])
     R = int(off[-1])
     print(f"[{name}] walks + rpe done: R={R} rows", flush=True)
+    # the fused kernel, whole output against the two-call path
+    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, d_seeds, M, m,
+                                                            wl.rng_seed)
+    assert ctx.check() == 0
+    assert torch.equal(f_walks, walks), "fused: walks differ"
+    assert torch.equal(f_off, off), "fused: offsets differ"
+    assert torch.equal(f_ids, ids[:R]), "fused: ids differ"
+    assert torch.equal(f_cnt.view(torch.int16), cnt[:R].view(torch.int16)), "fused: counts differ"
+    del f_walks, f_off, f_ids, f_cnt
+    print(f"[{name}] fused walk+rpe equals the two-call path", flush=True)
 
     rng = np.random.default_rng(12345)
     deg = np.diff(rp)
