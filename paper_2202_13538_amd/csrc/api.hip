@@ -394,7 +394,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
     hipError_t hrc;
     {
         KernelSpan span(ctx, SUREL_K_JOIN_COUNT);
-        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
+        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off, d_rpe_ids, d_rpe_cnt,
                                  n_blocks, m, max_set, d_queries, n_queries, k, counts, nullptr, 0,
                                  nullptr, nullptr, ctx->d_err);
     }
@@ -407,7 +407,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
     if (hrc != hipSuccess) return SUREL_E_HIP;
     if (d_join_ids) {
         KernelSpan span(ctx, SUREL_K_JOIN_FILL);
-        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, d_rpe_off, d_rpe_ids, d_rpe_cnt,
+        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off, d_rpe_ids, d_rpe_cnt,
                                  n_blocks, m, max_set, d_queries, n_queries, k, nullptr, d_join_off,
                                  cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
         if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;

@@ -3,8 +3,9 @@
 // vectors in tuple order, zeros where the node is absent from a set.
 //
 // Two launches of one kernel: the first only counts every query's union rows, an exclusive
-// scan turns the counts into join_off, the second writes the rows.  One wavefront per query;
-// the K sorted id lists are staged in LDS.
+// scan turns the counts into join_off, the second writes the rows.  A wavefront handles one
+// query at a time and loops over the queries (the grid is as large as the device holds at
+// once); the K sorted id lists are staged in LDS.
 //
 // Which union row a node lands in, and which table rows feed it ("sources"):
 //   - pairs: a merge path.  Lane l owns merged positions [l*VT, (l+1)*VT): a binary search on
@@ -13,10 +14,14 @@
 //   - triples: ranks.  A row is owned by the first list that holds its node; its position is
 //     #{a in list 0 : a < x} + sum over j >= 1 of #{b in list j : b < x, b in no earlier list},
 //     each term a lower bound in LDS plus a lookup in a prefix count of "new" elements.
-// Count vectors: 64 union rows at a time, a lane moves one (row, list) vector from the table
-// (or zeros) into an LDS tile laid out like the output, and the tile is streamed out as
-// whole dwords.  The kernel keeps its LDS footprint small on purpose: with the vectors read
-// in place it is the number of waves in flight, not LDS staging, that hides the latency.
+// Count vectors.  For the common walk lengths (m + 1 = 4 or 5 counts per vector) a lane takes
+// one union row: it gathers the row's K vectors from the table (zeros where the node is
+// absent), packs them into the row's K*L/2 words in registers, and the row goes out either
+// straight from the registers (vectors of whole words) or through a small LDS tile that is
+// streamed out as whole words (pairs of 5-count vectors, whose rows straddle words).  Other
+// shapes take a generic path: a lane moves one (row, list) vector into an LDS tile laid out
+// like the output.  The kernel keeps its LDS footprint small on purpose: the vectors are read
+// in place, and it is the number of waves in flight that hides the latency.
 #include "device_util.h"
 #include "kernels.h"
 
@@ -51,13 +56,26 @@ struct JoinLds {
     int total;
 };
 
-__host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L, bool fill) {
+// Rows whose K*L counts fill whole 32-bit words are put together in registers and written
+// straight to the output, one lane per row; other shapes go through the LDS tile.
+__host__ __device__ constexpr bool join_rows_direct(int K, int LT) {
+    return LT > 0 && (K * LT) % 2 == 0;
+}
+
+// The LDS tile is needed by the generic path and by pairs whose count vectors have an odd
+// number of entries (their rows are put together in the tile before they go out).
+__host__ __device__ constexpr bool join_uses_tile(int K, int LT) {
+    return !join_rows_direct(K, LT) || (K == 2 && LT % 2 == 1);
+}
+
+__host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L, bool fill,
+                                                      bool tile) {
     JoinLds o{};
     o.ids = 0;
     o.new_pre = o.ids + K * max_set;
     o.src = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
     o.tile = o.src + (fill ? (K * K * max_set + 1) / 2 : 0);
-    o.total = o.tile + (fill ? (kJoinChunkRows * K * L + 1) / 2 : 0);
+    o.total = o.tile + (fill && tile ? (kJoinChunkRows * K * L + 1) / 2 : 0);
     return o;
 }
 
@@ -225,21 +243,15 @@ __device__ __forceinline__ void zero_vector(uint16_t* dst, int L) {
 // kFill = false: write counts[q] only; kFill = true: join_off is complete, write the rows.
 // LT = m+1 at compile time for the common walk lengths, 0 = any.
 template <int K, int WPB, bool kFill, int LT>
-__global__ __launch_bounds__(WPB* kWave) void join_kernel(
-    const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids,
-    const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
-    const int32_t* __restrict__ queries, int64_t n_queries, int32_t* __restrict__ counts,
-    const int64_t* __restrict__ join_off, int64_t cap_rows, int32_t* __restrict__ out_ids,
-    uint16_t* __restrict__ out_cnt, uint32_t* __restrict__ err) {
-    extern __shared__ uint32_t lds32[];
-
-    const int lane = lane_id();
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t q = (int64_t)blockIdx.x * WPB + wave;
-    if (q >= n_queries) return;  // whole waves leave; no block-wide barrier is used below
+__device__ __forceinline__ void join_one_query(
+    uint32_t* lds32, int lane, int wave, int64_t q, const int64_t* __restrict__ rpe_off,
+    const int32_t* __restrict__ rpe_ids, const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks,
+    int32_t m, int32_t max_set, const int32_t* __restrict__ queries,
+    int32_t* __restrict__ counts, const int64_t* __restrict__ join_off, int64_t cap_rows,
+    int32_t* __restrict__ out_ids, uint16_t* __restrict__ out_cnt, uint32_t* __restrict__ err) {
 
     const int L = LT > 0 ? LT : m + 1;
-    const JoinLds lay = join_lds_layout(K, max_set, L, kFill);
+    const JoinLds lay = join_lds_layout(K, max_set, L, kFill, join_uses_tile(K, LT));
     uint32_t* base = lds32 + wave * lay.total;
     uint32_t* ids_lds = base + lay.ids;
     uint16_t* new_pre = reinterpret_cast<uint16_t*>(base + lay.new_pre);
@@ -307,6 +319,94 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     }
     wave_sync();
 
+    if constexpr (join_rows_direct(K, LT)) {
+        // one lane per union row: the K count vectors (or zeros) are packed into the row's
+        // K*L/2 words in registers and stored at the row's place
+        constexpr int kWords = K * LT / 2;
+        uint32_t* out_words = reinterpret_cast<uint32_t*>(out_cnt) + off * kWords;
+        if constexpr (K != 2) {
+            // larger tuples: most vectors are absent, so a lane loads only those its row has
+            for (int r = lane; r < n_out; r += kWave) {
+                uint16_t v[K * LT];
+                uint32_t id = 0;
+#pragma unroll
+                for (int j = K - 1; j >= 0; --j) {
+                    const uint16_t sj = src[j * src_stride + r];
+                    // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
+                    const bool present = (int)sj < n[j];
+                    const uint16_t* from = rpe_cnt + (lo[j] + (present ? sj : 0)) * LT;
+#pragma unroll
+                    for (int e = 0; e < LT; ++e) v[j * LT + e] = 0;
+                    if (present) {
+                        id = ids_lds[j * max_set + sj];
+#pragma unroll
+                        for (int e = 0; e < LT; ++e) v[j * LT + e] = from[e];
+                    }
+                }
+                out_ids[off + r] = (int32_t)id;
+                uint32_t* row_words = out_words + (int64_t)r * kWords;
+#pragma unroll
+                for (int d = 0; d < kWords; ++d)
+                    row_words[d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+            }
+            return;
+        }
+        // pairs: one round of 64 rows at a time
+        for (int r0 = 0; r0 < n_out; r0 += kWave) {
+            const int r = min(r0 + lane, n_out - 1);
+            uint16_t v[K * LT];
+            uint32_t id = 0;
+            bool present[K];
+#pragma unroll
+            for (int j = K - 1; j >= 0; --j) {
+                const uint16_t sj = src[j * src_stride + r];
+                // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
+                present[j] = (int)sj < n[j];
+                const uint32_t id_j = ids_lds[j * max_set + (present[j] ? sj : 0)];
+                if (present[j]) id = id_j;
+                // unconditional loads, from the table's first row where the list has no row for
+                // the node: a branch would make every load wait for the one before it
+                const uint16_t* from = present[j] ? rpe_cnt + (lo[j] + sj) * LT : rpe_cnt;
+#pragma unroll
+                for (int e = 0; e < LT; ++e) v[j * LT + e] = from[e];
+            }
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+#pragma unroll
+                for (int e = 0; e < LT; ++e)
+                    if (!present[j]) v[j * LT + e] = 0;
+            }
+            const bool live = r0 + lane < n_out;
+            if (live) out_ids[off + r] = (int32_t)id;
+            if constexpr (LT % 2 == 0) {
+                // count vectors of whole words: a lane's row is stored from its registers (the
+                // rows of neighbouring lanes adjoin, so the stores of a wave are contiguous)
+                if (live) {
+                    uint32_t* row_words = out_words + (int64_t)r * kWords;
+#pragma unroll
+                    for (int d = 0; d < kWords; ++d)
+                        row_words[d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+                }
+            } else {
+                // an odd number of 16-bit counts per list: the rows are put together in an LDS
+                // tile laid out like the output and go out as whole words, lane by lane
+#pragma unroll
+                for (int d = 0; d < kWords; ++d)
+                    tile32[lane * kWords + d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+                wave_sync();
+                const int n_words = min(kWave, n_out - r0) * kWords;
+                uint32_t* dst = out_words + (int64_t)r0 * kWords;
+#pragma unroll
+                for (int d = 0; d < kWords; ++d) {
+                    const int t = d * kWave + lane;
+                    if (t < n_words) dst[t] = tile32[t];
+                }
+                wave_sync();
+            }
+        }
+        return;
+    }
+
     const int KL = K * L;
     for (int r0 = 0; r0 < n_out; r0 += kJoinChunkRows) {
         const int rows = min(kJoinChunkRows, n_out - r0);
@@ -365,25 +465,56 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     }
 }
 
+// Waves loop over the queries (wave w of the grid takes queries w, w + waves, ...): a query is
+// little work, and a grid of one short-lived wave per query is bound by how fast waves can be
+// launched.  No workgroup-wide barrier is used.
+template <int K, int WPB, bool kFill, int LT>
+__global__ __launch_bounds__(WPB* kWave) void join_kernel(
+    const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids,
+    const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+    const int32_t* __restrict__ queries, int64_t n_queries, int32_t* __restrict__ counts,
+    const int64_t* __restrict__ join_off, int64_t cap_rows, int32_t* __restrict__ out_ids,
+    uint16_t* __restrict__ out_cnt, uint32_t* __restrict__ err) {
+    extern __shared__ uint32_t lds32[];
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t stride = (int64_t)gridDim.x * WPB;
+    for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
+        join_one_query<K, WPB, kFill, LT>(lds32, lane, wave, q, rpe_off, rpe_ids, rpe_cnt, n_blocks,
+                                          m, max_set, queries, counts, join_off, cap_rows, out_ids,
+                                          out_cnt, err);
+        wave_sync();  // the next query reuses the LDS words
+    }
+}
+
 #define SUREL_JOIN_PARAMS                                                                         \
-    hipStream_t stream, const int64_t *rpe_off, const int32_t *rpe_ids, const uint16_t *rpe_cnt,  \
+    hipStream_t stream, int n_cu, const int64_t *rpe_off, const int32_t *rpe_ids, const uint16_t *rpe_cnt,  \
         int64_t n_blocks, int32_t m, int32_t max_set, const int32_t *queries, int64_t n_queries,  \
         int32_t *counts, const int64_t *join_off, int64_t cap_rows, int32_t *out_ids,             \
         uint16_t *out_cnt, uint32_t *err
 #define SUREL_JOIN_ARGS                                                                          \
-    stream, rpe_off, rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off, \
+    stream, n_cu, rpe_off, rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off, \
         cap_rows, out_ids, out_cnt, err
 
 template <int K, int WPB, bool kFill, int LT>
 static hipError_t launch_join_cfg(SUREL_JOIN_PARAMS) {
-    const size_t lds_bytes = (size_t)WPB * join_lds_layout(K, max_set, m + 1, kFill).total * 4;
+    const size_t lds_bytes = (size_t)WPB * join_lds_layout(K, max_set, m + 1, kFill, join_uses_tile(K, LT)).total * 4;
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(
             reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (rc != hipSuccess) return rc;
     }
-    const dim3 grid((unsigned)((n_queries + WPB - 1) / WPB)), block(WPB * kWave);
+    // no more workgroups than the device holds at once: their waves loop over the queries
+    int per_cu = 0;
+    hipError_t orc = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+        &per_cu, reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>), WPB * kWave,
+        lds_bytes);
+    if (orc != hipSuccess) return orc;
+    if (per_cu < 1) return hipErrorInvalidValue;
+    int64_t blocks = (n_queries + WPB - 1) / WPB;
+    if (blocks > (int64_t)per_cu * n_cu) blocks = (int64_t)per_cu * n_cu;
+    const dim3 grid((unsigned)blocks), block(WPB * kWave);
     hipLaunchKernelGGL((join_kernel<K, WPB, kFill, LT>), grid, block, lds_bytes, stream, rpe_off,
                        rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off,
                        cap_rows, out_ids, out_cnt, err);
@@ -401,7 +532,9 @@ static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
 template <int K>
 static hipError_t launch_join_k(int max_lds_bytes, SUREL_JOIN_PARAMS) {
     const bool fill = counts == nullptr;
-    const size_t per_wave = (size_t)join_lds_layout(K, max_set, m + 1, fill).total * 4;
+    const int LT = (fill && (m + 1 == 5 || m + 1 == 4)) ? m + 1 : 0;  // as launch_join_kwf picks
+    const size_t per_wave =
+        (size_t)join_lds_layout(K, max_set, m + 1, fill, join_uses_tile(K, LT)).total * 4;
 #define SUREL_JOIN_CASE(W_)                                                \
     if (per_wave * (W_) <= (size_t)max_lds_bytes) {                        \
         if (fill) return launch_join_kwf<K, W_, true>(SUREL_JOIN_ARGS);    \
@@ -414,7 +547,7 @@ static hipError_t launch_join_k(int max_lds_bytes, SUREL_JOIN_PARAMS) {
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_join(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
+hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
                        const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                        int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
                        int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,

@@ -47,7 +47,7 @@ hipError_t launch_rpe_fill(hipStream_t stream, int max_lds_bytes, const int32_t*
 
 // join.hip.  counts != nullptr: counting launch (counts[q] = union rows of query q);
 // counts == nullptr: writing launch at join_off[q].
-hipError_t launch_join(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
+hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
                        const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                        int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
                        int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,

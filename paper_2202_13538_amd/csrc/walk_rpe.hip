@@ -407,11 +407,12 @@ static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
     const int by_lds = (int)((160 * 1024 - 1024) / per_wave);
     if (cu_waves > by_lds) cu_waves = by_lds;
     if (cu_waves > 32) cu_waves = 32;
-    int groups = (cu_waves + 15) / 16;
+    constexpr int kMaxW = 16;
+    int groups = (cu_waves + kMaxW - 1) / kMaxW;
     int W = groups > 0 ? cu_waves / groups : 0;
     if (W < 1) {  // not even one wave next to other workgroups: what one workgroup may have
         W = (int)(((size_t)max_lds_bytes - 64) / per_wave);
-        if (W > 16) W = 16;
+        if (W > kMaxW) W = kMaxW;
     }
     if (W < 1) return hipErrorInvalidValue;
     const size_t lds_bytes = (size_t)W * per_wave;
