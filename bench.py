@@ -150,11 +150,19 @@ def main() -> int:
     set_sizes = torch.empty(N, dtype=torch.int32, device="cuda")
     max_set = 1 + M * m
 
+    fused = not args.unfused
+
+    def walks_and_rpe():
+        if fused:
+            return binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, walks,
+                                                cap_r, rpe_off, rpe_ids, rpe_cnt)
+        binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
+                             set_sizes=set_sizes)
+        return binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
+                                     set_sizes=set_sizes)
+
     # sizing pass (untimed): the join's row total fixes its output allocation
-    binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
-                         set_sizes=set_sizes)
-    rc, R = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
-                                  set_sizes=set_sizes)
+    rc, R = walks_and_rpe()
     assert rc == binding.OK, rc
     rc, J = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, 0, join_off,
                                      None, None)
@@ -164,17 +172,8 @@ def main() -> int:
     in_rows = int((rpe_off[1:] - rpe_off[:-1])[d_q.long()].sum())
     log(f"[bench] R={R} RPE rows, J={J} joined rows, {in_rows} table rows read by the join")
 
-    fused = not args.unfused
-
     def one_step():
-        if fused:
-            rc1, r = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed,
-                                                  walks, cap_r, rpe_off, rpe_ids, rpe_cnt)
-        else:
-            binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, out=walks,
-                                 set_sizes=set_sizes)
-            rc1, r = binding.build_rpe_raw(ctx, walks, N, cap_r, rpe_off, rpe_ids, rpe_cnt,
-                                           set_sizes=set_sizes)
+        rc1, r = walks_and_rpe()
         rc2, j = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, J,
                                           join_off, join_ids, join_cnt)
         assert rc1 == binding.OK and rc2 == binding.OK and r == R and j == J
@@ -198,11 +197,12 @@ def main() -> int:
     kern = {name: (tot / n if n else 0.0) for name, (tot, n) in prof.items()}   # avg ms / launch
     per_step = {name: tot / args.steps for name, (tot, n) in prof.items()}       # ms / step
     join_ms = per_step.get("join_count", 0.0) + per_step.get("join_fill", 0.0)
+    expand_ms = per_step.get("edge_records", 0.0)   # CSR -> per-edge records, part of the walk
     if fused:
-        stage_ms = {"walk_rpe": per_step.get("walk_rpe", 0.0), "join": join_ms}
+        stage_ms = {"walk_rpe": per_step.get("walk_rpe", 0.0) + expand_ms, "join": join_ms}
         walk_ms = rpe_ms = stage_ms["walk_rpe"]     # one kernel makes both outputs
     else:
-        stage_ms = {"walk": per_step.get("walk", 0.0),
+        stage_ms = {"walk": per_step.get("walk", 0.0) + expand_ms,
                     "rpe": per_step.get("rpe_count", 0.0) + per_step.get("rpe_fill", 0.0),
                     "join": join_ms}
         walk_ms, rpe_ms = stage_ms["walk"], stage_ms["rpe"]

@@ -93,7 +93,9 @@ extern "C" {
 #define SUREL_K_JOIN_FILL   4   /* join: writing launch                               */
 #define SUREL_K_SCAN        5   /* the offset scans (three small launches each)       */
 #define SUREL_K_WALK_RPE    6   /* fused walk + RPE kernel (surel_sample_walks_rpe)   */
-#define SUREL_K_COUNT       7
+#define SUREL_K_EDGE_RECORDS 7  /* expansion of the CSR into per-edge neighbour records
+                                   (both walk calls, large jobs only)                 */
+#define SUREL_K_COUNT       8
 
 typedef struct surel_ctx surel_ctx;
 

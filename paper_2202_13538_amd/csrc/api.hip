@@ -148,10 +148,11 @@ int read_total(surel_ctx* ctx, const int64_t* d_off, int64_t n, int64_t* h_rows)
     return SUREL_OK;
 }
 
-// Room for the walk's per-edge neighbour records when the job is large enough to want them.
-// *records stays null when it is not, or when the device has no room (not an error: the walk
-// then reads the CSR directly).
-int edge_record_space(surel_ctx* ctx, int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m,
+// The walk's per-edge neighbour records, made afresh from the CSR when the job is large enough
+// to want them.  *records stays null when it is not, or when the device has no room (not an
+// error: the walk then reads the CSR directly).
+int make_edge_records(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                      int32_t n_nodes, int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m,
                       void** records) {
     *records = nullptr;
     if (!surel::walks_want_records(n_edges, n_seeds, M, m)) return SUREL_OK;
@@ -167,7 +168,12 @@ int edge_record_space(surel_ctx* ctx, int64_t n_edges, int64_t n_seeds, int32_t 
             (void)hipGetLastError();
         }
     }
-    if (ctx->rec_bytes >= need) *records = ctx->d_rec;
+    if (ctx->rec_bytes < need) return SUREL_OK;
+    KernelSpan span(ctx, SUREL_K_EDGE_RECORDS);
+    if (surel::launch_edge_records(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
+                                   ctx->d_rec) != hipSuccess)
+        return SUREL_E_HIP;
+    *records = ctx->d_rec;
     return SUREL_OK;
 }
 
@@ -266,7 +272,9 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
     void* records = nullptr;
-    if (int rc = edge_record_space(ctx, n_edges, n_seeds, M, m, &records)) return rc;
+    if (int rc = make_edge_records(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, n_seeds, M, m,
+                                   &records))
+        return rc;
     KernelSpan span(ctx, SUREL_K_WALK);
     hipError_t rc = surel::launch_walks(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
                                         d_seeds, n_seeds, M, m, rng_seed, d_walks, d_set_sizes,
@@ -343,7 +351,9 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
         return SUREL_OK;
     }
     void* records = nullptr;
-    if (int rc = edge_record_space(ctx, n_edges, n_seeds, M, m, &records)) return rc;
+    if (int rc = make_edge_records(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, n_seeds, M, m,
+                                   &records))
+        return rc;
     const size_t lb_need = (size_t)surel::walk_rpe_lookback_words(n_seeds) * sizeof(uint64_t);
     if (lb_need > ctx->lb_bytes) {
         if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;

@@ -7,14 +7,14 @@
 namespace surel {
 
 // walk.hip.  set_sizes (optional): int32[n_seeds], receives the number of distinct nodes of
-// every seed's walks; needs 1 + M*m <= 2048.  edge_records (optional): device scratch of
-// 16 * n_edges bytes; when given, the CSR is first expanded into per-edge neighbour records
-// (worth it when walks_want_records says so).
+// every seed's walks; needs 1 + M*m <= 2048.  edge_records (optional): the per-edge neighbour
+// records that launch_edge_records made of this CSR (16 * n_edges bytes; worth making when
+// walks_want_records says so).
 bool walks_want_records(int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m);
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
-                        int32_t* set_sizes, void* edge_records, uint32_t* err);
+                        int32_t* set_sizes, const void* edge_records, uint32_t* err);
 
 // Expands the CSR into edge_records (16 * n_edges bytes), see walk.hip.
 hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
@@ -31,7 +31,7 @@ hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, cons
                            const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
                            uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
-                           int32_t* ids, uint16_t* cnt, void* edge_records, uint64_t* lb,
+                           int32_t* ids, uint16_t* cnt, const void* edge_records, uint64_t* lb,
                            uint32_t spin_limit, uint32_t* err);
 
 // rpe.hip.  launch_rpe_count: set_sizes[i] = distinct nodes in walks[i].  launch_rpe_fill:

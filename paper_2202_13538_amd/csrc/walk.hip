@@ -151,13 +151,9 @@ hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
-                        int32_t* set_sizes, void* edge_records, uint32_t* err) {
+                        int32_t* set_sizes, const void* edge_records, uint32_t* err) {
     if (n_seeds == 0) return hipSuccess;
-    int4* rec = static_cast<int4*>(edge_records);
-    if (rec != nullptr) {
-        hipError_t rc = launch_edge_records(stream, row_ptr, col_idx, n_nodes, n_edges, rec);
-        if (rc != hipSuccess) return rc;
-    }
+    const int4* rec = static_cast<const int4*>(edge_records);
 #define SUREL_WALK_ARGS \
     stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m, rng_seed, walks, set_sizes, err
     if (set_sizes != nullptr) {

@@ -452,14 +452,9 @@ hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, cons
                            const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
                            uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
-                           int32_t* ids, uint16_t* cnt, void* edge_records, uint64_t* lb,
+                           int32_t* ids, uint16_t* cnt, const void* edge_records, uint64_t* lb,
                            uint32_t spin_limit, uint32_t* err) {
     const int4* rec = static_cast<const int4*>(edge_records);
-    if (rec != nullptr) {
-        hipError_t rc = launch_edge_records(stream, row_ptr, col_idx, n_nodes, n_edges,
-                                            edge_records);
-        if (rc != hipSuccess) return rc;
-    }
     const int n_key = M * (m + 1);
 #define SUREL_WR_CASE(E_) \
     if (n_key <= kWave * (E_)) return launch_walk_rpe_e<E_>(SUREL_WR_ARGS);
