@@ -51,6 +51,10 @@ def _load():
                                             i32p, ctypes.c_int64, ctypes.c_int32,
                                             ctypes.c_int64, i64p, i32p, u16p]
         lib.oracle_join_queries.restype = ctypes.c_int64
+        lib.oracle_query_rpe_ids.argtypes = [i32p, i64p, i32p, ctypes.c_int64, ctypes.c_int32,
+                                             ctypes.c_int32, i32p, ctypes.c_int64,
+                                             ctypes.c_int32, i64p]
+        lib.oracle_query_rpe_ids.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -139,3 +143,23 @@ def join_queries(rpe_off, rpe_ids, rpe_cnt, queries):
     if rows2 != rows:
         raise ValueError(f"oracle_join_queries failed with {rows2}")
     return off, ids, cnt
+
+
+def query_rpe_ids(walks, rpe_off, rpe_ids, queries) -> np.ndarray:
+    """int64[n_q][k][M][m+1][k]: for every node occurrence in the concatenated walks of a
+    query, the table rows of that node in each of the query's blocks (-1 where absent)."""
+    walks = _arr(walks, np.int32)
+    rpe_off = _arr(rpe_off, np.int64)
+    rpe_ids = _arr(rpe_ids, np.int32)
+    queries = _arr(queries, np.int32)
+    n_blocks, M, L = walks.shape
+    assert rpe_off.size == n_blocks + 1
+    n_q, k = queries.shape
+    out = np.empty((n_q, k, M, L, k), dtype=np.int64)
+    rc = _load().oracle_query_rpe_ids(_ptr(walks, ctypes.c_int32), _ptr(rpe_off, ctypes.c_int64),
+                                      _ptr(rpe_ids, ctypes.c_int32), n_blocks, M, L - 1,
+                                      _ptr(queries, ctypes.c_int32), n_q, k,
+                                      _ptr(out, ctypes.c_int64))
+    if rc != 0:
+        raise ValueError(f"oracle_query_rpe_ids failed with {rc}")
+    return out

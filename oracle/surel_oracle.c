@@ -20,6 +20,13 @@
  *                          X_{u,x}, all zeros where x is not in V_u; taken over the
  *                          union of the V_u (the set-union form the section's
  *                          closing remarks describe).
+ *   oracle_query_rpe_ids   Sec. 3.4, the form the section describes first: the walks
+ *                          W_u, u in Q, are concatenated, and every node occurrence x
+ *                          in them gets RPE-ID_{Q,x} = [RPE-ID_{u,x}]_{u in Q}, found
+ *                          through H_u(x).  Here the table of oracle_build_rpe is the
+ *                          (unpruned) central array T of Sec. 3.3, so RPE-ID_{u,x} is
+ *                          the index of (u, x)'s row in it, and -1 stands for "x is
+ *                          not in V_u" (the all-zero vector).
  *
  * Readings where the paper is silent:
  *   - a walk is stored with its start: m+1 positions, position 0 is the seed
@@ -233,4 +240,43 @@ int64_t oracle_join_queries(const int64_t *rpe_off, const int32_t *rpe_ids,
         join_off[q + 1] = total;
     }
     return overflow ? -2 : total;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Query-level RPE-IDs per walk position.                                    */
+/*   walks[b] is the walk block of table block b (the same seed).             */
+/*   out[q][j][w][s][j2] = row of the table that holds (block queries[q][j2], */
+/*   node walks[queries[q][j]][w][s]), or -1 if that block has no such node.  */
+/* ------------------------------------------------------------------------- */
+int oracle_query_rpe_ids(const int32_t *walks, const int64_t *rpe_off, const int32_t *rpe_ids,
+                         int64_t n_blocks, int32_t M, int32_t m, const int32_t *queries,
+                         int64_t n_queries, int32_t k, int64_t *out)
+{
+    if (n_blocks < 0 || M < 1 || m < 1 || n_queries < 0 || k < 1 || k > 8 || !rpe_off ||
+        (n_queries > 0 && (!queries || !walks || !out)))
+        return -1;
+    const int64_t L = (int64_t)m + 1;
+    for (int64_t q = 0; q < n_queries; ++q) {
+        for (int j = 0; j < k; ++j)
+            if (queries[q * k + j] < 0 || queries[q * k + j] >= n_blocks)
+                return -1;
+        for (int j = 0; j < k; ++j) {
+            const int32_t *W = walks + (int64_t)queries[q * k + j] * M * L;
+            for (int64_t t = 0; t < (int64_t)M * L; ++t) {
+                const int32_t x = W[t];
+                for (int j2 = 0; j2 < k; ++j2) {
+                    const int32_t b = queries[q * k + j2];
+                    const int32_t *set = rpe_ids + rpe_off[b];
+                    const int64_t n_set = rpe_off[b + 1] - rpe_off[b];
+                    const int32_t *hit =
+                        n_set > 0 ? (const int32_t *)bsearch(&x, set, (size_t)n_set,
+                                                             sizeof(int32_t), cmp_i32)
+                                  : NULL;
+                    out[(((q * k + j) * M * L) + t) * k + j2] =
+                        hit ? rpe_off[b] + (int64_t)(hit - set) : -1;
+                }
+            }
+        }
+    }
+    return 0;
 }

@@ -41,6 +41,14 @@ MUTANTS = {
     "join_halves_reversed": ("join_cnt + (total * k + j) * L", "join_cnt + (total * k + (k - 1 - j)) * L"),
     "join_no_zero_fill": ("memset(dst, 0, (size_t)L * sizeof(uint16_t));",
                           "memset(dst, 1, (size_t)L * sizeof(uint16_t));"),
+    "ids_looks_in_own_block_only": ("const int32_t b = queries[q * k + j2];\n                    const int32_t *set",
+                                    "const int32_t b = queries[q * k + j];\n                    const int32_t *set"),
+    "ids_local_instead_of_table_row": ("hit ? rpe_off[b] + (int64_t)(hit - set) : -1;",
+                                       "hit ? (int64_t)(hit - set) : -1;"),
+    "ids_absent_is_row_zero": ("hit ? rpe_off[b] + (int64_t)(hit - set) : -1;",
+                               "hit ? rpe_off[b] + (int64_t)(hit - set) : 0;"),
+    "ids_columns_transposed": ("out[(((q * k + j) * M * L) + t) * k + j2] =",
+                               "out[(((q * k + j2) * M * L) + t) * k + j] ="),
     "join_copies_wrong_row": ("memcpy(dst, rpe_cnt + head[j] * L,", "memcpy(dst, rpe_cnt + rpe_off[queries[q * k + j]] * L,"),
 }
 
@@ -55,6 +63,8 @@ PIN_TESTS = [
     "test_paper_worked_example_fragment",
     "test_rpe_hand_worked_table",
     "test_join_symmetry_and_repeated_node",
+    "test_query_rpe_ids_invariants_and_agreement_with_the_union_join",
+    "test_query_rpe_ids_on_the_paper_fragment",
 ]
 PARAM_PIN_TESTS = [
     ("test_walk_distribution_matches_enumeration", ("lollipop", 4)),
@@ -62,6 +72,7 @@ PARAM_PIN_TESTS = [
     ("test_rpe_equals_dense_counter_and_keeps_invariants", (50, 4)),
     ("test_join_equals_python_set_union", (2,)),
     ("test_join_equals_python_set_union", (3,)),
+    ("test_query_rpe_ids_equal_dictionary_lookups", (2,)),
 ]
 
 
@@ -102,7 +113,7 @@ def test_planted_mistake_is_caught(name, tmp_path, golden_dir, monkeypatch):
     real = oracle._load()
     mutant = ctypes.CDLL(str(lib_path))
     for fn in ("oracle_philox4x32_10", "oracle_sample_walks", "oracle_build_rpe",
-               "oracle_join_queries"):
+               "oracle_join_queries", "oracle_query_rpe_ids"):
         getattr(mutant, fn).argtypes = getattr(real, fn).argtypes
         getattr(mutant, fn).restype = getattr(real, fn).restype
     monkeypatch.setattr(oracle, "_lib", mutant)

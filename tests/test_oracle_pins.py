@@ -500,3 +500,89 @@ def test_join_empty_and_single_row_blocks():
     joff, jids, jcnt = oracle.join_queries(off, ids, cnt, [[0, 1]])
     assert jids[0] == 0 and jcnt[0].tolist() == [[6, 6, 6], [0, 0, 0]]
     assert jids.tolist() == sorted(set(ids.tolist()))
+
+
+# --------------------------------------------------------------------------- #
+# query-level RPE-IDs per walk position (the form Sec. 3.4 describes first)
+# --------------------------------------------------------------------------- #
+def _small_walks_and_table(M=30, m=3, n_seeds=40, graph_seed=8):
+    wl = synth.Workload("t", "chung_lu", 200, 700, 2.2, M, m, 0, 2, "uniform",
+                        graph_seed=graph_seed)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(n_seeds, dtype=np.int32)
+    w = oracle.sample_walks(rp, ci, seeds, M, m, rng_seed=33)
+    return (w,) + oracle.build_rpe(w)
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_query_rpe_ids_equal_dictionary_lookups(k):
+    w, off, ids, cnt = _small_walks_and_table()
+    n_blocks, M, L = w.shape
+    rng = np.random.default_rng(17)
+    queries = rng.integers(0, n_blocks, size=(25, k)).astype(np.int32)
+    queries[0] = 3                                   # a query that repeats one node
+    got = oracle.query_rpe_ids(w, off, ids, queries)
+    assert got.shape == (25, k, M, L, k)
+    # H_b(x): one Python dictionary per block, node id -> row of the table
+    H = [{int(x): int(off[b] + t) for t, x in enumerate(ids[off[b]:off[b + 1]])}
+         for b in range(n_blocks)]
+    absent_seen = False
+    for q, query in enumerate(queries.tolist()):
+        for j, b in enumerate(query):
+            for wi in range(M):
+                for s in range(L):
+                    x = int(w[b, wi, s])
+                    want = [H[b2].get(x, -1) for b2 in query]
+                    assert got[q, j, wi, s].tolist() == want
+                    absent_seen |= -1 in want
+    assert absent_seen
+
+
+def test_query_rpe_ids_invariants_and_agreement_with_the_union_join():
+    M, m = 30, 3
+    w, off, ids, cnt = _small_walks_and_table(M, m)
+    L = m + 1
+    queries = np.array([[1, 2], [7, 7], [30, 4], [12, 39]], dtype=np.int32)
+    got = oracle.query_rpe_ids(w, off, ids, queries)
+    joff, jids, jcnt = oracle.join_queries(off, ids, cnt, queries)
+    for q, (b0, b1) in enumerate(queries.tolist()):
+        blocks = (b0, b1)
+        for j in range(2):
+            own = got[q, j, :, :, j]
+            # a node of W_b is in V_b, and it was counted at the position it stands at
+            assert (own >= 0).all()
+            assert (ids[own] == w[blocks[j]]).all()
+            s_idx = np.broadcast_to(np.arange(L), own.shape)
+            assert (cnt[own, s_idx] >= 1).all()
+            for j2 in range(2):
+                rows = got[q, j, :, :, j2]
+                lo, hi = off[blocks[j2]], off[blocks[j2] + 1]
+                assert ((rows == -1) | ((rows >= lo) & (rows < hi))).all()
+                assert (ids[rows[rows >= 0]] == w[blocks[j]][rows >= 0]).all()
+        # T(RPE-ID_{Q,x}) is X_{Q,x}: the vectors the IDs point at (zeros for -1) are the row
+        # the set-union form holds for that node
+        union = {int(x): jcnt[joff[q] + t] for t, x in enumerate(jids[joff[q]:joff[q + 1]])}
+        for j in range(2):
+            for wi in range(M):
+                for s in range(L):
+                    x = int(w[blocks[j], wi, s])
+                    vec = [cnt[r].tolist() if r >= 0 else [0] * L for r in got[q, j, wi, s]]
+                    assert vec == union[x].tolist()
+
+
+def test_query_rpe_ids_on_the_paper_fragment(golden_dir):
+    # Sec. 3.4: X_{Q,u} = ([2,0,0],[0,0,1]) is what the query-level RPE-ID of u points at
+    ex = _read_example(golden_dir)
+    m, M = ex["m"][0], ex["M"][0]
+    walks = np.array([ex["walks_u"], ex["walks_v"]], dtype=np.int32).reshape(2, M, m + 1)
+    off, ids, cnt = oracle.build_rpe(walks)
+    got = oracle.query_rpe_ids(walks, off, ids, [[0, 1]])
+    id_u = got[0, 0, 0, 0]                        # u stands at position 0 of its own walks
+    assert [cnt[r].tolist() for r in id_u] == [ex["X_Q,u"][:3], ex["X_Q,u"][3:]]
+    # node a (walks_u, first walk, last position) is not in the second patch
+    assert got[0, 0, 0, 2, 1] == -1 and cnt[got[0, 0, 0, 2, 0]].tolist() == ex["X_u,a"]
+
+
+def test_query_rpe_ids_empty_query_list():
+    w, off, ids, cnt = _small_walks_and_table(6, 2, 5)
+    assert oracle.query_rpe_ids(w, off, ids, np.zeros((0, 2), dtype=np.int32)).shape[0] == 0
