@@ -104,6 +104,10 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--unfused", action="store_true",
                     help="sample_walks and build_rpe as two calls instead of the fused kernel")
+    ap.add_argument("--query-ids", action="store_true",
+                    help="also time surel_query_rpe_ids (Sec. 3.4's per-walk-position form of the "
+                         "join) after the timed region; reported under 'query_rpe_ids', not part "
+                         "of 'value'")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
@@ -244,6 +248,22 @@ def main() -> int:
         "pipeline_hbm_frac": round(pipeline_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": roofline,
     }
+    if args.query_ids:
+        qid = torch.empty((Q, k, M, L, k), dtype=torch.int32, device="cuda")
+        binding.query_rpe_ids(ctx, walks, rpe_off, rpe_ids[:R], d_q, max_set, out=qid)
+        ctx.profile(True)
+        for _ in range(args.steps):
+            binding.query_rpe_ids(ctx, walks, rpe_off, rpe_ids[:R], d_q, max_set, out=qid)
+        ms = ctx.profile_read()["query_ids"][0] / args.steps
+        ctx.profile(False)
+        assert ctx.check() == 0
+        # read: the k walk blocks and id lists of every query; written: k row indices per entry
+        q_bytes = Q * k * M * L * 4 + in_rows * 4 + Q * k * M * L * k * 4
+        out["query_rpe_ids"] = {
+            "ms": round(ms, 4), "walk_positions_per_s": Q * k * M * L / (ms * 1e-3),
+            "algorithmic_bytes": q_bytes,
+            "hbm_frac": round(q_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del qid
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
         b = torch.empty_like(a)

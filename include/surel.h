@@ -10,6 +10,8 @@
  *   surel_join_queries   per query tuple Q, the union of the V_u, u in Q, and for each
  *                        node x of it the query-level RPE X_{Q,x} = [X_{u,x}]_{u in Q},
  *                        zeros where x is not in V_u (Sec. 3.4, set-union form).
+ * Beside them: surel_sample_walks_rpe (the first two in one kernel) and surel_query_rpe_ids
+ * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values).
  *
  * Conventions
  *   - Plain C ABI.  Pointers named d_* are DEVICE memory owned by the caller, on the
@@ -95,7 +97,8 @@ extern "C" {
 #define SUREL_K_WALK_RPE    6   /* fused walk + RPE kernel (surel_sample_walks_rpe)   */
 #define SUREL_K_EDGE_RECORDS 7  /* expansion of the CSR into per-edge neighbour records
                                    (both walk calls, large jobs only)                 */
-#define SUREL_K_COUNT       8
+#define SUREL_K_QUERY_IDS   8   /* surel_query_rpe_ids                                */
+#define SUREL_K_COUNT       9
 
 typedef struct surel_ctx surel_ctx;
 
@@ -190,6 +193,27 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                        int32_t k, int64_t cap_rows, int64_t* d_join_off,
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
+
+/* Sec. 3.4, the per-walk-position form: the walks of a query's blocks are concatenated, and
+ * every node occurrence x in them gets its query-level RPE-ID, the tuple of the RPE table's row
+ * indices of x in each of the query's k blocks (the table is the unpruned central array of
+ * Sec. 3.3; -1 = the block does not hold x, i.e. the all-zero vector).
+ *   d_walks      int32[n_blocks][M][m+1] (device, read-only): d_walks[b] is the walk block whose
+ *                RPE rows are table block b (true for the outputs of surel_sample_walks /
+ *                surel_build_rpe / surel_sample_walks_rpe over one seed list).
+ *   d_rpe_off, d_rpe_ids   the RPE table (device, read-only); table_rows = its number of rows
+ *                (d_rpe_off[n_blocks]), at most 2^31 - 1 so that a row index fits int32.
+ *   max_set, d_queries, n_queries, k   as in surel_join_queries.
+ *   d_out        int32[n_queries][k][M][m+1][k] (device, written):
+ *                d_out[q][j][w][s][j2] = row of node d_walks[queries[q][j]][w][s] in block
+ *                queries[q][j2], or -1.
+ * Limits: 1 <= M <= SUREL_MAX_WALKS, 1 <= m <= SUREL_MAX_STEPS, M*(m+1) < 2^31 / 9,
+ * 2 <= k <= SUREL_MAX_TUPLE, 1 <= max_set <= SUREL_MAX_SET, 0 <= table_rows < 2^31.
+ * Device-detected: BAD_QUERY, BAD_TABLE, SET_TOO_LARGE (that query's entries are all -1). */
+int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d_rpe_off,
+                        const int32_t* d_rpe_ids, int64_t n_blocks, int64_t table_rows, int32_t M,
+                        int32_t m, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                        int32_t k, int32_t* d_out);
 
 /* Every wait inside the fused kernel of surel_sample_walks_rpe (a wave waiting for an offset,
  * the offset scan waiting for a row count) gives up after `spins` polls, raises

@@ -22,10 +22,11 @@ MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
 
 (K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_WALK_RPE,
- K_EDGE_RECORDS, K_COUNT) = range(9)
+ K_EDGE_RECORDS, K_QUERY_IDS, K_COUNT) = range(10)
 KERNEL_NAMES = {K_WALK: "walk", K_RPE_COUNT: "rpe_count", K_RPE_FILL: "rpe_fill",
                 K_JOIN_COUNT: "join_count", K_JOIN_FILL: "join_fill", K_SCAN: "scan",
-                K_WALK_RPE: "walk_rpe", K_EDGE_RECORDS: "edge_records"}
+                K_WALK_RPE: "walk_rpe", K_EDGE_RECORDS: "edge_records",
+                K_QUERY_IDS: "query_ids"}
 
 _vp = ctypes.c_void_p
 _i32, _i64, _u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
@@ -45,6 +46,8 @@ SIGNATURES = {
                                               ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "surel_query_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp,
+                                           _i64, _i32, _vp]),
     "surel_set_spin_limit": (ctypes.c_int, [_vp, ctypes.c_uint32]),
     "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
     "surel_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
@@ -293,3 +296,21 @@ def join_queries(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
     if rc != OK:
         raise SurelError(rc, "surel_join_queries")
     return off, ids[:rows], cnt[:rows]
+
+
+def query_rpe_ids(ctx: Context, walks: torch.Tensor, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
+                  queries: torch.Tensor, max_set: int, out: torch.Tensor | None = None):
+    """int32[n_q][k][M][m+1][k] on the GPU: the query-level RPE-IDs of every walk position."""
+    n_blocks, M, L = walks.shape
+    n_q, k = queries.shape
+    if out is None:
+        out = torch.empty((n_q, k, M, L, k), dtype=torch.int32, device=walks.device)
+    elif out.numel() != n_q * k * M * L * k:
+        raise ValueError("out has the wrong size")
+    rc = load().surel_query_rpe_ids(
+        ctx.handle, _ptr(walks, torch.int32, "walks"), _ptr(rpe_off, torch.int64, "rpe_off"),
+        _ptr(rpe_ids, torch.int32, "rpe_ids"), n_blocks, rpe_ids.numel(), M, L - 1, max_set,
+        _ptr(queries, torch.int32, "queries"), n_q, k, _ptr(out, torch.int32, "out"))
+    if rc != OK:
+        raise SurelError(rc, "surel_query_rpe_ids")
+    return out

@@ -430,6 +430,31 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
     return SUREL_OK;
 }
 
+int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d_rpe_off,
+                        const int32_t* d_rpe_ids, int64_t n_blocks, int64_t table_rows, int32_t M,
+                        int32_t m, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                        int32_t k, int32_t* d_out) {
+    if (M < 1 || M > SUREL_MAX_WALKS || m < 1 || m > SUREL_MAX_STEPS) return SUREL_E_RANGE;
+    if ((int64_t)M * (m + 1) >= (int64_t)0x7FFFFFFF / 9) return SUREL_E_RANGE;
+    if (k < 2 || k > SUREL_MAX_TUPLE) return SUREL_E_RANGE;
+    if (max_set < 1 || max_set > SUREL_MAX_SET) return SUREL_E_RANGE;
+    if (n_blocks < 0 || n_queries < 0 || n_queries > 0x7FFFFFFFll) return SUREL_E_RANGE;
+    if (table_rows < 0 || table_rows > 0x7FFFFFFFll) return SUREL_E_RANGE;
+    if (n_queries > 0 && (!d_walks || !d_rpe_off || !d_rpe_ids || !d_queries || !d_out))
+        return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    if (n_queries == 0) return SUREL_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    KernelSpan span(ctx, SUREL_K_QUERY_IDS);
+    hipError_t hrc = surel::launch_query_ids(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_walks,
+                                             d_rpe_off, d_rpe_ids, n_blocks, M, m, max_set,
+                                             table_rows, d_queries, n_queries, k, d_out,
+                                             ctx->d_err);
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    return hrc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
+}
+
 int surel_set_spin_limit(surel_ctx* ctx, uint32_t spins) {
     if (!ctx) return SUREL_E_CTX;
     ctx->spin_limit = spins;

@@ -53,6 +53,15 @@ hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const in
                        int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
                        int32_t* out_ids, uint16_t* out_cnt, uint32_t* err);
 
+// query_ids.hip.  out int32[n_queries][k][M][m+1][k]: for every entry of the walk blocks of a
+// query's k table blocks, the table rows that hold its node in each of the k blocks (-1 where
+// a block does not hold it).  walks[b] must be the walk block of table block b.
+hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* walks,
+                            const int64_t* rpe_off, const int32_t* rpe_ids, int64_t n_blocks,
+                            int32_t M, int32_t m, int32_t max_set, int64_t table_rows,
+                            const int32_t* queries, int64_t n_queries, int32_t k, int32_t* out,
+                            uint32_t* err);
+
 // scan.hip.  off[0..n] = exclusive prefix sums of counts[0..n-1] (off[n] = total).
 // partials: device scratch of scan_partials_len(n) int64.
 int64_t scan_partials_len(int64_t n);

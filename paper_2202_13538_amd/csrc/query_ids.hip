@@ -1,0 +1,205 @@
+// Query-level RPE-IDs per walk position (Sec. 3.4, the form the section describes first): the
+// walks W_u, u in Q, are concatenated and every node occurrence x in them gets
+// RPE-ID_{Q,x} = [RPE-ID_{u,x}]_{u in Q}.  The RPE table is the (unpruned) central array of
+// Sec. 3.3, so RPE-ID_{u,x} is the index of (u, x)'s row in it; -1 stands for "x is not in
+// V_u" (the all-zero vector).  The paper looks x up in the hash dictionary H_u; here the
+// blocks' id lists are sorted, so the lookup is a binary search in LDS.  (Per-query hash
+// dictionaries in LDS were measured too and lost: their probe loops diverge, and their
+// footprint leaves a compute unit too few waves.)
+//
+// A wavefront handles one query at a time and loops over the queries (the grid is as large as
+// the device holds at once).  It stages the K id lists in LDS, then runs over the K walk
+// blocks as flat arrays: a lane takes kQiEntries walk entries at a time and searches each in
+// all K lists with a fixed number of branch-free steps, so that the K * kQiEntries searches
+// of a round advance together and their LDS reads overlap; the K row indices of an entry lie
+// next to each other in the output.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace surel {
+
+constexpr int kQiEntries = 2;  // walk entries a lane looks up at a time
+
+template <int K, int WPB>
+__global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
+    const int32_t* __restrict__ walks, const int64_t* __restrict__ rpe_off,
+    const int32_t* __restrict__ rpe_ids, int64_t n_blocks, int32_t n_key, int32_t max_set,
+    int64_t table_rows, const int32_t* __restrict__ queries, int64_t n_queries,
+    int32_t* __restrict__ out, uint32_t* __restrict__ err) {
+    extern __shared__ uint32_t lds32[];
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // list j at [j*(max_set+1) + 1 ...); the word in front of it (index -1 of the list) is
+    // never smaller than a node id, so a search may read it
+    const int list_stride = max_set + 1;
+    uint32_t* ids_lds = lds32 + wave * (K * list_stride);
+    const int64_t stride = (int64_t)gridDim.x * WPB;
+    for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
+        // the K blocks of this query (wave-uniform)
+        int32_t blk[K];
+        int64_t lo[K];
+        int n[K];
+        uint32_t problem = 0;
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const int32_t b = queries[q * K + j];
+            blk[j] = 0;
+            lo[j] = 0;
+            n[j] = 0;
+            if (b < 0 || (int64_t)b >= n_blocks) {
+                problem |= kDevBadQuery;
+            } else {
+                const int64_t a = rpe_off[b];
+                const int64_t len = rpe_off[b + 1] - a;
+                if (a < 0 || len < 0 || a + len > table_rows) {
+                    problem |= kDevBadTable;
+                } else if (len > (int64_t)max_set) {
+                    problem |= kDevSetTooLarge;
+                } else {
+                    blk[j] = b;
+                    lo[j] = a;
+                    n[j] = (int)len;
+                }
+            }
+        }
+        int32_t* out_q = out + q * (int64_t)K * n_key * K;
+        if (problem != 0) {
+            // the query gets no RPE-IDs at all
+            if (lane == 0) atomicOr(err, problem);
+            for (int t = lane; t < K * n_key * K; t += kWave) out_q[t] = -1;
+            continue;
+        }
+        int top[K];  // largest power of two <= n[j] (0 for an empty list): the first step
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            if (lane == 0) ids_lds[j * list_stride] = 0xFFFFFFFFu;
+            stage_words<8>(ids_lds + j * list_stride + 1,
+                           reinterpret_cast<const uint32_t*>(rpe_ids + lo[j]), n[j], lane);
+            top[j] = n[j] > 0 ? 1 << (31 - __builtin_clz((unsigned)n[j])) : 0;
+        }
+        int top_max = 0;
+#pragma unroll
+        for (int j = 0; j < K; ++j) top_max = max(top_max, top[j]);
+        wave_sync();
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const int32_t* W = walks + (int64_t)blk[j] * n_key;
+            int32_t* out_j = out_q + (int64_t)j * n_key * K;
+            for (int t0 = 0; t0 < n_key; t0 += kQiEntries * kWave) {
+                uint32_t x[kQiEntries];
+                int pos[kQiEntries][K];  // elements of list j2 that are smaller than x
+#pragma unroll
+                for (int e = 0; e < kQiEntries; ++e) {
+                    const int t = min(t0 + e * kWave + lane, n_key - 1);
+                    x[e] = (uint32_t)__builtin_nontemporal_load(W + t);
+#pragma unroll
+                    for (int j2 = 0; j2 < K; ++j2) pos[e][j2] = 0;
+                }
+                for (int step = top_max; step > 0; step >>= 1) {
+#pragma unroll
+                    for (int e = 0; e < kQiEntries; ++e) {
+#pragma unroll
+                        for (int j2 = 0; j2 < K; ++j2) {
+                            // a step past the end of the list reads its last element again
+                            // (or the guard word of an empty list) and is not taken
+                            const int cand = pos[e][j2] + step;
+                            const uint32_t probe =
+                                ids_lds[j2 * list_stride + min(cand, n[j2])];
+                            if (cand <= n[j2] && probe < x[e]) pos[e][j2] = cand;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < kQiEntries; ++e) {
+                    const int t = t0 + e * kWave + lane;
+                    int32_t row[K];
+#pragma unroll
+                    for (int j2 = 0; j2 < K; ++j2) {
+                        const int p = pos[e][j2];
+                        const uint32_t at = ids_lds[j2 * list_stride + 1 + min(p, max(n[j2] - 1, 0))];
+                        const bool found = p < n[j2] && at == x[e];
+                        row[j2] = found ? (int32_t)(lo[j2] + p) : -1;
+                    }
+                    if (t < n_key) {
+#pragma unroll
+                        for (int j2 = 0; j2 < K; ++j2) out_j[(int64_t)t * K + j2] = row[j2];
+                    }
+                }
+            }
+        }
+        wave_sync();  // the next query reuses the LDS words
+    }
+}
+
+template <int K, int WPB>
+static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_t* walks,
+                                      const int64_t* rpe_off, const int32_t* rpe_ids,
+                                      int64_t n_blocks, int32_t M, int32_t m, int32_t max_set,
+                                      int64_t table_rows, const int32_t* queries,
+                                      int64_t n_queries, int32_t* out, uint32_t* err) {
+    const size_t lds_bytes = (size_t)WPB * K * (max_set + 1) * 4;
+    const void* fn = reinterpret_cast<const void*>(query_ids_kernel<K, WPB>);
+    if (lds_bytes > 48 * 1024) {
+        hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)lds_bytes);
+        if (rc != hipSuccess) return rc;
+    }
+    int per_cu = 0;
+    hipError_t rc = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, WPB * kWave, lds_bytes);
+    if (rc != hipSuccess) return rc;
+    if (per_cu < 1) return hipErrorInvalidValue;
+    int64_t blocks = (n_queries + WPB - 1) / WPB;
+    if (blocks > (int64_t)per_cu * n_cu) blocks = (int64_t)per_cu * n_cu;
+    hipLaunchKernelGGL((query_ids_kernel<K, WPB>), dim3((unsigned)blocks), dim3(WPB * kWave),
+                       lds_bytes, stream, walks, rpe_off, rpe_ids, n_blocks, M * (m + 1), max_set,
+                       table_rows, queries, n_queries, out, err);
+    return hipGetLastError();
+}
+
+template <int K>
+static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int n_cu,
+                                     const int32_t* walks, const int64_t* rpe_off,
+                                     const int32_t* rpe_ids, int64_t n_blocks, int32_t M, int32_t m,
+                                     int32_t max_set, int64_t table_rows, const int32_t* queries,
+                                     int64_t n_queries, int32_t* out, uint32_t* err) {
+    const size_t per_wave = (size_t)K * (max_set + 1) * 4;
+    // waves per workgroup: the choice that lets a compute unit hold the most waves
+    int best = 1, best_waves = 0;
+    for (int w = 4; w >= 1; w /= 2) {
+        const size_t wg = per_wave * w;
+        if (wg > (size_t)max_lds_bytes) continue;
+        int waves = (int)((size_t)max_lds_bytes / wg) * w;
+        if (waves > 32) waves = 32;
+        if (waves > best_waves) {
+            best_waves = waves;
+            best = w;
+        }
+    }
+#define SUREL_QI_CASE(W_)                                                                        \
+    if (best == (W_))                                                                            \
+        return launch_query_ids_kw<K, W_>(stream, n_cu, walks, rpe_off, rpe_ids, n_blocks, M, m, \
+                                          max_set, table_rows, queries, n_queries, out, err);
+    SUREL_QI_CASE(4)
+    SUREL_QI_CASE(2)
+    SUREL_QI_CASE(1)
+#undef SUREL_QI_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* walks,
+                            const int64_t* rpe_off, const int32_t* rpe_ids, int64_t n_blocks,
+                            int32_t M, int32_t m, int32_t max_set, int64_t table_rows,
+                            const int32_t* queries, int64_t n_queries, int32_t k, int32_t* out,
+                            uint32_t* err) {
+    if (n_queries == 0) return hipSuccess;
+    if ((size_t)k * (max_set + 1) * 4 > (size_t)max_lds_bytes) return hipErrorInvalidValue;
+#define SUREL_QI_ARGS \
+    stream, max_lds_bytes, n_cu, walks, rpe_off, rpe_ids, n_blocks, M, m, max_set, table_rows, \
+        queries, n_queries, out, err
+    if (k == 2) return launch_query_ids_k<2>(SUREL_QI_ARGS);
+    if (k == 3) return launch_query_ids_k<3>(SUREL_QI_ARGS);
+#undef SUREL_QI_ARGS
+    return hipErrorInvalidValue;
+}
+
+}  // namespace surel

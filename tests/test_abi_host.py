@@ -179,6 +179,37 @@ def test_sample_walks_rpe_argument_checks(lib, kw, want):
     assert lib.surel_sample_walks_rpe(*fused_args(**kw)) == want
 
 
+def ids_args(**kw):
+    a = dict(ctx=NULL, walks=P, off=P, ids=P, n_blocks=100, table_rows=5000, M=50, m=4,
+             max_set=201, queries=P, n_q=10, k=2, out=P)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "walks", "off", "ids", "n_blocks", "table_rows", "M", "m",
+                           "max_set", "queries", "n_q", "k", "out")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(M=0), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(k=1), binding.E_RANGE),
+    (dict(k=4), binding.E_RANGE),
+    (dict(max_set=0), binding.E_RANGE),
+    (dict(max_set=binding.MAX_SET + 1), binding.E_RANGE),
+    (dict(n_blocks=-1), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(table_rows=-1), binding.E_RANGE),
+    (dict(table_rows=1 << 31), binding.E_RANGE),      # a row index must fit int32
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(out=NULL), binding.E_NULL),
+    (dict(queries=NULL, out=NULL, walks=NULL, off=NULL, ids=NULL, n_q=0), binding.E_CTX),
+])
+def test_query_rpe_ids_argument_checks(lib, kw, want):
+    assert lib.surel_query_rpe_ids(*ids_args(**kw)) == want
+
+
 def join_args(**kw):
     a = dict(ctx=NULL, off=P, ids=P, cnt=P, n_blocks=100, m=4, max_set=201, queries=P, n_q=10,
              k=2, cap_rows=1000, joff=P, jids=P, jcnt=P, h_rows=NULL)

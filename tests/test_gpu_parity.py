@@ -82,6 +82,13 @@ def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
     assert ctx.check() == 0
     assert np.array_equal(f_walks.cpu().numpy(), w), "fused: walks differ"
     assert_table_equal((f_off, f_ids, f_cnt), table, "fused rpe")
+    if queries is not None and np.asarray(queries).shape[0] > 0:
+        # query-level RPE-IDs of every walk position
+        got = binding.query_rpe_ids(ctx, f_walks, f_off, f_ids, dev(np.asarray(queries, np.int32)),
+                                    max_set=1 + M * m)
+        assert ctx.check() == 0
+        want = oracle.query_rpe_ids(w, table[0], table[1], queries)
+        assert np.array_equal(got.cpu().numpy().astype(np.int64), want), "query RPE-IDs differ"
     return out
 
 
@@ -350,6 +357,25 @@ def test_fused_kernel_waits_are_bounded(ctx):
     assert_table_equal((f_off, f_ids, f_cnt), want, "rpe after the limit was restored")
 
 
+def test_query_rpe_ids_problems_are_flagged(ctx):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(32, dtype=np.int32)
+    walks, off, ids, cnt = binding.sample_walks_rpe(ctx, dev(rp), dev(ci), dev(seeds), wl.M, wl.m, 0)
+    q = np.array([[1, 2], [5, 32], [3, 4]], dtype=np.int32)          # 32 is not a block
+    got = binding.query_rpe_ids(ctx, walks, off, ids, dev(q), max_set=61).cpu().numpy()
+    assert ctx.check() == binding.DEV_BAD_QUERY
+    assert (got[1] == -1).all()
+    want = oracle.query_rpe_ids(walks.cpu().numpy(), off.cpu().numpy(), ids.cpu().numpy(),
+                                q[[0, 2]])
+    assert np.array_equal(got[[0, 2]].astype(np.int64), want)
+    sizes = np.diff(off.cpu().numpy())
+    big = int(np.argmax(sizes))
+    got = binding.query_rpe_ids(ctx, walks, off, ids, dev(np.array([[big, 0]], np.int32)),
+                                max_set=int(sizes[big]) - 1)
+    assert ctx.check() == binding.DEV_SET_TOO_LARGE and bool((got == -1).all())
+
+
 def test_join_problems_are_flagged(ctx):
     wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
     rp, ci = synth.make_graph(wl)
@@ -490,6 +516,26 @@ def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
         [np.arange(joff_h[q], joff_h[q + 1]) for q in qpick])).cuda()
     assert np.array_equal(jids[jrows].cpu().numpy(), w_jids), "sampled join ids differ"
     assert np.array_equal(rows_u16(jcnt, jrows), w_jcnt), "sampled join counts differ"
+
+    # query-level RPE-IDs: the sampled queries against the oracle, invariants over all
+    qids = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m)
+    assert ctx.check() == 0
+    sub_w = oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m, wl.rng_seed)
+    w_ids = oracle.query_rpe_ids(sub_w, sub_table[0], sub_table[1], local)
+    # the oracle's rows index the sub-table; turn both sides into (block, row inside block)
+    sub_off = sub_table[0]
+    got_ids = qids[torch.from_numpy(qpick).cuda()].cpu().numpy().astype(np.int64)
+    for col in range(k):
+        g_loc = got_ids[..., col] - off_h[sub_q[:, col]][:, None, None, None]
+        w_loc = w_ids[..., col] - sub_off[local[:, col]][:, None, None, None]
+        absent = w_ids[..., col] < 0
+        assert np.array_equal(got_ids[..., col] < 0, absent), "RPE-ID presence differs"
+        assert np.array_equal(g_loc[~absent], w_loc[~absent]), "sampled RPE-IDs differ"
+    own = torch.stack([qids[:, j, :, :, j] for j in range(k)], dim=1)      # [Q][k][M][L]
+    assert bool((own >= 0).all()), "a walk entry is missing from its own block"
+    assert bool((ids[own.long()] == walks[d_q.long()]).all()), "own RPE-ID names another node"
+    del qids, own
+    print(f"[{name}] query RPE-IDs parity + invariants ok", flush=True)
 
     # invariants over the whole join: sizes bounded by the parts, every half sums to M
     sizes = (off[1:] - off[:-1])[d_q.long()]
