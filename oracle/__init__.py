@@ -55,6 +55,9 @@ def _load():
                                              ctypes.c_int32, i32p, ctypes.c_int64,
                                              ctypes.c_int32, i64p]
         lib.oracle_query_rpe_ids.restype = ctypes.c_int
+        lib.oracle_prune_rpe.argtypes = [u16p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64,
+                                         u16p, i32p]
+        lib.oracle_prune_rpe.restype = ctypes.c_int64
         _lib = lib
     return _lib
 
@@ -163,3 +166,22 @@ def query_rpe_ids(walks, rpe_off, rpe_ids, queries) -> np.ndarray:
     if rc != 0:
         raise ValueError(f"oracle_query_rpe_ids failed with {rc}")
     return out
+
+
+def prune_rpe(rpe_cnt):
+    """(T uint16[n_T][m+1], code int32[R]): the distinct count vectors in ascending order and,
+    for every table row, the index of its vector in T."""
+    rpe_cnt = _arr(rpe_cnt, np.uint16)
+    n_rows, L = rpe_cnt.shape
+    lib = _load()
+    n_T = lib.oracle_prune_rpe(_ptr(rpe_cnt, ctypes.c_uint16), n_rows, L - 1, 0,
+                               _ptr(None, ctypes.c_uint16), _ptr(None, ctypes.c_int32))
+    if n_T < 0:
+        raise ValueError(f"oracle_prune_rpe failed with {n_T}")
+    T = np.empty((n_T, L), dtype=np.uint16)
+    code = np.empty(n_rows, dtype=np.int32)
+    n2 = lib.oracle_prune_rpe(_ptr(rpe_cnt, ctypes.c_uint16), n_rows, L - 1, n_T,
+                              _ptr(T, ctypes.c_uint16), _ptr(code, ctypes.c_int32))
+    if n2 != n_T:
+        raise ValueError(f"oracle_prune_rpe failed with {n2}")
+    return T, code

@@ -27,6 +27,11 @@
  *                          (unpruned) central array T of Sec. 3.3, so RPE-ID_{u,x} is
  *                          the index of (u, x)'s row in it, and -1 stands for "x is
  *                          not in V_u" (the all-zero vector).
+ *   oracle_prune_rpe       Sec. 3.3, last paragraph, and the last step of Algorithm 1: the
+ *                          central array T keeps every distinct RPE vector once, and
+ *                          every (u, x) keeps the index of its vector in T.  The paper
+ *                          leaves the order of T open; here T is sorted (vectors compared
+ *                          entry by entry), the canonical choice.
  *
  * Readings where the paper is silent:
  *   - a walk is stored with its start: m+1 positions, position 0 is the seed
@@ -279,4 +284,57 @@ int oracle_query_rpe_ids(const int32_t *walks, const int64_t *rpe_off, const int
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Pruning: distinct count vectors, sorted, and each row's index among them.  */
+/* ------------------------------------------------------------------------- */
+static int64_t g_vec_len; /* entries per vector, for the comparator (single-threaded code) */
+
+static int cmp_vec(const void *a, const void *b)
+{
+    const uint16_t *x = (const uint16_t *)a, *y = (const uint16_t *)b;
+    for (int64_t s = 0; s < g_vec_len; ++s)
+        if (x[s] != y[s])
+            return x[s] < y[s] ? -1 : 1;
+    return 0;
+}
+
+/* T: uint16[cap_T][m+1], code: int32[n_rows]; both may be NULL (count only).
+ * Returns the number of distinct vectors, or -2 if it exceeds cap_T (nothing is written then). */
+int64_t oracle_prune_rpe(const uint16_t *rpe_cnt, int64_t n_rows, int32_t m, int64_t cap_T,
+                         uint16_t *T, int32_t *code)
+{
+    if (n_rows < 0 || m < 1 || (n_rows > 0 && !rpe_cnt))
+        return -1;
+    const int64_t L = (int64_t)m + 1;
+    const size_t vec_bytes = (size_t)L * sizeof(uint16_t);
+    if (n_rows == 0)
+        return 0;
+    uint16_t *sorted = (uint16_t *)malloc((size_t)n_rows * vec_bytes);
+    if (!sorted)
+        return -1;
+    memcpy(sorted, rpe_cnt, (size_t)n_rows * vec_bytes);
+    g_vec_len = L;
+    qsort(sorted, (size_t)n_rows, vec_bytes, cmp_vec);
+    int64_t n_T = 0;
+    for (int64_t r = 0; r < n_rows; ++r)
+        if (r == 0 || cmp_vec(sorted + r * L, sorted + (r - 1) * L) != 0) {
+            memmove(sorted + n_T * L, sorted + r * L, vec_bytes);
+            n_T += 1;
+        }
+    if (T && code) {
+        if (n_T > cap_T) {
+            free(sorted);
+            return -2;
+        }
+        memcpy(T, sorted, (size_t)n_T * vec_bytes);
+        for (int64_t r = 0; r < n_rows; ++r) {
+            const uint16_t *hit = (const uint16_t *)bsearch(rpe_cnt + r * L, sorted, (size_t)n_T,
+                                                            vec_bytes, cmp_vec);
+            code[r] = (int32_t)((hit - sorted) / L);
+        }
+    }
+    free(sorted);
+    return n_T;
 }

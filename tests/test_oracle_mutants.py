@@ -49,6 +49,13 @@ MUTANTS = {
                                "hit ? rpe_off[b] + (int64_t)(hit - set) : 0;"),
     "ids_columns_transposed": ("out[(((q * k + j) * M * L) + t) * k + j2] =",
                                "out[(((q * k + j2) * M * L) + t) * k + j] ="),
+    "prune_compares_first_entry_only": ("for (int64_t s = 0; s < g_vec_len; ++s)\n        if (x[s] != y[s])",
+                                        "for (int64_t s = 0; s < 1; ++s)\n        if (x[s] != y[s])"),
+    "prune_descending": ("return x[s] < y[s] ? -1 : 1;", "return x[s] < y[s] ? 1 : -1;"),
+    "prune_keeps_duplicates": ("if (r == 0 || cmp_vec(sorted + r * L, sorted + (r - 1) * L) != 0) {",
+                               "if (1) {"),
+    "prune_code_off_by_one": ("code[r] = (int32_t)((hit - sorted) / L);",
+                              "code[r] = (int32_t)((hit - sorted) / L) + (r > 0);"),
     "join_copies_wrong_row": ("memcpy(dst, rpe_cnt + head[j] * L,", "memcpy(dst, rpe_cnt + rpe_off[queries[q * k + j]] * L,"),
 }
 
@@ -65,6 +72,9 @@ PIN_TESTS = [
     "test_join_symmetry_and_repeated_node",
     "test_query_rpe_ids_invariants_and_agreement_with_the_union_join",
     "test_query_rpe_ids_on_the_paper_fragment",
+    "test_prune_equals_python_set_and_dictionary",
+    "test_prune_on_the_paper_fragment",
+    "test_prune_orders_by_entries_not_by_bytes",
 ]
 PARAM_PIN_TESTS = [
     ("test_walk_distribution_matches_enumeration", ("lollipop", 4)),
@@ -113,7 +123,7 @@ def test_planted_mistake_is_caught(name, tmp_path, golden_dir, monkeypatch):
     real = oracle._load()
     mutant = ctypes.CDLL(str(lib_path))
     for fn in ("oracle_philox4x32_10", "oracle_sample_walks", "oracle_build_rpe",
-               "oracle_join_queries", "oracle_query_rpe_ids"):
+               "oracle_join_queries", "oracle_query_rpe_ids", "oracle_prune_rpe"):
         getattr(mutant, fn).argtypes = getattr(real, fn).argtypes
         getattr(mutant, fn).restype = getattr(real, fn).restype
     monkeypatch.setattr(oracle, "_lib", mutant)

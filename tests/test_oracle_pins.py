@@ -586,3 +586,47 @@ def test_query_rpe_ids_on_the_paper_fragment(golden_dir):
 def test_query_rpe_ids_empty_query_list():
     w, off, ids, cnt = _small_walks_and_table(6, 2, 5)
     assert oracle.query_rpe_ids(w, off, ids, np.zeros((0, 2), dtype=np.int32)).shape[0] == 0
+
+
+# --------------------------------------------------------------------------- #
+# pruning of the central RPE array (Sec. 3.3; Algorithm 1, last step)
+# --------------------------------------------------------------------------- #
+def test_prune_equals_python_set_and_dictionary():
+    w, off, ids, cnt = _small_walks_and_table()
+    T, code = oracle.prune_rpe(cnt)
+    rows = [tuple(r) for r in cnt.tolist()]
+    want_T = sorted(set(rows))                       # tuples compare entry by entry
+    index = {v: i for i, v in enumerate(want_T)}
+    assert [tuple(r) for r in T.tolist()] == want_T
+    assert code.tolist() == [index[r] for r in rows]
+    assert len(want_T) < len(rows)                   # there is something to prune
+    # NumPy's row-wise unique is the same operation
+    T2, inv = np.unique(cnt, axis=0, return_inverse=True)
+    assert np.array_equal(T, T2) and np.array_equal(code, inv.reshape(-1))
+    # T(RPE-ID) gives the vector back
+    assert np.array_equal(T[code], cnt)
+
+
+def test_prune_on_the_paper_fragment(golden_dir):
+    # Sec. 3.3: nodes a and v carry the same RPE value [0,0,1] in H_u and so get the same RPE-ID
+    ex = _read_example(golden_dir)
+    m, M = ex["m"][0], ex["M"][0]
+    walks = np.array([ex["walks_u"], ex["walks_v"]], dtype=np.int32).reshape(2, M, m + 1)
+    off, ids, cnt = oracle.build_rpe(walks)
+    T, code = oracle.prune_rpe(cnt)
+    blk = slice(off[0], off[1])
+    row = {int(x): int(c) for x, c in zip(ids[blk], code[blk])}
+    assert row[2] == row[1]                          # a and v
+    assert T[row[2]].tolist() == ex["X_u,a"]
+    assert row[0] != row[2] and T[row[0]].tolist() == ex["X_u,u"]
+    assert T.shape[0] < cnt.shape[0]
+
+
+def test_prune_orders_by_entries_not_by_bytes():
+    # 256 = bytes (0, 1) on a little-endian host: a byte-wise comparison would put it before 1
+    cnt = np.array([[256, 0], [1, 7], [1, 2], [256, 0], [0, 65535]], dtype=np.uint16)
+    T, code = oracle.prune_rpe(cnt)
+    assert T.tolist() == [[0, 65535], [1, 2], [1, 7], [256, 0]]
+    assert code.tolist() == [3, 2, 1, 3, 0]
+    T0, code0 = oracle.prune_rpe(np.zeros((0, 3), dtype=np.uint16))
+    assert T0.shape == (0, 3) and code0.size == 0
