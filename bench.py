@@ -108,6 +108,9 @@ def main() -> int:
                     help="also time surel_query_rpe_ids (Sec. 3.4's per-walk-position form of the "
                          "join) after the timed region; reported under 'query_rpe_ids', not part "
                          "of 'value'")
+    ap.add_argument("--prune", action="store_true",
+                    help="also time surel_prune_rpe (Sec. 3.3: distinct count vectors stored once) "
+                         "after the timed region; reported under 'prune_rpe', not part of 'value'")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
@@ -264,6 +267,24 @@ def main() -> int:
             "algorithmic_bytes": q_bytes,
             "hbm_frac": round(q_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del qid
+    if args.prune:
+        cap_T = 1 << 20
+        T = torch.empty((cap_T, L), dtype=torch.uint16, device="cuda")
+        code = torch.empty(R, dtype=torch.int32, device="cuda")
+        rc, n_T = binding.prune_rpe_raw(ctx, rpe_cnt[:R], cap_T, T, code)
+        assert rc == binding.OK, rc
+        ctx.profile(True)
+        for _ in range(args.steps):
+            rc, n_T = binding.prune_rpe_raw(ctx, rpe_cnt[:R], cap_T, T, code)
+        ms = ctx.profile_read()["prune"][0] / args.steps
+        ctx.profile(False)
+        assert ctx.check() == 0
+        p_bytes = R * 2 * L + R * 4 + n_T * 2 * L          # vectors read, codes and T written
+        out["prune_rpe"] = {
+            "ms": round(ms, 4), "rows_per_s": R / (ms * 1e-3), "distinct_vectors": n_T,
+            "algorithmic_bytes": p_bytes,
+            "hbm_frac": round(p_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del T, code
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
         b = torch.empty_like(a)

@@ -10,8 +10,9 @@
  *   surel_join_queries   per query tuple Q, the union of the V_u, u in Q, and for each
  *                        node x of it the query-level RPE X_{Q,x} = [X_{u,x}]_{u in Q},
  *                        zeros where x is not in V_u (Sec. 3.4, set-union form).
- * Beside them: surel_sample_walks_rpe (the first two in one kernel) and surel_query_rpe_ids
- * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values).
+ * Beside them: surel_sample_walks_rpe (the first two in one kernel), surel_query_rpe_ids
+ * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values) and
+ * surel_prune_rpe (Sec. 3.3: the distinct count vectors stored once, rows re-indexed).
  *
  * Conventions
  *   - Plain C ABI.  Pointers named d_* are DEVICE memory owned by the caller, on the
@@ -86,6 +87,7 @@ extern "C" {
 #define SUREL_MAX_WALK_ENTRIES 2048   /* build_rpe: M*(m+1) keys are sorted in one wavefront */
 #define SUREL_MAX_SET     2048        /* join: rows per block of the RPE table               */
 #define SUREL_MAX_TUPLE   3           /* join: k                                             */
+#define SUREL_MAX_DISTINCT 16777216   /* prune: cap_T (2^24 distinct count vectors)          */
 
 /* kernel groups for surel_profile_read */
 #define SUREL_K_WALK        0   /* walk kernel                                        */
@@ -98,7 +100,8 @@ extern "C" {
 #define SUREL_K_EDGE_RECORDS 7  /* expansion of the CSR into per-edge neighbour records
                                    (both walk calls, large jobs only)                 */
 #define SUREL_K_QUERY_IDS   8   /* surel_query_rpe_ids                                */
-#define SUREL_K_COUNT       9
+#define SUREL_K_PRUNE       9   /* surel_prune_rpe (all its launches)                 */
+#define SUREL_K_COUNT       10
 
 typedef struct surel_ctx surel_ctx;
 
@@ -215,8 +218,26 @@ int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d
                         int32_t m, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                         int32_t k, int32_t* d_out);
 
+/* Sec. 3.3, last paragraph / Algorithm 1, last step ("prune T"): the count vectors of the RPE
+ * table repeat a lot, so they are stored once.  d_T receives the distinct vectors, sorted
+ * (vectors compared entry by entry; the paper leaves the order open, sorted makes it unique),
+ * and d_code[r] the index in d_T of row r's vector: d_T[d_code[r]] == d_rpe_cnt[r].  A row of
+ * surel_query_rpe_ids' output, sent through d_code, is the paper's re-indexed RPE-ID.
+ *   d_rpe_cnt    uint16[n_rows][m+1] (device, read-only).
+ *   cap_T        vectors that d_T can hold, 1 .. SUREL_MAX_DISTINCT.
+ *   d_T          uint16[cap_T][m+1], d_code int32[n_rows] (device, written).
+ *   h_n_T        host int64, required: the number of distinct vectors.  The call always waits
+ *                for its own work (the sort is sized by that number).
+ * The context's workspace grows by 292 bytes per unit of cap_T (rounded up to a power of two).
+ * Returns SUREL_E_CAPACITY when there are more than cap_T distinct vectors (*h_n_T says how
+ * many; d_T and d_code are then undefined).  Limits: 1 <= m <= SUREL_MAX_STEPS, n_rows >= 0.
+ * Device-detected: STALL. */
+int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, int32_t m,
+                    int64_t cap_T, uint16_t* d_T, int32_t* d_code, int64_t* h_n_T);
+
 /* Every wait inside the fused kernel of surel_sample_walks_rpe (a wave waiting for an offset,
- * the offset scan waiting for a row count) gives up after `spins` polls, raises
+ * the offset scan waiting for a row count) and inside surel_prune_rpe (a lane waiting for
+ * another to finish writing a hash slot) gives up after `spins` polls, raises
  * SUREL_DEV_STALL and lets the kernel end.  The default (2^22 polls, seconds) is never reached
  * by a healthy run; tests set 0 to see the bounded exit.  Errors: SUREL_E_CTX. */
 int surel_set_spin_limit(surel_ctx* ctx, uint32_t spins);

@@ -20,13 +20,14 @@ DEV_SET_TOO_LARGE, DEV_CAPACITY, DEV_BAD_TABLE, DEV_BAD_SIZES = 0x10, 0x20, 0x40
 DEV_STALL = 0x100
 MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
+MAX_DISTINCT = 1 << 24
 
 (K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_WALK_RPE,
- K_EDGE_RECORDS, K_QUERY_IDS, K_COUNT) = range(10)
+ K_EDGE_RECORDS, K_QUERY_IDS, K_PRUNE, K_COUNT) = range(11)
 KERNEL_NAMES = {K_WALK: "walk", K_RPE_COUNT: "rpe_count", K_RPE_FILL: "rpe_fill",
                 K_JOIN_COUNT: "join_count", K_JOIN_FILL: "join_fill", K_SCAN: "scan",
                 K_WALK_RPE: "walk_rpe", K_EDGE_RECORDS: "edge_records",
-                K_QUERY_IDS: "query_ids"}
+                K_QUERY_IDS: "query_ids", K_PRUNE: "prune"}
 
 _vp = ctypes.c_void_p
 _i32, _i64, _u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
@@ -48,6 +49,8 @@ SIGNATURES = {
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_query_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp,
                                            _i64, _i32, _vp]),
+    "surel_prune_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i64, _vp, _vp,
+                                       ctypes.POINTER(_i64)]),
     "surel_set_spin_limit": (ctypes.c_int, [_vp, ctypes.c_uint32]),
     "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
     "surel_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
@@ -314,3 +317,26 @@ def query_rpe_ids(ctx: Context, walks: torch.Tensor, rpe_off: torch.Tensor, rpe_
     if rc != OK:
         raise SurelError(rc, "surel_query_rpe_ids")
     return out
+
+
+def prune_rpe_raw(ctx: Context, rpe_cnt: torch.Tensor, cap_T: int, T: torch.Tensor,
+                  code: torch.Tensor):
+    """One call of surel_prune_rpe into caller buffers.  Returns (status, n_T)."""
+    n_rows, L = rpe_cnt.shape
+    n_T = _i64(-1)
+    rc = load().surel_prune_rpe(ctx.handle, _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), n_rows, L - 1,
+                                cap_T, _ptr(T, torch.uint16, "T"), _ptr(code, torch.int32, "code"),
+                                ctypes.byref(n_T))
+    return rc, n_T.value
+
+
+def prune_rpe(ctx: Context, rpe_cnt: torch.Tensor, cap_T: int = 1 << 20):
+    """(T uint16[n_T][m+1], code int32[R]) on the GPU: the distinct count vectors, sorted, and
+    every row's index among them."""
+    n_rows, L = rpe_cnt.shape
+    T = torch.empty((cap_T, L), dtype=torch.uint16, device=rpe_cnt.device)
+    code = torch.empty(n_rows, dtype=torch.int32, device=rpe_cnt.device)
+    rc, n_T = prune_rpe_raw(ctx, rpe_cnt, cap_T, T, code)
+    if rc != OK:
+        raise SurelError(rc, "surel_prune_rpe")
+    return T[:n_T], code

@@ -23,6 +23,8 @@ struct surel_ctx {
     size_t rec_bytes = 0;
     void* d_lb = nullptr;         // grow-only workspace: look-back words of the fused kernel
     size_t lb_bytes = 0;
+    void* d_prune = nullptr;      // grow-only workspace: hash slots, sort list, counters of prune
+    size_t prune_bytes = 0;
     // optional per-kernel timing (surel_profile_*)
     struct Span {
         int kernel;
@@ -235,6 +237,7 @@ void surel_destroy(surel_ctx* ctx) {
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
     if (ctx->d_rec) (void)hipFree(ctx->d_rec);
     if (ctx->d_lb) (void)hipFree(ctx->d_lb);
+    if (ctx->d_prune) (void)hipFree(ctx->d_prune);
     if (ctx->d_err) (void)hipFree(ctx->d_err);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     delete ctx;
@@ -453,6 +456,47 @@ int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d
                                              ctx->d_err);
     if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
     return hrc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
+}
+
+int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, int32_t m,
+                    int64_t cap_T, uint16_t* d_T, int32_t* d_code, int64_t* h_n_T) {
+    if (m < 1 || m > SUREL_MAX_STEPS || n_rows < 0) return SUREL_E_RANGE;
+    if (cap_T < 1 || cap_T > SUREL_MAX_DISTINCT) return SUREL_E_RANGE;
+    if (!d_T || !h_n_T || (n_rows > 0 && (!d_rpe_cnt || !d_code))) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    const size_t slot_bytes = surel::prune_slot_bytes(cap_T);
+    const size_t list_bytes = align_up(surel::prune_list_bytes(cap_T), 256);
+    const size_t need = slot_bytes + list_bytes + 256;
+    if (need > ctx->prune_bytes) {
+        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+        if (ctx->d_prune) (void)hipFree(ctx->d_prune);
+        ctx->d_prune = nullptr;
+        ctx->prune_bytes = 0;
+        if (hipMalloc(&ctx->d_prune, need) != hipSuccess) return SUREL_E_HIP;
+        ctx->prune_bytes = need;
+    }
+    char* ws = static_cast<char*>(ctx->d_prune);
+    uint32_t* slots = reinterpret_cast<uint32_t*>(ws);
+    uint32_t* list = reinterpret_cast<uint32_t*>(ws + slot_bytes);
+    unsigned long long* counters = reinterpret_cast<unsigned long long*>(ws + slot_bytes + list_bytes);
+    KernelSpan span(ctx, SUREL_K_PRUNE);
+    if (surel::launch_prune_collect(ctx->stream, ctx->n_cu, d_rpe_cnt, n_rows, m, cap_T, slots,
+                                    counters, d_code, ctx->spin_limit, ctx->d_err) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipMemcpyAsync(ctx->h_pinned, counters, sizeof(int64_t), hipMemcpyDeviceToHost,
+                       ctx->stream) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    const int64_t n_T = ctx->h_pinned[0];
+    *h_n_T = n_T;
+    if (n_T > cap_T) return SUREL_E_CAPACITY;
+    if (surel::launch_prune_finish(ctx->stream, ctx->n_cu, n_rows, m, cap_T, n_T, slots, counters,
+                                   list, d_T, d_code) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    return SUREL_OK;
 }
 
 int surel_set_spin_limit(surel_ctx* ctx, uint32_t spins) {

@@ -62,6 +62,22 @@ hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, con
                             const int32_t* queries, int64_t n_queries, int32_t k, int32_t* out,
                             uint32_t* err);
 
+// prune.hip.  Distinct count vectors of the table, sorted, and every row's index among them.
+// slots: prune_slot_bytes(cap_T) bytes, list: prune_list_bytes(cap_T) bytes, counters: two
+// 64-bit words (all device scratch).  launch_prune_collect fills the hash set and leaves
+// counters[0] = number of distinct vectors; the host reads it and, if it fits cap_T, calls
+// launch_prune_finish with it.
+size_t prune_slot_bytes(int64_t cap_T);
+size_t prune_list_bytes(int64_t cap_T);
+hipError_t launch_prune_collect(hipStream_t stream, int n_cu, const uint16_t* cnt, int64_t n_rows,
+                                int32_t m, int64_t cap_T, uint32_t* slots,
+                                unsigned long long* counters, int32_t* code, uint32_t spin_limit,
+                                uint32_t* err);
+hipError_t launch_prune_finish(hipStream_t stream, int n_cu, int64_t n_rows, int32_t m,
+                               int64_t cap_T, int64_t n_T, uint32_t* slots,
+                               unsigned long long* counters, uint32_t* list, uint16_t* T,
+                               int32_t* code);
+
 // scan.hip.  off[0..n] = exclusive prefix sums of counts[0..n-1] (off[n] = total).
 // partials: device scratch of scan_partials_len(n) int64.
 int64_t scan_partials_len(int64_t n);

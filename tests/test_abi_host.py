@@ -210,6 +210,30 @@ def test_query_rpe_ids_argument_checks(lib, kw, want):
     assert lib.surel_query_rpe_ids(*ids_args(**kw)) == want
 
 
+def prune_args(**kw):
+    a = dict(ctx=NULL, cnt=P, n_rows=100, m=4, cap_T=1000, T=P, code=P,
+             n_T=ctypes.pointer(ctypes.c_int64(0)))
+    a.update(kw)
+    return [a[k] for k in ("ctx", "cnt", "n_rows", "m", "cap_T", "T", "code", "n_T")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(m=0), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(n_rows=-1), binding.E_RANGE),
+    (dict(cap_T=0), binding.E_RANGE),
+    (dict(cap_T=binding.MAX_DISTINCT + 1), binding.E_RANGE),
+    (dict(cnt=NULL), binding.E_NULL),
+    (dict(T=NULL), binding.E_NULL),
+    (dict(code=NULL), binding.E_NULL),
+    (dict(n_T=NULL), binding.E_NULL),
+    (dict(cnt=NULL, code=NULL, n_rows=0), binding.E_CTX),
+])
+def test_prune_rpe_argument_checks(lib, kw, want):
+    assert lib.surel_prune_rpe(*prune_args(**kw)) == want
+
+
 def join_args(**kw):
     a = dict(ctx=NULL, off=P, ids=P, cnt=P, n_blocks=100, m=4, max_set=201, queries=P, n_q=10,
              k=2, cap_rows=1000, joff=P, jids=P, jcnt=P, h_rows=NULL)

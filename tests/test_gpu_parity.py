@@ -82,6 +82,12 @@ def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
     assert ctx.check() == 0
     assert np.array_equal(f_walks.cpu().numpy(), w), "fused: walks differ"
     assert_table_equal((f_off, f_ids, f_cnt), table, "fused rpe")
+    # the pruned central array and the re-indexed rows
+    T, code = binding.prune_rpe(ctx, f_cnt, cap_T=max(1, table[2].shape[0]))
+    assert ctx.check() == 0
+    want_T, want_code = oracle.prune_rpe(table[2])
+    assert np.array_equal(host_u16(T), want_T), "pruned array differs"
+    assert np.array_equal(code.cpu().numpy(), want_code), "re-indexed rows differ"
     if queries is not None and np.asarray(queries).shape[0] > 0:
         # query-level RPE-IDs of every walk position
         got = binding.query_rpe_ids(ctx, f_walks, f_off, f_ids, dev(np.asarray(queries, np.int32)),
@@ -357,6 +363,31 @@ def test_fused_kernel_waits_are_bounded(ctx):
     assert_table_equal((f_off, f_ids, f_cnt), want, "rpe after the limit was restored")
 
 
+def test_prune_capacity_and_degenerate_tables(ctx):
+    rng = np.random.default_rng(3)
+    cnt = rng.integers(0, 3, size=(5000, 4)).astype(np.uint16)          # at most 81 vectors
+    want_T, want_code = oracle.prune_rpe(cnt)
+    d_cnt = dev(cnt.view(np.int16)).view(torch.uint16)
+    n_T = want_T.shape[0]
+    T = torch.zeros((n_T, 4), dtype=torch.int16, device="cuda").view(torch.uint16)
+    code = torch.empty(5000, dtype=torch.int32, device="cuda")
+    rc, got = binding.prune_rpe_raw(ctx, d_cnt, n_T, T, code)           # exactly enough room
+    assert rc == binding.OK and got == n_T and ctx.check() == 0
+    assert np.array_equal(host_u16(T), want_T) and np.array_equal(code.cpu().numpy(), want_code)
+    rc, got = binding.prune_rpe_raw(ctx, d_cnt, n_T - 1, T, code)       # one too few
+    assert rc == binding.E_CAPACITY and got == n_T
+    assert ctx.check() == binding.DEV_CAPACITY
+    # one row, all rows equal, widest vectors (m = 15), no rows
+    for arr in (np.array([[7, 0, 9]], np.uint16), np.full((300, 5), 65535, np.uint16),
+                rng.integers(0, 2, size=(700, 16)).astype(np.uint16),
+                np.zeros((0, 4), np.uint16)):
+        T, code = binding.prune_rpe(ctx, dev(arr.view(np.int16)).view(torch.uint16), cap_T=1024)
+        assert ctx.check() == 0
+        w_T, w_code = oracle.prune_rpe(arr)
+        assert np.array_equal(host_u16(T).reshape(w_T.shape), w_T)
+        assert np.array_equal(code.cpu().numpy(), w_code)
+
+
 def test_query_rpe_ids_problems_are_flagged(ctx):
     wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
     rp, ci = synth.make_graph(wl)
@@ -516,6 +547,28 @@ def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
         [np.arange(joff_h[q], joff_h[q + 1]) for q in qpick])).cuda()
     assert np.array_equal(jids[jrows].cpu().numpy(), w_jids), "sampled join ids differ"
     assert np.array_equal(rows_u16(jcnt, jrows), w_jcnt), "sampled join counts differ"
+
+    # pruning: T is strictly ascending, every row finds its vector through its code, every entry
+    # of T is used, and on the sampled blocks the oracle's distinct vectors are all in T with
+    # the same order; together that is the sorted set of distinct vectors, which is unique
+    T, code = binding.prune_rpe(ctx, cnt[:R])
+    assert ctx.check() == 0
+    T_h = host_u16(T)
+    as_tuples = [tuple(r) for r in T_h.tolist()]
+    assert all(a < b for a, b in zip(as_tuples, as_tuples[1:])), "T is not strictly ascending"
+    code_l = code.long()
+    for s in range(0, R, 1 << 26):
+        e = min(R, s + (1 << 26))
+        assert torch.equal(T.view(torch.int16)[code_l[s:e]], cnt.view(torch.int16)[s:e]), \
+            "a row's code does not name its vector"
+    assert int(torch.bincount(code_l, minlength=T.shape[0]).min()) > 0, "unused entry in T"
+    s_T, s_code = oracle.prune_rpe(t_cnt)
+    pos = {v: i for i, v in enumerate(as_tuples)}
+    ranks = [pos[tuple(r)] for r in s_T.tolist()]
+    assert ranks == sorted(ranks)
+    assert np.array_equal(np.asarray(ranks)[s_code], code[rows_d].cpu().numpy())
+    print(f"[{name}] pruning ok: {T.shape[0]} distinct vectors for {R} rows", flush=True)
+    del T, code, code_l
 
     # query-level RPE-IDs: the sampled queries against the oracle, invariants over all
     qids = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m)
