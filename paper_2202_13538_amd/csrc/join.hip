@@ -30,6 +30,8 @@ namespace surel {
 constexpr uint16_t kNoSrc = 0xFFFFu;
 constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
 constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
+constexpr int kPairRounds = 1;           // rounds of 64 union rows a wave gathers together (pairs;
+                                         // more than one was measured and gains nothing)
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {
@@ -351,57 +353,85 @@ __device__ __forceinline__ void join_one_query(
             }
             return;
         }
-        // pairs: one round of 64 rows at a time
-        for (int r0 = 0; r0 < n_out; r0 += kWave) {
-            const int r = min(r0 + lane, n_out - 1);
-            uint16_t v[K * LT];
-            uint32_t id = 0;
-            bool present[K];
+        // pairs: kPairRounds rounds of 64 rows are gathered together (all their loads are in
+        // flight before the first is waited for: a wave's time is a chain of memory round
+        // trips), then the rounds go out one after the other
+        const uint32_t* cnt_words = reinterpret_cast<const uint32_t*>(rpe_cnt);
+        for (int r0 = 0; r0 < n_out; r0 += kPairRounds * kWave) {
+            constexpr int kCover = LT / 2 + 1;  // aligned words that cover a vector
+            uint32_t raw[kPairRounds][K][kCover + 1];
+            uint32_t shift[kPairRounds][K];
+            bool present[kPairRounds][K];
+            uint32_t id[kPairRounds];
 #pragma unroll
-            for (int j = K - 1; j >= 0; --j) {
-                const uint16_t sj = src[j * src_stride + r];
-                // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
-                present[j] = (int)sj < n[j];
-                const uint32_t id_j = ids_lds[j * max_set + (present[j] ? sj : 0)];
-                if (present[j]) id = id_j;
-                // unconditional loads, from the table's first row where the list has no row for
-                // the node: a branch would make every load wait for the one before it
-                const uint16_t* from = present[j] ? rpe_cnt + (lo[j] + sj) * LT : rpe_cnt;
+            for (int g = 0; g < kPairRounds; ++g) {
+                const int r = min(r0 + g * kWave + lane, n_out - 1);
+                id[g] = 0;
 #pragma unroll
-                for (int e = 0; e < LT; ++e) v[j * LT + e] = from[e];
+                for (int j = K - 1; j >= 0; --j) {
+                    const uint16_t sj = src[j * src_stride + r];
+                    // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
+                    present[g][j] = (int)sj < n[j];
+                    const uint32_t id_j = ids_lds[j * max_set + (present[g][j] ? sj : 0)];
+                    if (present[g][j]) id[g] = id_j;
+                    // unconditional loads, from the table's first row where the list has no
+                    // row for the node: a branch would make every load wait for the one
+                    // before it.  A vector is read as the aligned words that cover it
+                    // (misaligned wide loads are taken apart lane by lane by the L1) and
+                    // shifted into place afterwards; the last word may reach one count past
+                    // the vector, never past the word that holds the table's last count.
+                    const int64_t first = present[g][j] ? (lo[j] + sj) * LT : 0;  // uint16 index
+                    shift[g][j] = (uint32_t)(first & 1) * 2u;
+                    const uint32_t* aligned = cnt_words + (first >> 1);
+#pragma unroll
+                    for (int t = 0; t < kCover; ++t)
+                        raw[g][j][t] = (LT % 2 == 0 && t == kCover - 1) ? 0u : aligned[t];
+                    raw[g][j][kCover] = 0u;
+                }
             }
 #pragma unroll
-            for (int j = 0; j < K; ++j) {
+            for (int g = 0; g < kPairRounds; ++g) {
+                if (r0 + g * kWave >= n_out) break;
+                uint16_t v[K * LT];
 #pragma unroll
-                for (int e = 0; e < LT; ++e)
-                    if (!present[j]) v[j * LT + e] = 0;
-            }
-            const bool live = r0 + lane < n_out;
-            if (live) out_ids[off + r] = (int32_t)id;
-            if constexpr (LT % 2 == 0) {
-                // count vectors of whole words: a lane's row is stored from its registers (the
-                // rows of neighbouring lanes adjoin, so the stores of a wave are contiguous)
-                if (live) {
-                    uint32_t* row_words = out_words + (int64_t)r * kWords;
+                for (int j = 0; j < K; ++j) {
+#pragma unroll
+                    for (int e = 0; e < LT; ++e) {
+                        const uint32_t word = __builtin_amdgcn_alignbyte(
+                            raw[g][j][e / 2 + 1], raw[g][j][e / 2], shift[g][j]);
+                        const uint32_t c = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
+                        v[j * LT + e] = present[g][j] ? (uint16_t)c : (uint16_t)0;
+                    }
+                }
+                const int r = r0 + g * kWave + lane;
+                const bool live = r < n_out;
+                if (live) out_ids[off + r] = (int32_t)id[g];
+                if constexpr (LT % 2 == 0) {
+                    // count vectors of whole words: a lane's row is stored from its registers
+                    // (the rows of neighbouring lanes adjoin, so a wave's stores are contiguous)
+                    if (live) {
+                        uint32_t* row_words = out_words + (int64_t)r * kWords;
+#pragma unroll
+                        for (int d = 0; d < kWords; ++d)
+                            row_words[d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+                    }
+                } else {
+                    // an odd number of 16-bit counts per list: the rows are put together in an
+                    // LDS tile laid out like the output and go out as whole words, lane by lane
 #pragma unroll
                     for (int d = 0; d < kWords; ++d)
-                        row_words[d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
-                }
-            } else {
-                // an odd number of 16-bit counts per list: the rows are put together in an LDS
-                // tile laid out like the output and go out as whole words, lane by lane
+                        tile32[lane * kWords + d] =
+                            (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+                    wave_sync();
+                    const int n_words = min(kWave, n_out - (r0 + g * kWave)) * kWords;
+                    uint32_t* dst = out_words + (int64_t)(r0 + g * kWave) * kWords;
 #pragma unroll
-                for (int d = 0; d < kWords; ++d)
-                    tile32[lane * kWords + d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
-                wave_sync();
-                const int n_words = min(kWave, n_out - r0) * kWords;
-                uint32_t* dst = out_words + (int64_t)r0 * kWords;
-#pragma unroll
-                for (int d = 0; d < kWords; ++d) {
-                    const int t = d * kWave + lane;
-                    if (t < n_words) dst[t] = tile32[t];
+                    for (int d = 0; d < kWords; ++d) {
+                        const int t = d * kWave + lane;
+                        if (t < n_words) dst[t] = tile32[t];
+                    }
+                    wave_sync();
                 }
-                wave_sync();
             }
         }
         return;
