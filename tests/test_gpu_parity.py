@@ -326,6 +326,28 @@ def test_fused_bad_seed_capacity_and_count_only(ctx):
     assert rc == binding.OK and rows == 0 and int(off[0]) == 0
 
 
+@pytest.mark.parametrize("M,m", [(50, 4), (200, 3)])
+def test_fused_kernel_seed_counts_around_its_group_and_window_sizes(ctx, M, m):
+    # seeds are handed out in groups of 8 and the offset scan reads 2048 counts a round: seed
+    # counts on, just below and just above those sizes, against the two-call path
+    wl = synth.Workload("t", "rmat", 2048, 12000, 0.0, M, m, 0, 2, "uniform", graph_seed=5)
+    rp, ci = synth.make_graph(wl)
+    d_rp, d_ci = dev(rp), dev(ci)
+    rng = np.random.default_rng(8)
+    all_seeds = dev(rng.integers(0, wl.n_nodes, size=20000).astype(np.int32))
+    for n in (1, 2, 7, 8, 9, 15, 16, 17, 63, 64, 65, 511, 2047, 2048, 2049, 4104, 16384, 16391,
+              20000):
+        d_seeds = all_seeds[:n].contiguous()
+        walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, 11)
+        off, ids, cnt = binding.build_rpe(ctx, walks, wl.n_nodes)
+        f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, d_seeds, M, m, 11)
+        assert ctx.check() == 0
+        assert torch.equal(f_walks, walks), f"walks differ at {n} seeds"
+        assert torch.equal(f_off, off), f"offsets differ at {n} seeds"
+        assert torch.equal(f_ids, ids), f"ids differ at {n} seeds"
+        assert torch.equal(f_cnt.view(torch.int16), cnt.view(torch.int16)), f"counts differ at {n}"
+
+
 def test_fused_kernel_waits_are_bounded(ctx):
     # with a spin limit of zero every wait inside the fused kernel gives up at once: the kernel
     # must still end, say so, and write nothing out of place; the default limit then gives the
