@@ -58,6 +58,10 @@ def _load():
         lib.oracle_prune_rpe.argtypes = [u16p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64,
                                          u16p, i32p]
         lib.oracle_prune_rpe.restype = ctypes.c_int64
+        lib.oracle_bfs_batch.argtypes = [i32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                         i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                         i32p, i32p, i64p]
+        lib.oracle_bfs_batch.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -185,3 +189,23 @@ def prune_rpe(rpe_cnt):
     if n2 != n_T:
         raise ValueError(f"oracle_prune_rpe failed with {n2}")
     return T, code
+
+
+def bfs_batch(queries, n_nodes: int, start, B1: int, B2: int):
+    """(vbar int32[<=B1], batch int32[<=B2]): the node set and the queries that a breadth-first
+    search from the seed-set `start` over query-sharing nodes reaches, each in the order reached,
+    until the node set has B1 members or the batch B2."""
+    queries = _arr(queries, np.int32)
+    if queries.ndim != 2:
+        raise ValueError("queries must be int32[n_queries][k]")
+    start = _arr(start, np.int32).reshape(-1)
+    vbar = np.empty(max(B1, 1), dtype=np.int32)
+    batch = np.empty(max(B2, 1), dtype=np.int32)
+    counts = np.zeros(2, dtype=np.int64)
+    rc = _load().oracle_bfs_batch(_ptr(queries, ctypes.c_int32), queries.shape[0],
+                                  queries.shape[1], n_nodes, _ptr(start, ctypes.c_int32),
+                                  start.shape[0], B1, B2, _ptr(vbar, ctypes.c_int32),
+                                  _ptr(batch, ctypes.c_int32), _ptr(counts, ctypes.c_int64))
+    if rc != 0:
+        raise ValueError(f"oracle_bfs_batch failed with {rc}")
+    return vbar[:counts[0]].copy(), batch[:counts[1]].copy()

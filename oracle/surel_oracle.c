@@ -32,6 +32,16 @@
  *                          every (u, x) keeps the index of its vector in T.  The paper
  *                          leaves the order of T open; here T is sorted (vectors compared
  *                          entry by entry), the canonical choice.
+ *   oracle_bfs_batch       Sec. 3.6 "Mini-batching for Training" and the BFS step of
+ *                          Algorithm 2: from a seed-set of nodes, breadth-first search
+ *                          in which two nodes are neighbours when a query holds both;
+ *                          reached queries are collected until the node set has B1
+ *                          members or the batch B2.  The paper fixes neither the order
+ *                          of the search nor what happens at the limit; here the queue
+ *                          is first-in first-out, a node's queries are taken in
+ *                          ascending index, a query's nodes in tuple order, and a query
+ *                          enters the batch only together with all its nodes (the search
+ *                          ends at the first query whose new nodes no longer fit).
  *
  * Readings where the paper is silent:
  *   - a walk is stored with its start: m+1 positions, position 0 is the seed
@@ -337,4 +347,91 @@ int64_t oracle_prune_rpe(const uint16_t *rpe_cnt, int64_t n_rows, int32_t m, int
     }
     free(sorted);
     return n_T;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Mini-batching: breadth-first search over nodes that share queries.         */
+/* ------------------------------------------------------------------------- */
+
+/* queries: int32[n_queries][k] node ids; start: the seed-set, in the order drawn (repeats are
+ * dropped).  vbar: int32[B1] receives the node set in the order reached, batch: int32[B2] the
+ * reached queries in the order reached; counts[0] = |vbar|, counts[1] = |batch|.
+ * Returns 0, or -1 for a bad argument (also a node id outside [0, n_nodes)). */
+int oracle_bfs_batch(const int32_t *queries, int64_t n_queries, int32_t k, int32_t n_nodes,
+                     const int32_t *start, int64_t n_start, int64_t B1, int64_t B2,
+                     int32_t *vbar, int32_t *batch, int64_t counts[2])
+{
+    if (n_queries < 0 || k < 1 || n_nodes < 1 || n_start < 0 || B1 < 1 || B2 < 1 || !vbar ||
+        !batch || !counts || (n_queries > 0 && !queries) || (n_start > 0 && !start))
+        return -1;
+    for (int64_t t = 0; t < n_queries * k; ++t)
+        if (queries[t] < 0 || queries[t] >= n_nodes)
+            return -1;
+    for (int64_t i = 0; i < n_start; ++i)
+        if (start[i] < 0 || start[i] >= n_nodes)
+            return -1;
+
+    /* the queries of every node, ascending: first[x] .. first[x+1] in held[] */
+    int64_t *first = (int64_t *)calloc((size_t)n_nodes + 1, sizeof(int64_t));
+    int64_t *fill = (int64_t *)calloc((size_t)n_nodes + 1, sizeof(int64_t));
+    int32_t *held = (int32_t *)malloc((size_t)(n_queries * k + 1) * sizeof(int32_t));
+    char *in_vbar = (char *)calloc((size_t)n_nodes, 1);
+    char *in_batch = (char *)calloc((size_t)n_queries + 1, 1);
+    if (!first || !fill || !held || !in_vbar || !in_batch) {
+        free(first); free(fill); free(held); free(in_vbar); free(in_batch);
+        return -3;
+    }
+    for (int64_t t = 0; t < n_queries * k; ++t)
+        first[queries[t] + 1] += 1;
+    for (int32_t x = 0; x < n_nodes; ++x)
+        first[x + 1] += first[x];
+    for (int64_t q = 0; q < n_queries; ++q)
+        for (int32_t j = 0; j < k; ++j) {
+            const int32_t x = queries[q * k + j];
+            held[first[x] + fill[x]++] = (int32_t)q;
+        }
+
+    int64_t n_v = 0, n_b = 0;
+    for (int64_t i = 0; i < n_start && n_v < B1; ++i)
+        if (!in_vbar[start[i]]) {
+            in_vbar[start[i]] = 1;
+            vbar[n_v++] = start[i];
+        }
+    int done = (n_v == B1);
+    /* vbar doubles as the queue: nodes leave it in the order they entered */
+    for (int64_t head = 0; head < n_v && !done; ++head) {
+        const int32_t u = vbar[head];
+        for (int64_t e = first[u]; e < first[u + 1] && !done; ++e) {
+            const int32_t q = held[e];
+            if (in_batch[q])
+                continue;
+            int64_t n_new = 0;
+            for (int32_t j = 0; j < k; ++j) {
+                const int32_t x = queries[(int64_t)q * k + j];
+                int seen = in_vbar[x];
+                for (int32_t i = 0; i < j; ++i)
+                    seen |= (queries[(int64_t)q * k + i] == x);
+                n_new += !seen;
+            }
+            if (n_v + n_new > B1) {
+                done = 1;
+                break;
+            }
+            in_batch[q] = 1;
+            batch[n_b++] = q;
+            for (int32_t j = 0; j < k; ++j) {
+                const int32_t x = queries[(int64_t)q * k + j];
+                if (!in_vbar[x]) {
+                    in_vbar[x] = 1;
+                    vbar[n_v++] = x;
+                }
+            }
+            if (n_b == B2 || n_v == B1)
+                done = 1;
+        }
+    }
+    counts[0] = n_v;
+    counts[1] = n_b;
+    free(first); free(fill); free(held); free(in_vbar); free(in_batch);
+    return 0;
 }

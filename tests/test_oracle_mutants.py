@@ -56,6 +56,16 @@ MUTANTS = {
                                "if (1) {"),
     "prune_code_off_by_one": ("code[r] = (int32_t)((hit - sorted) / L);",
                               "code[r] = (int32_t)((hit - sorted) / L) + (r > 0);"),
+    "bfs_queries_of_a_node_descending": ("const int32_t q = held[e];",
+                                         "const int32_t q = held[first[u] + first[u + 1] - 1 - e];"),
+    "bfs_limit_off_by_one": ("if (n_v + n_new > B1) {", "if (n_v + n_new >= B1) {"),
+    "bfs_ignores_full_node_set": ("if (n_b == B2 || n_v == B1)", "if (n_b == B2)"),
+    "bfs_forgets_reached_queries": ("in_batch[q] = 1;", ";"),
+    "bfs_nodes_in_reverse_tuple_order": (
+        "const int32_t x = queries[(int64_t)q * k + j];\n                if (!in_vbar[x]) {",
+        "const int32_t x = queries[(int64_t)q * k + (k - 1 - j)];\n                if (!in_vbar[x]) {"),
+    "bfs_keeps_repeated_seeds": ("if (!in_vbar[start[i]]) {", "if (1) {"),
+    "bfs_counts_a_repeated_node_twice": ("seen |= (queries[(int64_t)q * k + i] == x);", "seen |= 0;"),
     "join_copies_wrong_row": ("memcpy(dst, rpe_cnt + head[j] * L,", "memcpy(dst, rpe_cnt + rpe_off[queries[q * k + j]] * L,"),
 }
 
@@ -75,6 +85,9 @@ PIN_TESTS = [
     "test_prune_equals_python_set_and_dictionary",
     "test_prune_on_the_paper_fragment",
     "test_prune_orders_by_entries_not_by_bytes",
+    "test_bfs_batch_on_a_chain_a_star_and_two_components",
+    "test_bfs_batch_limits",
+    "test_bfs_batch_with_limits_is_a_prefix_that_stops_for_a_stated_reason",
 ]
 PARAM_PIN_TESTS = [
     ("test_walk_distribution_matches_enumeration", ("lollipop", 4)),
@@ -83,6 +96,7 @@ PARAM_PIN_TESTS = [
     ("test_join_equals_python_set_union", (2,)),
     ("test_join_equals_python_set_union", (3,)),
     ("test_query_rpe_ids_equal_dictionary_lookups", (2,)),
+    ("test_bfs_batch_levels_equal_set_expansion_and_scipy_distances", (3,)),
 ]
 
 
@@ -123,7 +137,8 @@ def test_planted_mistake_is_caught(name, tmp_path, golden_dir, monkeypatch):
     real = oracle._load()
     mutant = ctypes.CDLL(str(lib_path))
     for fn in ("oracle_philox4x32_10", "oracle_sample_walks", "oracle_build_rpe",
-               "oracle_join_queries", "oracle_query_rpe_ids", "oracle_prune_rpe"):
+               "oracle_join_queries", "oracle_query_rpe_ids", "oracle_prune_rpe",
+               "oracle_bfs_batch"):
         getattr(mutant, fn).argtypes = getattr(real, fn).argtypes
         getattr(mutant, fn).restype = getattr(real, fn).restype
     monkeypatch.setattr(oracle, "_lib", mutant)

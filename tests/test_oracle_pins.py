@@ -10,6 +10,11 @@ What fixes each part:
               with NumPy scatter-adds, and the invariants of the definition (Sec. 3.2).
   join        Python set / dict union with zero fill (Sec. 3.4), symmetry under swapping
               the query's nodes, u == v, and triple-versus-pair consistency.
+  RPE-IDs     dictionary lookups, agreement with the union join, the paper's fragment.
+  pruning     Python sets and NumPy's row-wise unique, the paper's fragment.
+  mini-batch  hand-worked chains, stars and triples, a level-by-level search written with
+              sets, SciPy's shortest paths in the node-query incidence graph, and the order
+              rules inside a level (Sec. 3.6; Algorithm 2).
 """
 import itertools
 import os
@@ -630,3 +635,148 @@ def test_prune_orders_by_entries_not_by_bytes():
     assert code.tolist() == [3, 2, 1, 3, 0]
     T0, code0 = oracle.prune_rpe(np.zeros((0, 3), dtype=np.uint16))
     assert T0.shape == (0, 3) and code0.size == 0
+
+
+# --------------------------------------------------------------------------- #
+# mini-batching by breadth-first search over query-sharing nodes (Sec. 3.6; Algorithm 2)
+# --------------------------------------------------------------------------- #
+def _random_queries(rng, n_nodes, n_queries, k, hubs=0):
+    q = rng.integers(0, n_nodes, size=(n_queries, k))
+    if hubs:  # some nodes held by many queries, as the endpoints of sampled edges are
+        pick = rng.random(n_queries) < 0.3
+        q[pick, 0] = rng.integers(0, hubs, size=int(pick.sum()))
+    return q.astype(np.int32)
+
+
+def _level_sets(queries, start):
+    """Breadth-first levels written with sets: (node levels, query levels)."""
+    seen_nodes, seen_queries = set(int(s) for s in start), set()
+    frontier = set(seen_nodes)
+    node_levels, query_levels = [set(frontier)], []
+    while frontier:
+        reached = {qi for qi, tup in enumerate(queries)
+                   if qi not in seen_queries and frontier & set(int(x) for x in tup)}
+        seen_queries |= reached
+        nxt = {int(x) for qi in reached for x in queries[qi]} - seen_nodes
+        seen_nodes |= nxt
+        query_levels.append(reached)
+        node_levels.append(nxt)
+        frontier = nxt
+    return node_levels, query_levels
+
+
+def test_bfs_batch_on_a_chain_a_star_and_two_components():
+    chain = np.array([[i, i + 1] for i in range(6)], dtype=np.int32)      # query i = (i, i+1)
+    vbar, batch = oracle.bfs_batch(chain, 7, [0], 100, 100)
+    assert vbar.tolist() == [0, 1, 2, 3, 4, 5, 6] and batch.tolist() == [0, 1, 2, 3, 4, 5]
+    # from the middle: node 3 is held by queries 2 = (2,3) and 3 = (3,4), taken in that order
+    vbar, batch = oracle.bfs_batch(chain, 7, [3], 100, 100)
+    assert vbar.tolist() == [3, 2, 4, 1, 5, 0, 6] and batch.tolist() == [2, 3, 1, 4, 0, 5]
+    star = np.array([[0, i] for i in range(1, 6)], dtype=np.int32)
+    vbar, batch = oracle.bfs_batch(star, 6, [3], 100, 100)
+    assert vbar.tolist() == [3, 0, 1, 2, 4, 5] and batch.tolist() == [2, 0, 1, 3, 4]
+    two = np.array([[0, 1], [5, 6], [1, 2], [6, 7]], dtype=np.int32)
+    vbar, batch = oracle.bfs_batch(two, 9, [1], 100, 100)
+    assert sorted(vbar.tolist()) == [0, 1, 2] and sorted(batch.tolist()) == [0, 2]
+    vbar, batch = oracle.bfs_batch(two, 9, [8], 100, 100)                 # a node no query holds
+    assert vbar.tolist() == [8] and batch.tolist() == []
+    # triples, tuple order of the new nodes, a repeated node inside a query, repeated seeds
+    tri = np.array([[4, 2, 9], [9, 9, 1], [7, 4, 2]], dtype=np.int32)
+    vbar, batch = oracle.bfs_batch(tri, 10, [2, 2], 100, 100)
+    assert batch.tolist() == [0, 2, 1] and vbar.tolist() == [2, 4, 9, 7, 1]
+
+
+def test_bfs_batch_limits():
+    chain = np.array([[i, i + 1] for i in range(6)], dtype=np.int32)
+    vbar, batch = oracle.bfs_batch(chain, 7, [3], 100, 3)                 # the batch fills up
+    assert batch.tolist() == [2, 3, 1] and vbar.tolist() == [3, 2, 4, 1]
+    vbar, batch = oracle.bfs_batch(chain, 7, [3], 4, 100)                 # the node set fills up
+    assert batch.tolist() == [2, 3, 1] and vbar.tolist() == [3, 2, 4, 1]
+    # a query enters only with all its nodes: (5,6,7) needs two more nodes, one place is left
+    tri = np.array([[0, 1, 2], [2, 5, 6], [2, 3, 3]], dtype=np.int32)
+    vbar, batch = oracle.bfs_batch(tri, 8, [0], 4, 100)
+    assert batch.tolist() == [0] and vbar.tolist() == [0, 1, 2]
+    # more seeds than places: the node set is the first B1 distinct seeds, no query is reached
+    vbar, batch = oracle.bfs_batch(chain, 7, [6, 6, 0, 3], 2, 100)
+    assert vbar.tolist() == [6, 0] and batch.tolist() == []
+    # the search ends as soon as the node set is full, also before a query that needs no new node
+    twice = np.array([[0, 1], [0, 1]], dtype=np.int32)
+    vbar, batch = oracle.bfs_batch(twice, 2, [0], 2, 100)
+    assert vbar.tolist() == [0, 1] and batch.tolist() == [0]
+    # a node that a query names twice takes one place
+    vbar, batch = oracle.bfs_batch(np.array([[0, 3, 3]], dtype=np.int32), 4, [0], 2, 100)
+    assert vbar.tolist() == [0, 3] and batch.tolist() == [0]
+    vbar, batch = oracle.bfs_batch(np.zeros((0, 2), np.int32), 7, [4], 5, 5)
+    assert vbar.tolist() == [4] and batch.tolist() == []
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_bfs_batch_levels_equal_set_expansion_and_scipy_distances(k):
+    from scipy.sparse import coo_matrix
+    from scipy.sparse.csgraph import shortest_path
+    rng = np.random.default_rng(100 + k)
+    for trial in range(6):
+        n_nodes, n_queries = 60, int(rng.integers(20, 70))
+        queries = _random_queries(rng, n_nodes, n_queries, k, hubs=3 if trial % 2 else 0)
+        start = rng.integers(0, n_nodes, size=int(rng.integers(1, 5)))
+        vbar, batch = oracle.bfs_batch(queries, n_nodes, start, 10 ** 6, 10 ** 6)
+        assert len(set(vbar.tolist())) == len(vbar) and len(set(batch.tolist())) == len(batch)
+        # levels, by a search written with sets
+        node_levels, query_levels = _level_sets(queries, start)
+        at = 0
+        for lev in node_levels:
+            assert set(vbar[at:at + len(lev)].tolist()) == lev
+            at += len(lev)
+        assert at == len(vbar)
+        at = 0
+        for lev in query_levels:
+            assert set(batch[at:at + len(lev)].tolist()) == lev
+            at += len(lev)
+        assert at == len(batch)
+        # distances in the node-query incidence graph, by SciPy: nodes 0.., queries n_nodes..,
+        # and one extra vertex tied to every seed
+        src = n_nodes + n_queries
+        rows = np.concatenate([np.repeat(np.arange(n_queries) + n_nodes, k), np.full(len(start), src)])
+        cols = np.concatenate([queries.reshape(-1), start])
+        g = coo_matrix((np.ones(len(rows)), (rows, cols)), shape=(src + 1, src + 1))
+        dist = shortest_path(g, directed=False, unweighted=True, indices=src)
+        reach_q = {qi for qi in range(n_queries) if np.isfinite(dist[n_nodes + qi])}
+        reach_v = {x for x in range(n_nodes) if np.isfinite(dist[x])}
+        assert set(batch.tolist()) == reach_q and set(vbar.tolist()) == reach_v
+        assert np.all(np.diff(dist[n_nodes + batch]) >= 0) and np.all(np.diff(dist[vbar]) >= 0)
+        # inside a level: a query is reached from its earliest-queued node, queries of one node in
+        # ascending index; a node enters with the first batch query that holds it, in tuple order
+        pos_v = {int(x): i for i, x in enumerate(vbar)}
+        keys = [(min(pos_v[int(x)] for x in queries[qi]), int(qi)) for qi in batch]
+        assert keys == sorted(keys)
+        pos_q = {int(qi): i for i, qi in enumerate(batch)}
+        seeds_in_order = list(dict.fromkeys(int(s) for s in start))
+        assert vbar[:len(seeds_in_order)].tolist() == seeds_in_order
+        keys = []
+        for x in vbar[len(seeds_in_order):]:
+            holders = [(pos_q[qi], int(np.argmax(queries[qi] == x))) for qi in pos_q
+                       if x in queries[qi]]
+            keys.append(min(holders))
+        assert keys == sorted(keys) and len(set(keys)) == len(keys)
+
+
+def test_bfs_batch_with_limits_is_a_prefix_that_stops_for_a_stated_reason():
+    rng = np.random.default_rng(77)
+    for trial in range(40):
+        k = 2 + trial % 2
+        n_nodes = 50
+        queries = _random_queries(rng, n_nodes, int(rng.integers(10, 80)), k, hubs=2)
+        start = rng.integers(0, n_nodes, size=int(rng.integers(1, 4)))
+        full_v, full_b = oracle.bfs_batch(queries, n_nodes, start, 10 ** 6, 10 ** 6)
+        B1, B2 = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        vbar, batch = oracle.bfs_batch(queries, n_nodes, start, B1, B2)
+        assert len(vbar) <= B1 and len(batch) <= B2
+        assert batch.tolist() == full_b[:len(batch)].tolist()
+        assert vbar.tolist() == full_v[:len(vbar)].tolist()
+        held = set(int(s) for s in list(dict.fromkeys(start.tolist()))[:B1])
+        held |= {int(x) for qi in batch for x in queries[qi]}
+        assert set(vbar.tolist()) == held                       # exactly the seeds and the batch's nodes
+        if len(batch) < len(full_b):                            # stopped early: say why
+            nxt = full_b[len(batch)]
+            need = len(set(int(x) for x in queries[nxt]) - held)
+            assert len(batch) == B2 or len(vbar) == B1 or len(vbar) + need > B1
