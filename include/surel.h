@@ -12,7 +12,9 @@
  *                        zeros where x is not in V_u (Sec. 3.4, set-union form).
  * Beside them: surel_sample_walks_rpe (the first two in one kernel), surel_query_rpe_ids
  * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values) and
- * surel_prune_rpe (Sec. 3.3: the distinct count vectors stored once, rows re-indexed).
+ * surel_prune_rpe (Sec. 3.3: the distinct count vectors stored once, rows re-indexed), and
+ * surel_query_incidence + surel_bfs_batches (Sec. 3.6 "Mini-batching for Training";
+ * Algorithm 2: mini-batches of queries that share nodes, by breadth-first search).
  *
  * Conventions
  *   - Plain C ABI.  Pointers named d_* are DEVICE memory owned by the caller, on the
@@ -22,7 +24,8 @@
  *     a non-NULL h_rows is passed (then it waits for its own work and reports the row
  *     total).  Calls on one context must not overlap from several host threads.
  *   - The context owns grow-only device workspaces (per-seed / per-query row counts, scan
- *     partials, the walk's per-edge neighbour records, the fused kernel's look-back words)
+ *     partials, the walk's per-edge neighbour records, the fused kernel's look-back words,
+ *     the hash tables and sort arrays of pruning and mini-batching)
  *     and a device error word; nothing else is allocated.
  *   - Return value: SUREL_OK (0) or a negative SUREL_E_* code.  Arguments are validated on
  *     the host before anything is enqueued, so a call that returns SUREL_E_NULL or
@@ -77,7 +80,8 @@ extern "C" {
 #define SUREL_DEV_BAD_SIZES     0x80u  /* a seed's d_set_sizes entry is not its number of
                                           distinct nodes; that seed's rows are not written   */
 #define SUREL_DEV_STALL         0x100u /* a bounded wait inside surel_sample_walks_rpe ran out
-                                          (see surel_set_spin_limit); its outputs are
+                                          (see surel_set_spin_limit), or a bounded probe of a
+                                          hash table of surel_bfs_batches; outputs are
                                           incomplete                                         */
 
 /* limits */
@@ -88,6 +92,7 @@ extern "C" {
 #define SUREL_MAX_SET     2048        /* join: rows per block of the RPE table               */
 #define SUREL_MAX_TUPLE   3           /* join: k                                             */
 #define SUREL_MAX_DISTINCT 16777216   /* prune: cap_T (2^24 distinct count vectors)          */
+#define SUREL_MAX_BATCH   1048576     /* mini-batching: B1, B2 and the seed-set size (2^20)   */
 
 /* kernel groups for surel_profile_read */
 #define SUREL_K_WALK        0   /* walk kernel                                        */
@@ -101,7 +106,8 @@ extern "C" {
                                    (both walk calls, large jobs only)                 */
 #define SUREL_K_QUERY_IDS   8   /* surel_query_rpe_ids                                */
 #define SUREL_K_PRUNE       9   /* surel_prune_rpe (all its launches)                 */
-#define SUREL_K_COUNT       10
+#define SUREL_K_BATCH       10  /* surel_query_incidence and surel_bfs_batches        */
+#define SUREL_K_COUNT       11
 
 typedef struct surel_ctx surel_ctx;
 
@@ -234,6 +240,50 @@ int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d
  * Device-detected: STALL. */
 int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, int32_t m,
                     int64_t cap_T, uint16_t* d_T, int32_t* d_code, int64_t* h_n_T);
+
+/* The queries of every node, the adjacency that the mini-batch search of Sec. 3.6 runs on
+ * ("a neighbor of node u is a node that shares at least one query with it"): for every node x,
+ * the indices of the queries that name x, ascending.  Built once per query list.
+ *   d_queries    int32[n_queries][k] NODE ids (device, read-only), 1 <= k <= SUREL_MAX_TUPLE,
+ *                n_queries * k < 2^31.
+ *   d_inc_off    int64[n_nodes + 1] (device, written): node x's part of d_inc_q is
+ *                [d_inc_off[x], d_inc_off[x+1]).
+ *   d_inc_q      int32[n_queries * k] (device, written); a query that names x twice is listed
+ *                twice in x's part.
+ * Asynchronous.  Device-detected: BAD_QUERY (an id outside [0, n_nodes); that entry is left out
+ * of every part, d_inc_off[n_nodes] is the number of entries kept). */
+int surel_query_incidence(surel_ctx* ctx, const int32_t* d_queries, int64_t n_queries, int32_t k,
+                          int32_t n_nodes, int64_t* d_inc_off, int32_t* d_inc_q);
+
+/* Mini-batches for training (Sec. 3.6 "Mini-batching for Training"; Algorithm 2, the steps
+ * that choose a seed-set and expand it by breadth-first search): n_batches independent
+ * searches in one launch.  Search b starts from the nodes d_start[b][0..n_start) (the random
+ * seed-set is the caller's draw; repeated nodes count once) and collects the node set V̄ and
+ * the reached queries until V̄ has B1 nodes or the batch has B2 queries.  Where the paper leaves
+ * the order open: the queue is first-in first-out, a node's queries are taken in ascending
+ * index, a query's nodes in tuple order; a query enters the batch together with all of its
+ * nodes, and the search ends at the first query whose new nodes no longer fit into B1.
+ *   d_queries, n_queries, k, n_nodes   the query list, as for surel_query_incidence.
+ *   d_inc_off, d_inc_q   what surel_query_incidence wrote for this query list (read-only).
+ *   d_start      int32[n_batches][n_start] (device, read-only).
+ *   d_vbar       int32[n_batches][B1] (device, written): V̄ of every batch in the order reached
+ *                (start nodes first); entries past the batch's node count are not written.
+ *   d_batch      int32[n_batches][B2] (device, written): the indices of the reached queries in
+ *                the order reached; entries past the batch's query count are not written.
+ *   d_tuples     int32[n_batches][B2][k] or NULL (device, written): the same queries as node
+ *                tuples, ready to be a query list of the join calls when node x's RPE block is
+ *                block x.
+ *   d_counts     int32[n_batches][2] (device, written): (nodes in V̄, queries in the batch).
+ * Limits: 1 <= n_start, B1, B2 <= SUREL_MAX_BATCH.  The context's workspace grows by 16 bytes
+ * times (B1 + B2 + n_start + 4096), rounded up to powers of two, for each search in flight
+ * (4 x compute units of them, fewer where that would pass 4 GiB).  Asynchronous.
+ * Device-detected: BAD_QUERY (a start node or query entry outside [0, n_nodes): skipped),
+ * BAD_TABLE (d_inc_off / d_inc_q are not lists of this query list: those entries are skipped). */
+int surel_bfs_batches(surel_ctx* ctx, const int32_t* d_queries, int64_t n_queries, int32_t k,
+                      int32_t n_nodes, const int64_t* d_inc_off, const int32_t* d_inc_q,
+                      const int32_t* d_start, int64_t n_batches, int32_t n_start, int32_t B1,
+                      int32_t B2, int32_t* d_vbar, int32_t* d_batch, int32_t* d_tuples,
+                      int32_t* d_counts);
 
 /* Every wait inside the fused kernel of surel_sample_walks_rpe (a wave waiting for an offset,
  * the offset scan waiting for a row count) and inside surel_prune_rpe (a lane waiting for

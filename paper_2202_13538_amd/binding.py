@@ -21,13 +21,14 @@ DEV_STALL = 0x100
 MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
 MAX_DISTINCT = 1 << 24
+MAX_BATCH = 1 << 20
 
 (K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_WALK_RPE,
- K_EDGE_RECORDS, K_QUERY_IDS, K_PRUNE, K_COUNT) = range(11)
+ K_EDGE_RECORDS, K_QUERY_IDS, K_PRUNE, K_BATCH, K_COUNT) = range(12)
 KERNEL_NAMES = {K_WALK: "walk", K_RPE_COUNT: "rpe_count", K_RPE_FILL: "rpe_fill",
                 K_JOIN_COUNT: "join_count", K_JOIN_FILL: "join_fill", K_SCAN: "scan",
                 K_WALK_RPE: "walk_rpe", K_EDGE_RECORDS: "edge_records",
-                K_QUERY_IDS: "query_ids", K_PRUNE: "prune"}
+                K_QUERY_IDS: "query_ids", K_PRUNE: "prune", K_BATCH: "batch"}
 
 _vp = ctypes.c_void_p
 _i32, _i64, _u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
@@ -51,6 +52,9 @@ SIGNATURES = {
                                            _i64, _i32, _vp]),
     "surel_prune_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i64, _vp, _vp,
                                        ctypes.POINTER(_i64)]),
+    "surel_query_incidence": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _vp]),
+    "surel_bfs_batches": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _i32,
+                                         _i32, _i32, _vp, _vp, _vp, _vp]),
     "surel_set_spin_limit": (ctypes.c_int, [_vp, ctypes.c_uint32]),
     "surel_check": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint32)]),
     "surel_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
@@ -340,3 +344,50 @@ def prune_rpe(ctx: Context, rpe_cnt: torch.Tensor, cap_T: int = 1 << 20):
     if rc != OK:
         raise SurelError(rc, "surel_prune_rpe")
     return T[:n_T], code
+
+
+def query_incidence(ctx: Context, queries: torch.Tensor, n_nodes: int):
+    """(inc_off int64[n_nodes+1], inc_q int32[n_queries*k]) on the GPU: for every node the
+    indices of the queries that name it, ascending (surel_query_incidence)."""
+    n_queries, k = queries.shape
+    inc_off = torch.empty(n_nodes + 1, dtype=torch.int64, device=queries.device)
+    inc_q = torch.empty(n_queries * k, dtype=torch.int32, device=queries.device)
+    rc = load().surel_query_incidence(ctx.handle, _ptr(queries, torch.int32, "queries"), n_queries,
+                                      k, n_nodes, _ptr(inc_off, torch.int64, "inc_off"),
+                                      _ptr(inc_q, torch.int32, "inc_q"))
+    if rc != OK:
+        raise SurelError(rc, "surel_query_incidence")
+    return inc_off, inc_q
+
+
+def bfs_batches_raw(ctx: Context, queries, n_nodes: int, inc_off, inc_q, start, B1: int, B2: int,
+                    vbar, batch, tuples, counts) -> int:
+    """One call of surel_bfs_batches into caller buffers.  Returns the status."""
+    n_queries, k = queries.shape
+    n_batches, n_start = start.shape
+    return load().surel_bfs_batches(
+        ctx.handle, _ptr(queries, torch.int32, "queries"), n_queries, k, n_nodes,
+        _ptr(inc_off, torch.int64, "inc_off"), _ptr(inc_q, torch.int32, "inc_q"),
+        _ptr(start, torch.int32, "start"), n_batches, n_start, B1, B2,
+        _ptr(vbar, torch.int32, "vbar"), _ptr(batch, torch.int32, "batch"),
+        None if tuples is None else _ptr(tuples, torch.int32, "tuples"),
+        _ptr(counts, torch.int32, "counts"))
+
+
+def bfs_batches(ctx: Context, queries: torch.Tensor, n_nodes: int, inc_off: torch.Tensor,
+                inc_q: torch.Tensor, start: torch.Tensor, B1: int, B2: int, want_tuples=True):
+    """(vbar int32[n_batches][B1], batch int32[n_batches][B2], tuples int32[n_batches][B2][k] or
+    None, counts int32[n_batches][2]) on the GPU: one mini-batch per row of `start`
+    (surel_bfs_batches).  Only the first counts[b] entries of a row are written."""
+    n_batches = start.shape[0]
+    k = queries.shape[1]
+    dev = queries.device
+    vbar = torch.empty((n_batches, B1), dtype=torch.int32, device=dev)
+    batch = torch.empty((n_batches, B2), dtype=torch.int32, device=dev)
+    tuples = torch.empty((n_batches, B2, k), dtype=torch.int32, device=dev) if want_tuples else None
+    counts = torch.empty((n_batches, 2), dtype=torch.int32, device=dev)
+    rc = bfs_batches_raw(ctx, queries, n_nodes, inc_off, inc_q, start, B1, B2, vbar, batch, tuples,
+                         counts)
+    if rc != OK:
+        raise SurelError(rc, "surel_bfs_batches")
+    return vbar, batch, tuples, counts

@@ -25,6 +25,8 @@ struct surel_ctx {
     size_t lb_bytes = 0;
     void* d_prune = nullptr;      // grow-only workspace: hash slots, sort list, counters of prune
     size_t prune_bytes = 0;
+    void* d_batch = nullptr;      // grow-only workspace: sort arrays of the incidence lists, hash
+    size_t batch_bytes = 0;       // tables of the mini-batch search
     // optional per-kernel timing (surel_profile_*)
     struct Span {
         int kernel;
@@ -238,6 +240,7 @@ void surel_destroy(surel_ctx* ctx) {
     if (ctx->d_rec) (void)hipFree(ctx->d_rec);
     if (ctx->d_lb) (void)hipFree(ctx->d_lb);
     if (ctx->d_prune) (void)hipFree(ctx->d_prune);
+    if (ctx->d_batch) (void)hipFree(ctx->d_batch);
     if (ctx->d_err) (void)hipFree(ctx->d_err);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     delete ctx;
@@ -496,6 +499,60 @@ int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, i
                                    list, d_T, d_code) != hipSuccess)
         return SUREL_E_HIP;
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    return SUREL_OK;
+}
+
+// Grows the mini-batching workspace to `need` bytes (contents are not kept).
+static int ensure_batch_workspace(surel_ctx* ctx, size_t need) {
+    if (need <= ctx->batch_bytes) return SUREL_OK;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    if (ctx->d_batch) (void)hipFree(ctx->d_batch);
+    ctx->d_batch = nullptr;
+    ctx->batch_bytes = 0;
+    if (hipMalloc(&ctx->d_batch, need) != hipSuccess) return SUREL_E_HIP;
+    ctx->batch_bytes = need;
+    return SUREL_OK;
+}
+
+int surel_query_incidence(surel_ctx* ctx, const int32_t* d_queries, int64_t n_queries, int32_t k,
+                          int32_t n_nodes, int64_t* d_inc_off, int32_t* d_inc_q) {
+    if (n_nodes < 1 || n_nodes > SUREL_MAX_NODES || n_queries < 0) return SUREL_E_RANGE;
+    if (k < 1 || k > SUREL_MAX_TUPLE || n_queries > (int64_t)0x7FFFFFFF / k) return SUREL_E_RANGE;
+    if (!d_inc_off || (n_queries > 0 && (!d_queries || !d_inc_q))) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (int rc = ensure_batch_workspace(ctx, surel::incidence_scratch_bytes(n_queries * k))) return rc;
+    KernelSpan span(ctx, SUREL_K_BATCH);
+    if (surel::launch_query_incidence(ctx->stream, d_queries, n_queries, k, n_nodes, d_inc_off,
+                                      d_inc_q, ctx->d_batch, ctx->d_err) != hipSuccess)
+        return SUREL_E_HIP;
+    return SUREL_OK;
+}
+
+int surel_bfs_batches(surel_ctx* ctx, const int32_t* d_queries, int64_t n_queries, int32_t k,
+                      int32_t n_nodes, const int64_t* d_inc_off, const int32_t* d_inc_q,
+                      const int32_t* d_start, int64_t n_batches, int32_t n_start, int32_t B1,
+                      int32_t B2, int32_t* d_vbar, int32_t* d_batch, int32_t* d_tuples,
+                      int32_t* d_counts) {
+    if (n_nodes < 1 || n_nodes > SUREL_MAX_NODES || n_queries < 0 || n_batches < 0) return SUREL_E_RANGE;
+    if (k < 1 || k > SUREL_MAX_TUPLE || n_queries > (int64_t)0x7FFFFFFF / k) return SUREL_E_RANGE;
+    if (n_start < 1 || n_start > SUREL_MAX_BATCH || B1 < 1 || B1 > SUREL_MAX_BATCH || B2 < 1 ||
+        B2 > SUREL_MAX_BATCH)
+        return SUREL_E_RANGE;
+    if (n_batches > 0 && (!d_inc_off || !d_start || !d_vbar || !d_batch || !d_counts)) return SUREL_E_NULL;
+    if (n_batches > 0 && n_queries > 0 && (!d_queries || !d_inc_q)) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    if (n_batches == 0) return SUREL_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (int rc = ensure_batch_workspace(ctx, surel::bfs_scratch_bytes(ctx->n_cu, n_batches, n_start, B1, B2)))
+        return rc;
+    KernelSpan span(ctx, SUREL_K_BATCH);
+    if (surel::launch_bfs_batches(ctx->stream, ctx->n_cu, d_queries, n_queries, k, n_nodes, d_inc_off,
+                                  d_inc_q, d_start, n_batches, n_start, B1, B2, d_vbar, d_batch,
+                                  d_tuples, d_counts, ctx->d_batch, ctx->d_err) != hipSuccess)
+        return SUREL_E_HIP;
     return SUREL_OK;
 }
 

@@ -78,6 +78,25 @@ hipError_t launch_prune_finish(hipStream_t stream, int n_cu, int64_t n_rows, int
                                unsigned long long* counters, uint32_t* list, uint16_t* T,
                                int32_t* code);
 
+// incidence.hip.  The queries of every node: inc_q[inc_off[x] .. inc_off[x+1]) = indices of the
+// queries that name node x, ascending (a query that names x twice is listed twice).  Entries
+// outside [0, n_nodes) are flagged and left out.  scratch: incidence_scratch_bytes(n_queries*k).
+size_t incidence_scratch_bytes(int64_t n_entries);
+hipError_t launch_query_incidence(hipStream_t stream, const int32_t* queries, int64_t n_queries,
+                                  int32_t k, int32_t n_nodes, int64_t* inc_off, int32_t* inc_q,
+                                  void* scratch, uint32_t* err);
+
+// bfs.hip.  n_batches mini-batches, each by breadth-first search from its own n_start start
+// nodes over nodes that share queries, until B1 nodes or B2 queries.  vbar int32[n_batches][B1],
+// batch int32[n_batches][B2], tuples int32[n_batches][B2][k] (optional), counts
+// int32[n_batches][2] = (nodes, queries) of every batch.  scratch: bfs_scratch_bytes(...).
+size_t bfs_scratch_bytes(int n_cu, int64_t n_batches, int32_t n_start, int32_t B1, int32_t B2);
+hipError_t launch_bfs_batches(hipStream_t stream, int n_cu, const int32_t* queries,
+                              int64_t n_queries, int32_t k, int32_t n_nodes, const int64_t* inc_off,
+                              const int32_t* inc_q, const int32_t* start, int64_t n_batches,
+                              int32_t n_start, int32_t B1, int32_t B2, int32_t* vbar, int32_t* batch,
+                              int32_t* tuples, int32_t* counts, void* scratch, uint32_t* err);
+
 // scan.hip.  off[0..n] = exclusive prefix sums of counts[0..n-1] (off[n] = total).
 // partials: device scratch of scan_partials_len(n) int64.
 int64_t scan_partials_len(int64_t n);

@@ -234,6 +234,67 @@ def test_prune_rpe_argument_checks(lib, kw, want):
     assert lib.surel_prune_rpe(*prune_args(**kw)) == want
 
 
+def incidence_args(**kw):
+    a = dict(ctx=NULL, queries=P, n_q=10, k=2, n_nodes=100, inc_off=P, inc_q=P)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "queries", "n_q", "k", "n_nodes", "inc_off", "inc_q")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(k=1), binding.E_CTX),
+    (dict(k=0), binding.E_RANGE),
+    (dict(k=4), binding.E_RANGE),
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(n_nodes=binding.MAX_NODES + 1), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(n_q=(1 << 30), k=3), binding.E_RANGE),
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(inc_off=NULL), binding.E_NULL),
+    (dict(inc_q=NULL), binding.E_NULL),
+    (dict(queries=NULL, inc_q=NULL, n_q=0), binding.E_CTX),
+])
+def test_query_incidence_argument_checks(lib, kw, want):
+    assert lib.surel_query_incidence(*incidence_args(**kw)) == want
+
+
+def batches_args(**kw):
+    a = dict(ctx=NULL, queries=P, n_q=10, k=2, n_nodes=100, inc_off=P, inc_q=P, start=P,
+             n_batches=4, n_start=2, B1=64, B2=32, vbar=P, batch=P, tuples=P, counts=P)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "queries", "n_q", "k", "n_nodes", "inc_off", "inc_q", "start",
+                           "n_batches", "n_start", "B1", "B2", "vbar", "batch", "tuples", "counts")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(tuples=NULL), binding.E_CTX),
+    (dict(k=0), binding.E_RANGE),
+    (dict(k=4), binding.E_RANGE),
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(n_batches=-1), binding.E_RANGE),
+    (dict(n_start=0), binding.E_RANGE),
+    (dict(B1=0), binding.E_RANGE),
+    (dict(B2=0), binding.E_RANGE),
+    (dict(B1=binding.MAX_BATCH + 1), binding.E_RANGE),
+    (dict(B2=binding.MAX_BATCH + 1), binding.E_RANGE),
+    (dict(n_start=binding.MAX_BATCH + 1), binding.E_RANGE),
+    (dict(B1=binding.MAX_BATCH, B2=binding.MAX_BATCH), binding.E_CTX),
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(inc_off=NULL), binding.E_NULL),
+    (dict(inc_q=NULL), binding.E_NULL),
+    (dict(start=NULL), binding.E_NULL),
+    (dict(vbar=NULL), binding.E_NULL),
+    (dict(batch=NULL), binding.E_NULL),
+    (dict(counts=NULL), binding.E_NULL),
+    (dict(queries=NULL, inc_q=NULL, n_q=0), binding.E_CTX),
+    (dict(start=NULL, vbar=NULL, batch=NULL, counts=NULL, n_batches=0), binding.E_CTX),
+])
+def test_bfs_batches_argument_checks(lib, kw, want):
+    assert lib.surel_bfs_batches(*batches_args(**kw)) == want
+
+
 def join_args(**kw):
     a = dict(ctx=NULL, off=P, ids=P, cnt=P, n_blocks=100, m=4, max_set=201, queries=P, n_q=10,
              k=2, cap_rows=1000, joff=P, jids=P, jcnt=P, h_rows=NULL)
