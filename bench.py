@@ -111,6 +111,12 @@ def main() -> int:
     ap.add_argument("--prune", action="store_true",
                     help="also time surel_prune_rpe (Sec. 3.3: distinct count vectors stored once) "
                          "after the timed region; reported under 'prune_rpe', not part of 'value'")
+    ap.add_argument("--batches", action="store_true",
+                    help="also time surel_query_incidence + surel_bfs_batches (Sec. 3.6: mini-batches "
+                         "of queries that share nodes) after the timed region, and the join over "
+                         "the batches' queries next to the join over as many queries in the given "
+                         "order; reported under 'bfs_batches', not part of 'value'")
+    ap.add_argument("--batch-size", type=int, default=4096, help="B2 of --batches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
@@ -285,6 +291,67 @@ def main() -> int:
             "algorithmic_bytes": p_bytes,
             "hbm_frac": round(p_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del T, code
+    if args.batches:
+        B2 = args.batch_size
+        B1 = B2 * k                       # the batch size is the limit that binds
+        n_batches, n_start = max(1, Q // B2), 16
+        g = torch.Generator(device="cpu").manual_seed(7)
+        # Algorithm 2 draws the seed-set from the nodes that queries name
+        start = d_q.reshape(-1)[torch.randint(0, Q * k, (n_batches * n_start,), generator=g).cuda()]
+        start = start.reshape(n_batches, n_start).contiguous()
+        inc_off, inc_q = binding.query_incidence(ctx, d_q, N)
+        vbar, batch, tuples, counts = binding.bfs_batches(ctx, d_q, N, inc_off, inc_q, start, B1, B2)
+        assert ctx.check() == 0
+        ctx.profile(True)
+        for _ in range(args.steps):
+            binding.query_incidence(ctx, d_q, N)
+        inc_ms = ctx.profile_read()["batch"][0] / args.steps
+        ctx.profile(True)
+        for _ in range(args.steps):
+            binding.bfs_batches_raw(ctx, d_q, N, inc_off, inc_q, start, B1, B2, vbar, batch, tuples,
+                                    counts)
+        bfs_ms = ctx.profile_read()["batch"][0] / args.steps
+        ctx.profile(False)
+        assert ctx.check() == 0
+        n_b = counts[:, 1].long()
+        keep = torch.arange(B2, device="cuda")[None, :] < n_b[:, None]
+        bq = tuples[keep].contiguous()                      # the batches' queries, batch after batch
+        Qb = bq.shape[0]
+        given = d_q[:Qb].contiguous()                       # as many queries in the given order
+        nodes_bfs = float(counts[:, 0].float().sum()) / max(Qb, 1)
+        nodes_given = sum(int(torch.unique(d_q[i * B2:(i + 1) * B2]).numel())
+                          for i in range(min(n_batches, 32))) / (min(n_batches, 32) * B2)
+
+        def time_join(qs):
+            off = torch.empty(qs.shape[0] + 1, dtype=torch.int64, device="cuda")
+            rc, rows = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, qs, max_set, 0, off,
+                                                None, None)
+            assert rc == binding.OK, rc
+            ids = torch.empty(rows, dtype=torch.int32, device="cuda")
+            cnt = torch.empty((rows, k, L), dtype=torch.uint16, device="cuda")
+            binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, qs, max_set, rows, off, ids, cnt)
+            ctx.profile(True)
+            for _ in range(args.steps):
+                binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, qs, max_set, rows, off, ids,
+                                         cnt)
+            pr = ctx.profile_read()
+            ctx.profile(False)
+            return (pr["join_count"][0] + pr["join_fill"][0] + pr["scan"][0]) / args.steps, rows
+
+        join_bfs_ms, rows_bfs = time_join(bq)
+        join_given_ms, rows_given = time_join(given)
+        assert ctx.check() == 0
+        out["bfs_batches"] = {
+            "n_batches": n_batches, "B1": B1, "B2": B2, "seed_set": n_start,
+            "incidence_ms": round(inc_ms, 4), "bfs_ms": round(bfs_ms, 4),
+            "queries_in_batches": Qb, "batched_queries_per_s": Qb / (bfs_ms * 1e-3),
+            "distinct_nodes_per_query": {"bfs_batches": round(nodes_bfs, 4),
+                                         "given_order": round(nodes_given, 4)},
+            "join_ms": {"bfs_batches": round(join_bfs_ms, 4), "given_order": round(join_given_ms, 4)},
+            "joined_rows": {"bfs_batches": rows_bfs, "given_order": rows_given},
+            "joined_rows_per_s": {"bfs_batches": rows_bfs / (join_bfs_ms * 1e-3),
+                                  "given_order": rows_given / (join_given_ms * 1e-3)}}
+        del vbar, batch, tuples, counts, inc_off, inc_q
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
         b = torch.empty_like(a)
