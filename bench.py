@@ -134,6 +134,8 @@ def main() -> int:
                          "the batches' queries next to the join over as many queries in the given "
                          "order; reported under 'bfs_batches', not part of 'value'")
     ap.add_argument("--batch-size", type=int, default=4096, help="B2 of --batches")
+    ap.add_argument("--batch-nodes", type=int, default=0,
+                    help="B1 of --batches (default k * B2, so that B2 is the limit that binds)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
@@ -310,7 +312,7 @@ def main() -> int:
         del T, code
     if args.batches:
         B2 = args.batch_size
-        B1 = B2 * k                       # the batch size is the limit that binds
+        B1 = args.batch_nodes or B2 * k   # default: the batch size is the limit that binds
         n_batches, n_start = max(1, Q // B2), 16
         g = torch.Generator(device="cpu").manual_seed(7)
         # Algorithm 2 draws the seed-set from the nodes that queries name

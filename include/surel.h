@@ -275,8 +275,9 @@ int surel_query_incidence(surel_ctx* ctx, const int32_t* d_queries, int64_t n_qu
  *                block x.
  *   d_counts     int32[n_batches][2] (device, written): (nodes in V̄, queries in the batch).
  * Limits: 1 <= n_start, B1, B2 <= SUREL_MAX_BATCH.  The context's workspace grows by 16 bytes
- * times (B1 + B2 + n_start + 4096), rounded up to powers of two, for each search in flight
- * (4 x compute units of them, fewer where that would pass 4 GiB).  Asynchronous.
+ * times (B1 + B2 + n_start + 4 c), c = 4 B2 rounded up to a power of two within [64, 1024],
+ * both tables rounded up to powers of two, for each search in flight (4 per compute unit, 16
+ * where B2 <= 64; fewer where that would pass 4 GiB).  Asynchronous.
  * Device-detected: BAD_QUERY (a start node or query entry outside [0, n_nodes): skipped),
  * BAD_TABLE (d_inc_off / d_inc_q are not lists of this query list: those entries are skipped). */
 int surel_bfs_batches(surel_ctx* ctx, const int32_t* d_queries, int64_t n_queries, int32_t k,

@@ -1,12 +1,13 @@
 // Mini-batches by breadth-first search over nodes that share queries (Sec. 3.6 "Mini-batching
-// for Training"; Algorithm 2, the BFS step).  One workgroup builds one mini-batch; a launch
-// builds many (the iterations of Algorithm 2 draw their seed-sets independently).
+// for Training"; Algorithm 2, the BFS step).  One workgroup (four wavefronts, or one for small
+// batches) builds one mini-batch; a launch builds many (the iterations of Algorithm 2 draw their seed-sets independently).
 //
 // The search is the first-in first-out one: the node set V̄ is its own queue, a node's queries
 // are taken in ascending index, a query's nodes in tuple order, and a query enters the batch
 // together with all its nodes or ends the search.  The workgroup reproduces that order without
 // walking the queue one node at a time: it takes the next stretch of the queue whose query
-// lists hold at most kBfsChunk entries, numbers those entries ("candidates") in queue order,
+// lists hold at most a chunk of entries (1,024, fewer for small batches), numbers those
+// entries ("candidates") in queue order,
 // and lets every query keep the smallest candidate number that names it (atomic minimum in a
 // hash table).  The candidates that kept their query are the newly reached queries, in the
 // order the queue would have reached them; their nodes are numbered (query's place, position
@@ -19,9 +20,9 @@ namespace surel {
 
 namespace {
 
-constexpr int kBfsThreads = 256;
-constexpr int kBfsPer = 4;                          // candidates (or new queries) per thread
-constexpr int kBfsChunk = kBfsThreads * kBfsPer;    // candidates settled at a time
+constexpr int kBfsPer = 4;        // candidates (or new queries) per thread
+constexpr int kBfsMaxThreads = 256;  // a workgroup has 256 threads, or 64 for small batches
+constexpr int kBfsMaxChunk = kBfsMaxThreads * kBfsPer;  // candidates settled at a time, at most
 constexpr int kBfsMaxK = 3;
 constexpr uint32_t kBfsEmpty = 0xFFFFFFFFu;
 
@@ -56,7 +57,8 @@ __device__ __forceinline__ uint32_t insert_min(uint32_t* tab, uint32_t mask, uin
     return kBfsEmpty;
 }
 
-// Exclusive prefix sum of one value per thread over the workgroup; *total = the sum.
+// Exclusive prefix sum of one value per thread over the workgroup of T threads; *total = the sum.
+template <int T>
 __device__ __forceinline__ uint32_t bfs_block_scan(uint32_t v, uint32_t* total, uint32_t* wave_sums) {
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
@@ -66,7 +68,7 @@ __device__ __forceinline__ uint32_t bfs_block_scan(uint32_t v, uint32_t* total, 
     __syncthreads();
     uint32_t base = 0, sum = 0;
 #pragma unroll
-    for (int w = 0; w < kBfsThreads / kWave; ++w) {
+    for (int w = 0; w < T / kWave; ++w) {
         if (w < wave) base += wave_sums[w];
         sum += wave_sums[w];
     }
@@ -91,16 +93,19 @@ struct BfsArgs {
     int32_t* __restrict__ counts;        // [n_batches][2]
     uint32_t* tables;                    // per workgroup: query table, node table
     uint32_t slots_q, slots_v;           // powers of two
+    uint32_t chunk;                      // candidates settled at a time: at most four per thread
     uint32_t* err;
 };
 
-__global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
-    __shared__ uint32_t wave_sums[kBfsThreads / kWave];
-    __shared__ uint32_t pre[kBfsThreads + 1];       // candidates before each node of the stretch
-    __shared__ uint32_t cand_q[kBfsChunk];          // query of each candidate
-    __shared__ uint32_t cand_slot[kBfsChunk];       // its slot in the query table
-    __shared__ uint32_t new_q[kBfsChunk];           // newly reached queries, in order
-    __shared__ uint32_t node_slot[kBfsChunk * kBfsMaxK];
+template <int T>
+__global__ __launch_bounds__(T) void bfs_batch_kernel(BfsArgs a) {
+    constexpr int kChunk = T * kBfsPer;          // a.chunk <= kChunk
+    __shared__ uint32_t wave_sums[T / kWave];
+    __shared__ uint32_t pre[T + 1];              // candidates before each node of the stretch
+    __shared__ uint32_t cand_q[kChunk];          // query of each candidate
+    __shared__ uint32_t cand_slot[kChunk];       // its slot in the query table
+    __shared__ uint32_t new_q[kChunk];           // newly reached queries, in order
+    __shared__ uint32_t node_slot[kChunk * kBfsMaxK];
     __shared__ uint32_t s_take;
 
     const int tid = threadIdx.x;
@@ -117,13 +122,16 @@ __global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
         int32_t* tuples = a.tuples ? a.tuples + b * (int64_t)a.B2 * k : nullptr;
         const int32_t* start = a.start + b * (int64_t)a.n_start;
 
-        for (uint32_t i = tid; i < 2u * (a.slots_q + a.slots_v); i += kBfsThreads) q_tab[i] = kBfsEmpty;
+        // both tables empty (they lie back to back; 16 bytes a store)
+        uint4* clear = reinterpret_cast<uint4*>(q_tab);
+        for (uint32_t i = tid; i < (a.slots_q + a.slots_v) / 2u; i += T)
+            clear[i] = make_uint4(kBfsEmpty, kBfsEmpty, kBfsEmpty, kBfsEmpty);
         __threadfence();
         __syncthreads();
 
         uint32_t n_v = 0, n_b = 0;
         // the seed-set: distinct start nodes in the order given, B1 at most
-        for (int32_t s0 = 0; s0 < a.n_start && n_v < (uint32_t)a.B1; s0 += kBfsChunk) {
+        for (int32_t s0 = 0; s0 < a.n_start && n_v < (uint32_t)a.B1; s0 += kChunk) {
             uint32_t slot[kBfsPer];
             int32_t node[kBfsPer];
 #pragma unroll
@@ -150,7 +158,7 @@ __global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
                 own |= mine ? 1u << r : 0u;
             }
             uint32_t total;
-            uint32_t at = n_v + bfs_block_scan((uint32_t)__popc(own), &total, wave_sums);
+            uint32_t at = n_v + bfs_block_scan<T>((uint32_t)__popc(own), &total, wave_sums);
 #pragma unroll
             for (int r = 0; r < kBfsPer; ++r)
                 if (own & (1u << r)) {
@@ -167,29 +175,29 @@ __global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
         uint32_t cand_base = 0;  // candidates numbered so far
         while (!done && head < n_v) {
             // the stretch: nodes head .. head+nf, thread t looks at node head+t
-            const uint32_t nf = min((uint32_t)kBfsThreads, n_v - head);
+            const uint32_t nf = min((uint32_t)T, n_v - head);
             uint32_t deg = 0;
             if ((uint32_t)tid < nf) {
                 const int32_t u = vbar[head + tid];
                 const int64_t len = a.inc_off[u + 1] - a.inc_off[u] - (tid == 0 ? (int64_t)j_cur : 0);
                 bad_lists |= len < 0;
                 // a list longer than a chunk is taken in pieces; how much longer does not matter
-                deg = (uint32_t)max((int64_t)0, min(len, (int64_t)kBfsChunk + 1));
+                deg = (uint32_t)max((int64_t)0, min(len, (int64_t)a.chunk + 1));
             }
             uint32_t total;
-            const uint32_t excl = bfs_block_scan(deg, &total, wave_sums);
+            const uint32_t excl = bfs_block_scan<T>(deg, &total, wave_sums);
             pre[tid] = excl;
-            if (tid == kBfsThreads - 1) pre[kBfsThreads] = total;
+            if (tid == T - 1) pre[T] = total;
             if (tid == 0) s_take = 0;
             __syncthreads();
-            // nodes taken whole: the longest prefix of the stretch with at most kBfsChunk entries
-            if ((uint32_t)tid < nf && pre[tid + 1] <= (uint32_t)kBfsChunk &&
-                ((uint32_t)tid + 1 == nf || pre[tid + 2] > (uint32_t)kBfsChunk))
+            // nodes taken whole: the longest prefix of the stretch with at most a.chunk entries
+            if ((uint32_t)tid < nf && pre[tid + 1] <= a.chunk &&
+                ((uint32_t)tid + 1 == nf || pre[tid + 2] > a.chunk))
                 s_take = (uint32_t)tid + 1;
             __syncthreads();
             const uint32_t take = s_take;
             const bool partial = take == 0;  // the first node's list alone is longer than a chunk
-            const uint32_t n_c = partial ? (uint32_t)kBfsChunk : pre[take];
+            const uint32_t n_c = partial ? a.chunk : pre[take];
             const uint32_t n_src = partial ? 1u : take;
 
             // candidates: entry j of node t' of the stretch, numbered cand_base + c
@@ -231,7 +239,7 @@ __global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
                     own |= 1u << r;
             }
             uint32_t n_new;
-            uint32_t at = bfs_block_scan((uint32_t)__popc(own), &n_new, wave_sums);
+            uint32_t at = bfs_block_scan<T>((uint32_t)__popc(own), &n_new, wave_sums);
 #pragma unroll
             for (int r = 0; r < kBfsPer; ++r)
                 if (own & (1u << r)) new_q[at++] = cand_q[(uint32_t)tid * kBfsPer + r];
@@ -276,7 +284,7 @@ __global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
                 }
             }
             uint32_t all_fresh;
-            uint32_t before = n_v + bfs_block_scan(n_fresh, &all_fresh, wave_sums);
+            uint32_t before = n_v + bfs_block_scan<T>(n_fresh, &all_fresh, wave_sums);
             // a query is taken if the queue would have reached it: room for its nodes, and neither
             // limit met by the queries before it
             uint32_t n_ok = 0, nodes_ok = 0;
@@ -297,8 +305,8 @@ __global__ __launch_bounds__(kBfsThreads) void bfs_batch_kernel(BfsArgs a) {
                 before += mine;
             }
             uint32_t took, took_nodes;
-            (void)bfs_block_scan(n_ok, &took, wave_sums);
-            (void)bfs_block_scan(nodes_ok, &took_nodes, wave_sums);
+            (void)bfs_block_scan<T>(n_ok, &took, wave_sums);
+            (void)bfs_block_scan<T>(nodes_ok, &took_nodes, wave_sums);
 #pragma unroll
             for (int r = 0; r < kBfsPer; ++r) {
                 const uint32_t i = (uint32_t)tid * kBfsPer + r;
@@ -344,19 +352,29 @@ uint32_t pow2_at_least(uint64_t x) {
 
 }  // namespace
 
+// Candidates settled at a time: every one of them may turn out to be a new query whose nodes
+// are entered into the node table before the limits cut, so small batches take small bites.
+static uint32_t bfs_chunk(int32_t B2) {
+    const uint32_t want = pow2_at_least(4ull * (uint64_t)B2);
+    return want < 64u ? 64u : (want > (uint32_t)kBfsMaxChunk ? (uint32_t)kBfsMaxChunk : want);
+}
+// One wavefront per search where a chunk fits its four candidates a lane: more searches in
+// flight per compute unit, and their barriers cost nothing.
+static int bfs_threads(int32_t B2) { return bfs_chunk(B2) <= (uint32_t)(kWave * kBfsPer) ? kWave : kBfsMaxThreads; }
+
 // Slots of the two hash tables of one workgroup: at most half of them are ever used.
-static uint32_t bfs_slots_q(int32_t B2) { return pow2_at_least(2ull * ((uint64_t)B2 + kBfsChunk)); }
-static uint32_t bfs_slots_v(int32_t B1, int32_t n_start) {
-    return pow2_at_least(2ull * ((uint64_t)B1 + (uint64_t)kBfsChunk * kBfsMaxK + (uint64_t)n_start));
+static uint32_t bfs_slots_q(int32_t B2) { return pow2_at_least(2ull * ((uint64_t)B2 + bfs_chunk(B2))); }
+static uint32_t bfs_slots_v(int32_t B1, int32_t B2, int32_t n_start) {
+    return pow2_at_least(2ull * ((uint64_t)B1 + (uint64_t)bfs_chunk(B2) * kBfsMaxK + (uint64_t)n_start));
 }
 
 static size_t bfs_table_bytes(int32_t n_start, int32_t B1, int32_t B2) {
-    return 2u * sizeof(uint32_t) * ((size_t)bfs_slots_q(B2) + bfs_slots_v(B1, n_start));
+    return 2u * sizeof(uint32_t) * ((size_t)bfs_slots_q(B2) + bfs_slots_v(B1, B2, n_start));
 }
 
-// Searches in flight: four workgroups a compute unit, fewer if their tables would pass 4 GiB.
-static int bfs_grid(int n_cu, int64_t n_batches, size_t table_bytes) {
-    int64_t resident = (int64_t)n_cu * 4;
+// Searches in flight: 16 waves a compute unit, fewer if their tables would pass 4 GiB.
+static int bfs_grid(int n_cu, int64_t n_batches, size_t table_bytes, int threads) {
+    int64_t resident = (int64_t)n_cu * (16 * kWave / threads);
     const int64_t by_memory = (int64_t)(((size_t)4 << 30) / table_bytes);
     if (resident > by_memory) resident = by_memory > 0 ? by_memory : 1;
     return (int)(n_batches < resident ? n_batches : resident);
@@ -364,7 +382,7 @@ static int bfs_grid(int n_cu, int64_t n_batches, size_t table_bytes) {
 
 size_t bfs_scratch_bytes(int n_cu, int64_t n_batches, int32_t n_start, int32_t B1, int32_t B2) {
     const size_t per = bfs_table_bytes(n_start, B1, B2);
-    return (size_t)bfs_grid(n_cu, n_batches, per) * per;
+    return (size_t)bfs_grid(n_cu, n_batches, per, bfs_threads(B2)) * per;
 }
 
 hipError_t launch_bfs_batches(hipStream_t stream, int n_cu, const int32_t* queries,
@@ -391,10 +409,16 @@ hipError_t launch_bfs_batches(hipStream_t stream, int n_cu, const int32_t* queri
     a.counts = counts;
     a.tables = static_cast<uint32_t*>(scratch);
     a.slots_q = bfs_slots_q(B2);
-    a.slots_v = bfs_slots_v(B1, n_start);
+    a.slots_v = bfs_slots_v(B1, B2, n_start);
+    a.chunk = bfs_chunk(B2);
     a.err = err;
-    const int grid = bfs_grid(n_cu, n_batches, bfs_table_bytes(n_start, B1, B2));
-    bfs_batch_kernel<<<dim3((unsigned)grid), dim3(kBfsThreads), 0, stream>>>(a);
+    const int threads = bfs_threads(B2);
+    const int grid = bfs_grid(n_cu, n_batches, bfs_table_bytes(n_start, B1, B2), threads);
+    if (threads == kWave) {
+        bfs_batch_kernel<kWave><<<dim3((unsigned)grid), dim3(kWave), 0, stream>>>(a);
+    } else {
+        bfs_batch_kernel<kBfsMaxThreads><<<dim3((unsigned)grid), dim3(kBfsMaxThreads), 0, stream>>>(a);
+    }
     return hipGetLastError();
 }
 
