@@ -168,3 +168,8 @@ def test_bfs_batches_on_the_workloads_queries(ctx, name):
                              which=rng.choice(n_batches, size=12, replace=False))
     print(f"[{name}] batches: mean nodes {counts[:, 0].mean():.0f}, mean queries {counts[:, 1].mean():.0f}",
           flush=True)
+    # the paper's default limits (Sec. 4.1: batch capacity 1500, batch size 32), many batches
+    start = rng.choice(in_queries, size=(4096, 4)).astype(np.int32)
+    counts = compare_batches(ctx, queries, wl.n_nodes, start, 1500, 32,
+                             which=rng.choice(4096, size=16, replace=False))
+    assert counts[:, 1].max() <= 32 and counts[:, 0].max() <= 1500
