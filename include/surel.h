@@ -27,6 +27,10 @@
  *     partials, the walk's per-edge neighbour records, the fused kernel's look-back words,
  *     the hash tables and sort arrays of pruning and mini-batching)
  *     and a device error word; nothing else is allocated.
+ *   - Stream capture: a call that is given no h_* pointer only enqueues kernels (no memset,
+ *     no copy, no wait), so once an eager call of the same shape has grown the workspaces it
+ *     can be captured into a HIP graph and replayed.  surel_prune_rpe, surel_check and the
+ *     profile calls wait for the stream and cannot be captured.
  *   - Return value: SUREL_OK (0) or a negative SUREL_E_* code.  Arguments are validated on
  *     the host before anything is enqueued, so a call that returns SUREL_E_NULL or
  *     SUREL_E_RANGE has launched nothing.  Problems only visible on the device (a seed or

@@ -350,8 +350,11 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
     if (!ctx) return SUREL_E_CTX;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
-    if (n_seeds == 0) {
-        if (hipMemsetAsync(d_rpe_off, 0, sizeof(int64_t), ctx->stream) != hipSuccess)
+    if (n_seeds == 0) {  // rpe_off[0] = 0, by the scan's own kernels (valid under stream capture)
+        int32_t* counts = nullptr;
+        int64_t* partials = nullptr;
+        if (int rc = ensure_workspace(ctx, 0, &counts, &partials)) return rc;
+        if (surel::launch_exclusive_scan(ctx->stream, counts, 0, d_rpe_off, partials) != hipSuccess)
             return SUREL_E_HIP;
         if (h_rows) return read_total(ctx, d_rpe_off, 0, h_rows);
         return SUREL_OK;

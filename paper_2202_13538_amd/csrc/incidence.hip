@@ -153,20 +153,18 @@ hipError_t launch_query_incidence(hipStream_t stream, const int32_t* queries, in
     while (bits < 32 && ((uint32_t)n_nodes >> bits) != 0u) ++bits;
     int cur = 0;
     for (int shift = 0; shift < bits; shift += 8) {
+        const bool last = shift + 8 >= bits;  // the last pass puts the queries where they belong
+        uint32_t* out_vals = last ? reinterpret_cast<uint32_t*>(inc_q) : val[cur ^ 1];
         sort_hist_kernel<<<dim3((unsigned)n_tiles), dim3(kWave), 0, stream>>>(key[cur], n, shift,
                                                                              n_tiles, hist);
         if (hipError_t e = launch_exclusive_scan(stream, hist, cells, first, partials); e != hipSuccess)
             return e;
         sort_scatter_kernel<<<dim3((unsigned)n_tiles), dim3(kWave), 0, stream>>>(
-            key[cur], val[cur], n, shift, n_tiles, first, key[cur ^ 1], val[cur ^ 1]);
+            key[cur], val[cur], n, shift, n_tiles, first, key[cur ^ 1], out_vals);
         cur ^= 1;
     }
     incidence_offsets_kernel<<<dim3((unsigned)(((int64_t)n_nodes + 1 + 255) / 256)), dim3(256), 0,
                                stream>>>(key[cur], n, n_nodes, inc_off);
-    if (hipError_t e = hipMemcpyAsync(inc_q, val[cur], (size_t)n * sizeof(int32_t),
-                                      hipMemcpyDeviceToDevice, stream);
-        e != hipSuccess)
-        return e;
     return hipGetLastError();
 }
 

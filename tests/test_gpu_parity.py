@@ -348,6 +348,57 @@ def test_fused_kernel_seed_counts_around_its_group_and_window_sizes(ctx, M, m):
         assert torch.equal(f_cnt.view(torch.int16), cnt.view(torch.int16)), f"counts differ at {n}"
 
 
+def test_one_pass_captured_in_a_graph_replays_to_the_same_bytes():
+    # with no row totals asked for, the calls only enqueue kernels: a pass can be captured once
+    # and replayed; every replay (with other work on the stream in between) gives the eager bytes
+    wl = synth.Workload("t", "rmat", 4096, 30000, 0.0, 50, 4, 0, 2, "uniform", graph_seed=9)
+    rp, ci = synth.make_graph(wl)
+    rng = np.random.default_rng(4)
+    seeds = rng.integers(0, wl.n_nodes, size=1500).astype(np.int32)
+    queries = rng.integers(0, seeds.size, size=(700, 2)).astype(np.int32)
+    M, m, L, S = wl.M, wl.m, wl.m + 1, seeds.size
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        c = binding.Context(stream=stream)
+        d_rp, d_ci, d_seeds, d_q = dev(rp), dev(ci), dev(seeds), dev(queries)
+        cap_r = binding.rpe_rows_bound(S, M, m)
+        walks = torch.empty((S, M, L), dtype=torch.int32, device="cuda")
+        off = torch.empty(S + 1, dtype=torch.int64, device="cuda")
+        ids = torch.empty(cap_r, dtype=torch.int32, device="cuda")
+        cnt = torch.empty((cap_r, L), dtype=torch.uint16, device="cuda")
+        joff = torch.empty(queries.shape[0] + 1, dtype=torch.int64, device="cuda")
+        max_set = 1 + M * m
+        # eager pass: sizes the join's output, warms the context's workspaces, is the reference
+        rc, R = binding.sample_walks_rpe_raw(c, d_rp, d_ci, d_seeds, M, m, 5, walks, cap_r, off, ids, cnt)
+        assert rc == binding.OK
+        rc, J = binding.join_queries_raw(c, off, ids, cnt, d_q, max_set, 0, joff, None, None)
+        assert rc == binding.OK
+        jids = torch.empty(J, dtype=torch.int32, device="cuda")
+        jcnt = torch.empty((J, 2, L), dtype=torch.uint16, device="cuda")
+        rc, _ = binding.join_queries_raw(c, off, ids, cnt, d_q, max_set, J, joff, jids, jcnt)
+        assert rc == binding.OK and c.check() == 0
+        outs = [walks, off, ids[:R], cnt[:R].view(torch.int16), joff, jids, jcnt.view(torch.int16)]
+        want = [t.clone() for t in outs]
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream, capture_error_mode="thread_local"):
+            rc1, _ = binding.sample_walks_rpe_raw(c, d_rp, d_ci, d_seeds, M, m, 5, walks, cap_r, off,
+                                                  ids, cnt, want_rows=False)
+            rc2, _ = binding.join_queries_raw(c, off, ids, cnt, d_q, max_set, J, joff, jids, jcnt,
+                                              want_rows=False)
+        assert rc1 == binding.OK and rc2 == binding.OK
+        for replay in range(3):
+            for t in outs:
+                t.fill_(-7 - replay)                 # eager work between the replays
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            assert c.check() == 0, f"replay {replay}"
+            for got, ref in zip(outs, want):
+                assert torch.equal(got, ref), f"replay {replay} differs from the eager pass"
+        c.close()
+
+
 def test_fused_kernel_waits_are_bounded(ctx):
     # with a spin limit of zero every wait inside the fused kernel gives up at once: the kernel
     # must still end, say so, and write nothing out of place; the default limit then gives the
