@@ -123,20 +123,28 @@ int drain_spans(surel_ctx* ctx) {
     return SUREL_OK;
 }
 
+// Grows one of the context's workspaces to `need` bytes (contents are not kept).  The old
+// buffer may still be in use by earlier work on the stream, so the stream is drained first.
+int grow_buffer(surel_ctx* ctx, void** buf, size_t* have, size_t need) {
+    if (need <= *have) return SUREL_OK;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
+    if (*buf) (void)hipFree(*buf);
+    *buf = nullptr;
+    *have = 0;
+    if (hipMalloc(buf, need) != hipSuccess) {
+        (void)hipGetLastError();
+        return SUREL_E_HIP;
+    }
+    *have = need;
+    return SUREL_OK;
+}
+
 // Workspace: int32 counts[n] followed by the int64 scan partials.
 int ensure_workspace(surel_ctx* ctx, int64_t n, int32_t** counts, int64_t** partials) {
     const size_t counts_bytes = align_up((size_t)(n > 0 ? n : 1) * sizeof(int32_t), 256);
     const size_t part_bytes = (size_t)surel::scan_partials_len(n) * sizeof(int64_t);
     const size_t need = counts_bytes + align_up(part_bytes, 256);
-    if (need > ctx->ws_bytes) {
-        // the old workspace may still be in use by earlier work on the stream
-        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
-        if (ctx->d_ws) (void)hipFree(ctx->d_ws);
-        ctx->d_ws = nullptr;
-        ctx->ws_bytes = 0;
-        if (hipMalloc(&ctx->d_ws, need) != hipSuccess) return SUREL_E_HIP;
-        ctx->ws_bytes = need;
-    }
+    if (int rc = grow_buffer(ctx, &ctx->d_ws, &ctx->ws_bytes, need)) return rc;
     *counts = static_cast<int32_t*>(ctx->d_ws);
     *partials = reinterpret_cast<int64_t*>(static_cast<char*>(ctx->d_ws) + counts_bytes);
     return SUREL_OK;
@@ -161,17 +169,7 @@ int make_edge_records(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d
     *records = nullptr;
     if (!surel::walks_want_records(n_edges, n_seeds, M, m)) return SUREL_OK;
     const size_t need = (size_t)n_edges * 16;
-    if (need > ctx->rec_bytes) {
-        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
-        if (ctx->d_rec) (void)hipFree(ctx->d_rec);
-        ctx->d_rec = nullptr;
-        ctx->rec_bytes = 0;
-        if (hipMalloc(&ctx->d_rec, need) == hipSuccess) {
-            ctx->rec_bytes = need;
-        } else {
-            (void)hipGetLastError();
-        }
-    }
+    (void)grow_buffer(ctx, &ctx->d_rec, &ctx->rec_bytes, need);
     if (ctx->rec_bytes < need) return SUREL_OK;
     KernelSpan span(ctx, SUREL_K_EDGE_RECORDS);
     if (surel::launch_edge_records(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
@@ -364,14 +362,7 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
                                    &records))
         return rc;
     const size_t lb_need = (size_t)surel::walk_rpe_lookback_words(n_seeds) * sizeof(uint64_t);
-    if (lb_need > ctx->lb_bytes) {
-        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
-        if (ctx->d_lb) (void)hipFree(ctx->d_lb);
-        ctx->d_lb = nullptr;
-        ctx->lb_bytes = 0;
-        if (hipMalloc(&ctx->d_lb, lb_need) != hipSuccess) return SUREL_E_HIP;
-        ctx->lb_bytes = lb_need;
-    }
+    if (int rc = grow_buffer(ctx, &ctx->d_lb, &ctx->lb_bytes, lb_need)) return rc;
     {
         KernelSpan span(ctx, SUREL_K_WALK_RPE);
         hipError_t hrc = surel::launch_walk_rpe(
@@ -475,14 +466,7 @@ int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, i
     const size_t slot_bytes = surel::prune_slot_bytes(cap_T);
     const size_t list_bytes = align_up(surel::prune_list_bytes(cap_T), 256);
     const size_t need = slot_bytes + list_bytes + 256;
-    if (need > ctx->prune_bytes) {
-        if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
-        if (ctx->d_prune) (void)hipFree(ctx->d_prune);
-        ctx->d_prune = nullptr;
-        ctx->prune_bytes = 0;
-        if (hipMalloc(&ctx->d_prune, need) != hipSuccess) return SUREL_E_HIP;
-        ctx->prune_bytes = need;
-    }
+    if (int rc = grow_buffer(ctx, &ctx->d_prune, &ctx->prune_bytes, need)) return rc;
     char* ws = static_cast<char*>(ctx->d_prune);
     uint32_t* slots = reinterpret_cast<uint32_t*>(ws);
     uint32_t* list = reinterpret_cast<uint32_t*>(ws + slot_bytes);
@@ -505,18 +489,6 @@ int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, i
     return SUREL_OK;
 }
 
-// Grows the mini-batching workspace to `need` bytes (contents are not kept).
-static int ensure_batch_workspace(surel_ctx* ctx, size_t need) {
-    if (need <= ctx->batch_bytes) return SUREL_OK;
-    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
-    if (ctx->d_batch) (void)hipFree(ctx->d_batch);
-    ctx->d_batch = nullptr;
-    ctx->batch_bytes = 0;
-    if (hipMalloc(&ctx->d_batch, need) != hipSuccess) return SUREL_E_HIP;
-    ctx->batch_bytes = need;
-    return SUREL_OK;
-}
-
 int surel_query_incidence(surel_ctx* ctx, const int32_t* d_queries, int64_t n_queries, int32_t k,
                           int32_t n_nodes, int64_t* d_inc_off, int32_t* d_inc_q) {
     if (n_nodes < 1 || n_nodes > SUREL_MAX_NODES || n_queries < 0) return SUREL_E_RANGE;
@@ -525,7 +497,9 @@ int surel_query_incidence(surel_ctx* ctx, const int32_t* d_queries, int64_t n_qu
     if (!ctx) return SUREL_E_CTX;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
-    if (int rc = ensure_batch_workspace(ctx, surel::incidence_scratch_bytes(n_queries * k))) return rc;
+    if (int rc = grow_buffer(ctx, &ctx->d_batch, &ctx->batch_bytes,
+                             surel::incidence_scratch_bytes(n_queries * k)))
+        return rc;
     KernelSpan span(ctx, SUREL_K_BATCH);
     if (surel::launch_query_incidence(ctx->stream, d_queries, n_queries, k, n_nodes, d_inc_off,
                                       d_inc_q, ctx->d_batch, ctx->d_err) != hipSuccess)
@@ -549,7 +523,8 @@ int surel_bfs_batches(surel_ctx* ctx, const int32_t* d_queries, int64_t n_querie
     if (n_batches == 0) return SUREL_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
-    if (int rc = ensure_batch_workspace(ctx, surel::bfs_scratch_bytes(ctx->n_cu, n_batches, n_start, B1, B2)))
+    if (int rc = grow_buffer(ctx, &ctx->d_batch, &ctx->batch_bytes,
+                             surel::bfs_scratch_bytes(ctx->n_cu, n_batches, n_start, B1, B2)))
         return rc;
     KernelSpan span(ctx, SUREL_K_BATCH);
     if (surel::launch_bfs_batches(ctx->stream, ctx->n_cu, d_queries, n_queries, k, n_nodes, d_inc_off,
