@@ -126,6 +126,15 @@ def test_bfs_batches_with_long_lists_wide_levels_and_many_seeds(ctx):
     compare_batches(ctx, queries3, 500, start, 10 ** 6, 33)
 
 
+def test_bfs_batches_of_single_node_queries(ctx):
+    # k = 1: a query shares its node with the queries that name the same node, nothing spreads
+    rng = np.random.default_rng(12)
+    queries = rng.integers(0, 50, size=(400, 1)).astype(np.int32)
+    start = rng.integers(0, 50, size=(20, 3)).astype(np.int32)
+    compare_batches(ctx, queries, 50, start, 100, 100)
+    compare_batches(ctx, queries, 50, start, 100, 7)
+
+
 def test_bfs_batches_degenerate_inputs(ctx):
     # no queries at all: every batch is its seed-set
     empty = torch.empty((0, 2), dtype=torch.int32, device="cuda")
