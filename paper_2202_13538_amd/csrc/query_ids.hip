@@ -12,15 +12,23 @@
 // blocks as flat arrays: a lane takes kQiEntries walk entries at a time and searches each in
 // all K lists with a fixed number of branch-free steps, so that the K * kQiEntries searches
 // of a round advance together and their LDS reads overlap; the K row indices of an entry lie
-// next to each other in the output.
+// next to each other in the output and go out as one store.  The first round of every walk
+// block (the whole block, for up to 512 entries) is loaded before the id lists are staged:
+// a query then costs one wait for memory, not one per block.
 #include "device_util.h"
 #include "kernels.h"
 
 namespace surel {
 
-constexpr int kQiEntries = 2;  // walk entries a lane looks up at a time
+// The K row indices of one walk entry (4-byte aligned, written with one store).
+template <int K>
+struct __attribute__((aligned(4))) RowIds {
+    int32_t v[K];
+};
 
-template <int K, int WPB>
+// kQiEntries: walk entries a lane looks up at a time (1, 2, 4 or 8: enough for a whole walk block
+// of up to 512 entries in one round).
+template <int K, int WPB, int kQiEntries>
 __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
     const int32_t* __restrict__ walks, const int64_t* __restrict__ rpe_off,
     const int32_t* __restrict__ rpe_ids, int64_t n_blocks, int32_t n_key, int32_t max_set,
@@ -69,6 +77,16 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
             for (int t = lane; t < K * n_key * K; t += kWave) out_q[t] = -1;
             continue;
         }
+        // the first kQiEntries * 64 entries of every walk block (all of it, for the usual sizes)
+        // are asked for before the id lists, so that one wait covers both
+        uint32_t x_first[K][kQiEntries];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const int32_t* W = walks + (int64_t)blk[j] * n_key;
+#pragma unroll
+            for (int e = 0; e < kQiEntries; ++e)
+                x_first[j][e] = (uint32_t)__builtin_nontemporal_load(W + min(e * kWave + lane, n_key - 1));
+        }
         int top[K];  // largest power of two <= n[j] (0 for an empty list): the first step
 #pragma unroll
         for (int j = 0; j < K; ++j) {
@@ -91,7 +109,7 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
 #pragma unroll
                 for (int e = 0; e < kQiEntries; ++e) {
                     const int t = min(t0 + e * kWave + lane, n_key - 1);
-                    x[e] = (uint32_t)__builtin_nontemporal_load(W + t);
+                    x[e] = t0 == 0 ? x_first[j][e] : (uint32_t)__builtin_nontemporal_load(W + t);
 #pragma unroll
                     for (int j2 = 0; j2 < K; ++j2) pos[e][j2] = 0;
                 }
@@ -121,8 +139,11 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
                         row[j2] = found ? (int32_t)(lo[j2] + p) : -1;
                     }
                     if (t < n_key) {
+                        // the K indices of an entry as one 4*K-byte store
+                        RowIds<K> ids;
 #pragma unroll
-                        for (int j2 = 0; j2 < K; ++j2) out_j[(int64_t)t * K + j2] = row[j2];
+                        for (int j2 = 0; j2 < K; ++j2) ids.v[j2] = row[j2];
+                        *reinterpret_cast<RowIds<K>*>(out_j + (int64_t)t * K) = ids;
                     }
                 }
             }
@@ -131,14 +152,14 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
     }
 }
 
-template <int K, int WPB>
-static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_t* walks,
+template <int K, int WPB, int QE>
+static hipError_t launch_query_ids_kwe(hipStream_t stream, int n_cu, const int32_t* walks,
                                       const int64_t* rpe_off, const int32_t* rpe_ids,
                                       int64_t n_blocks, int32_t M, int32_t m, int32_t max_set,
                                       int64_t table_rows, const int32_t* queries,
                                       int64_t n_queries, int32_t* out, uint32_t* err) {
     const size_t lds_bytes = (size_t)WPB * K * (max_set + 1) * 4;
-    const void* fn = reinterpret_cast<const void*>(query_ids_kernel<K, WPB>);
+    const void* fn = reinterpret_cast<const void*>(query_ids_kernel<K, WPB, QE>);
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)lds_bytes);
@@ -150,10 +171,27 @@ static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_
     if (per_cu < 1) return hipErrorInvalidValue;
     int64_t blocks = (n_queries + WPB - 1) / WPB;
     if (blocks > (int64_t)per_cu * n_cu) blocks = (int64_t)per_cu * n_cu;
-    hipLaunchKernelGGL((query_ids_kernel<K, WPB>), dim3((unsigned)blocks), dim3(WPB * kWave),
+    hipLaunchKernelGGL((query_ids_kernel<K, WPB, QE>), dim3((unsigned)blocks), dim3(WPB * kWave),
                        lds_bytes, stream, walks, rpe_off, rpe_ids, n_blocks, M * (m + 1), max_set,
                        table_rows, queries, n_queries, out, err);
     return hipGetLastError();
+}
+
+template <int K, int WPB>
+static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_t* walks,
+                                      const int64_t* rpe_off, const int32_t* rpe_ids,
+                                      int64_t n_blocks, int32_t M, int32_t m, int32_t max_set,
+                                      int64_t table_rows, const int32_t* queries,
+                                      int64_t n_queries, int32_t* out, uint32_t* err) {
+    const int64_t n_key = (int64_t)M * (m + 1);
+#define SUREL_QI_ENTRIES(QE_)                                                                     \
+    return launch_query_ids_kwe<K, WPB, QE_>(stream, n_cu, walks, rpe_off, rpe_ids, n_blocks, M, \
+                                             m, max_set, table_rows, queries, n_queries, out, err)
+    if (n_key <= kWave) SUREL_QI_ENTRIES(1);
+    if (n_key <= 2 * kWave) SUREL_QI_ENTRIES(2);
+    if (n_key <= 4 * kWave) SUREL_QI_ENTRIES(4);
+    SUREL_QI_ENTRIES(8);
+#undef SUREL_QI_ENTRIES
 }
 
 template <int K>
