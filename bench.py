@@ -202,6 +202,16 @@ def main() -> int:
     join_ids = torch.empty(J, dtype=torch.int32, device="cuda")
     join_cnt = torch.empty((J, k, L), dtype=torch.uint16, device="cuda")
     in_rows = int((rpe_off[1:] - rpe_off[:-1])[d_q.long()].sum())
+    # what the synthetic input looks like (the byte formulas depend on it)
+    deg = np.diff(rp)
+    set_len = (rpe_off[1:] - rpe_off[:-1]).float()
+    input_stats = {
+        "csr_entries": int(ci.size), "max_degree": int(deg.max()), "isolated_nodes": int((deg == 0).sum()),
+        "set_size_mean": round(float(set_len.mean()), 2),
+        "set_size_p95": int(torch.quantile(set_len[:: max(1, N // 1_000_000)], 0.95)),
+        "joined_rows_per_query": round(J / Q, 2),
+        "shared_nodes_per_query": round((in_rows - J) / Q, 2),
+    }
     log(f"[bench] R={R} RPE rows, J={J} joined rows, {in_rows} table rows read by the join")
 
     def one_step():
@@ -264,7 +274,8 @@ def main() -> int:
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": wl.name, "graph": wl.graph, "n_nodes": N, "n_edges": wl.n_edges,
                    "M": M, "m": m, "n_queries": Q, "k": k, "rpe_rows": R, "joined_rows": J,
-                   "walk_and_rpe": "one fused kernel" if fused else "two calls"},
+                   "walk_and_rpe": "one fused kernel" if fused else "two calls",
+                   "input_stats": input_stats},
         "walk_steps_per_s": N * M * m / (walk_ms * 1e-3) if walk_ms else None,
         "rpe_rows_per_s": R / (rpe_ms * 1e-3) if rpe_ms else None,
         "joined_rows_per_s": J / (join_ms * 1e-3) if join_ms else None,
