@@ -686,3 +686,61 @@ def test_cl2900k_full_size(ctx):
 
 def test_cl1m_triples_full_size(ctx):
     check_workload(ctx, "cl1m_triples")
+
+
+def test_table_with_more_than_2_31_rows(ctx):
+    # the 2.9M-node graph with M = 330: 2.35 G table rows, so row numbers and byte offsets pass
+    # 2^31 and 2^32; fused kernel against the two calls in full, then seeds (mostly from the far
+    # end of the table) and queries against the oracle
+    wl = synth.WORKLOADS["cl2900k"]
+    M, m = 330, 4
+    L = m + 1
+    rp, ci = synth.make_graph(wl)
+    queries = synth.make_queries(wl, rp, ci)[:200000]
+    N = wl.n_nodes
+    d_rp, d_ci, d_q = dev(rp), dev(ci), dev(queries)
+    seeds = torch.arange(N, dtype=torch.int32, device="cuda")
+    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, seeds, M, m, 0)
+    assert ctx.check() == 0
+    R = int(f_off[-1])
+    assert R > 2 ** 31 and bool((f_off[1:] > f_off[:-1]).all())
+    print(f"[2^31] fused done: R={R}", flush=True)
+    sizes = torch.empty(N, dtype=torch.int32, device="cuda")
+    walks = binding.sample_walks(ctx, d_rp, d_ci, seeds, M, m, 0, set_sizes=sizes)
+    assert torch.equal(walks, f_walks)
+    del walks
+    off = torch.empty(N + 1, dtype=torch.int64, device="cuda")
+    ids = torch.empty(R, dtype=torch.int32, device="cuda")
+    cnt = torch.empty((R, L), dtype=torch.uint16, device="cuda")
+    rc, R2 = binding.build_rpe_raw(ctx, f_walks, N, R, off, ids, cnt, set_sizes=sizes)
+    assert rc == binding.OK and R2 == R and ctx.check() == 0
+    assert torch.equal(off, f_off) and torch.equal(ids, f_ids)
+    for s in range(0, R, 1 << 28):
+        e = min(R, s + (1 << 28))
+        assert torch.equal(cnt.view(torch.int16)[s:e], f_cnt.view(torch.int16)[s:e])
+    del ids, cnt, off
+    print("[2^31] the two-call path equals the fused kernel", flush=True)
+    rng = np.random.default_rng(1)
+    pick = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 200),
+                                     rng.integers(N - 5000, N, 200)])).astype(np.int32)
+    w = oracle.sample_walks(rp, ci, pick, M, m, 0)
+    assert np.array_equal(f_walks[torch.from_numpy(pick).long().cuda()].cpu().numpy(), w)
+    t_off, t_ids, t_cnt = oracle.build_rpe(w)
+    off_h = f_off.cpu().numpy()
+    assert np.array_equal(off_h[pick + 1] - off_h[pick], np.diff(t_off))
+    rows = torch.from_numpy(np.concatenate([np.arange(off_h[u], off_h[u + 1]) for u in pick])).cuda()
+    assert int(rows.max()) > 2 ** 31
+    assert np.array_equal(f_ids[rows].cpu().numpy(), t_ids)
+    assert np.array_equal(rows_u16(f_cnt, rows), t_cnt)
+    joff, jids, jcnt = binding.join_queries(ctx, f_off, f_ids, f_cnt, d_q, max_set=1 + M * m)
+    assert ctx.check() == 0
+    qp = np.unique(rng.integers(0, queries.shape[0], 150))
+    sub = queries[qp]
+    nodes, local = np.unique(sub, return_inverse=True)
+    tab = oracle.build_rpe(oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m, 0))
+    w_off, w_ids, w_cnt = oracle.join_queries(*tab, local.reshape(sub.shape).astype(np.int32))
+    joff_h = joff.cpu().numpy()
+    assert np.array_equal(joff_h[qp + 1] - joff_h[qp], np.diff(w_off))
+    jr = torch.from_numpy(np.concatenate([np.arange(joff_h[q], joff_h[q + 1]) for q in qp])).cuda()
+    assert np.array_equal(jids[jr].cpu().numpy(), w_ids)
+    assert np.array_equal(rows_u16(jcnt, jr), w_cnt)
