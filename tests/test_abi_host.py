@@ -343,3 +343,23 @@ def test_create_reports_missing_device_or_bad_arguments(lib):
     handle = ctypes.c_void_p()
     rc = lib.surel_create(ctypes.byref(handle), 1 << 20, None)   # no such device anywhere
     assert rc == binding.E_HIP and not handle.value
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/surel.h compiles as C99 with every warning on, and a C program that names every
+    declared entry point links against libsurel.so (nothing is called: no GPU here)."""
+    import subprocess
+    names = declared_functions()
+    src = tmp_path / "use_surel.c"
+    src.write_text('#include "surel.h"\n#include <stdio.h>\n'
+                   "int main(void) {\n    const void* fns[] = {\n"
+                   + "".join(f"        (const void*)&{n},\n" for n in names)
+                   + "    };\n    printf(\"%d entry points\\n\", (int)(sizeof fns / sizeof fns[0]));\n"
+                   "    return 0;\n}\n")
+    exe = tmp_path / "use_surel"
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                    "-Wno-pedantic",  # function-to-object pointer casts are the point here
+                    "-I", os.path.dirname(HEADER), str(src), "-o", str(exe),
+                    "-L", lib_dir, "-lsurel", f"-Wl,-rpath,{lib_dir}", "-Wl,--allow-shlib-undefined"],
+                   check=True)
