@@ -136,6 +136,9 @@ def main() -> int:
     ap.add_argument("--batch-size", type=int, default=4096, help="B2 of --batches")
     ap.add_argument("--batch-nodes", type=int, default=0,
                     help="B1 of --batches (default k * B2, so that B2 is the limit that binds)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one pass (no row totals read back) into a HIP graph and time "
+                         "its replays; reported under 'graph_replay', not part of 'value'")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "
@@ -169,6 +172,8 @@ def main() -> int:
         f"(generated in {time.time() - t0:.1f} s)")
 
     torch.cuda.set_device(0)
+    if args.graph:
+        torch.cuda.set_stream(torch.cuda.Stream())   # graphs are not captured on the default stream
     ctx = binding.Context(0)
     d_rp, d_ci = torch.from_numpy(rp).cuda(), torch.from_numpy(ci).cuda()
     d_q = torch.from_numpy(queries).cuda()
@@ -382,6 +387,32 @@ def main() -> int:
             "joined_rows_per_s": {"bfs_batches": rows_bfs / (join_bfs_ms * 1e-3),
                                   "given_order": rows_given / (join_given_ms * 1e-3)}}
         del vbar, batch, tuples, counts, inc_off, inc_q
+    if args.graph:
+        if not fused:
+            raise SystemExit("--graph replays the fused pass; drop --unfused")
+
+        def one_step_enqueued():
+            rc1, _ = binding.sample_walks_rpe_raw(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, walks,
+                                                  cap_r, rpe_off, rpe_ids, rpe_cnt, want_rows=False)
+            rc2, _ = binding.join_queries_raw(ctx, rpe_off, rpe_ids, rpe_cnt, d_q, max_set, J,
+                                              join_off, join_ids, join_cnt, want_rows=False)
+            assert rc1 == binding.OK and rc2 == binding.OK
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.current_stream(),
+                              capture_error_mode="thread_local"):
+            one_step_enqueued()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_g = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t_g) * 1e3 / args.steps
+        assert ctx.check() == 0 and int(rpe_off[-1]) == R and int(join_off[-1]) == J
+        out["graph_replay"] = {"ms_per_step": round(graph_ms, 4),
+                               "eager_ms_per_step": round(ms_per_step, 4)}
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
         b = torch.empty_like(a)
