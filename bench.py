@@ -136,6 +136,10 @@ def main() -> int:
     ap.add_argument("--batch-size", type=int, default=4096, help="B2 of --batches")
     ap.add_argument("--batch-nodes", type=int, default=0,
                     help="B1 of --batches (default k * B2, so that B2 is the limit that binds)")
+    ap.add_argument("--relabel-by-degree", action="store_true",
+                    help="renumber the nodes by descending degree before the run (hubs get the "
+                         "smallest ids and lie together in memory): a different input labelling, "
+                         "not a different method; the line says so in config.labelling")
     ap.add_argument("--graph", action="store_true",
                     help="also capture one pass (no row totals read back) into a HIP graph and time "
                          "its replays; reported under 'graph_replay', not part of 'value'")
@@ -168,6 +172,17 @@ def main() -> int:
     t0 = time.time()
     rp, ci = synth.make_graph(wl)
     queries = synth.make_queries(wl, rp, ci)
+    if args.relabel_by_degree:
+        deg0 = np.diff(rp)
+        order = np.argsort(-deg0, kind="stable")            # old id of the node that becomes id i
+        new_id = np.empty(N, dtype=np.int64)
+        new_id[order] = np.arange(N)
+        src = np.repeat(new_id, deg0)                        # new id of every entry's row
+        dst = new_id[ci]
+        keys = np.argsort(src * N + dst, kind="stable")     # rows in new order, ascending inside
+        ci = dst[keys].astype(np.int32)
+        rp = np.concatenate([[0], np.cumsum(deg0[order])]).astype(np.int32)
+        queries = new_id[queries].astype(np.int32)
     log(f"[bench] {wl.name}: N={N} E2={ci.size} M={M} m={m} queries={Q}x{k} "
         f"(generated in {time.time() - t0:.1f} s)")
 
@@ -280,6 +295,7 @@ def main() -> int:
         "config": {"workload": wl.name, "graph": wl.graph, "n_nodes": N, "n_edges": wl.n_edges,
                    "M": M, "m": m, "n_queries": Q, "k": k, "rpe_rows": R, "joined_rows": J,
                    "walk_and_rpe": "one fused kernel" if fused else "two calls",
+                   "labelling": "by descending degree" if args.relabel_by_degree else "random permutation",
                    "input_stats": input_stats},
         "walk_steps_per_s": N * M * m / (walk_ms * 1e-3) if walk_ms else None,
         "rpe_rows_per_s": R / (rpe_ms * 1e-3) if rpe_ms else None,
