@@ -63,6 +63,9 @@ def test_header_constants_match_binding():
     assert val["SUREL_MAX_WALK_ENTRIES"] == binding.MAX_WALK_ENTRIES
     assert val["SUREL_MAX_SET"] == binding.MAX_SET
     assert val["SUREL_MAX_TUPLE"] == binding.MAX_TUPLE
+    assert val["SUREL_MAX_DISTINCT"] == binding.MAX_DISTINCT
+    assert val["SUREL_MAX_BATCH"] == binding.MAX_BATCH
+    assert val["SUREL_DEV_STALL"] == binding.DEV_STALL
 
 
 def test_strerror_and_bound(lib):
