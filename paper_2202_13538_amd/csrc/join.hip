@@ -30,8 +30,9 @@ namespace surel {
 constexpr uint16_t kNoSrc = 0xFFFFu;
 constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
 constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
-constexpr int kPairRounds = 1;           // rounds of 64 union rows a wave gathers together (pairs;
-                                         // more than one was measured and gains nothing)
+constexpr int kPairRounds = 8;           // rounds of 64 union rows a wave gathers together (pairs):
+                                         // a quarter off the fill launch where queries are few and
+                                         // their blocks large, 2 % where occupancy hides the latency
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {
@@ -365,6 +366,7 @@ __device__ __forceinline__ void join_one_query(
             uint32_t id[kPairRounds];
 #pragma unroll
             for (int g = 0; g < kPairRounds; ++g) {
+                if (r0 + g * kWave >= n_out) break;  // wave-uniform: no round past the last row
                 const int r = min(r0 + g * kWave + lane, n_out - 1);
                 id[g] = 0;
 #pragma unroll
