@@ -30,9 +30,10 @@ namespace surel {
 constexpr uint16_t kNoSrc = 0xFFFFu;
 constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
 constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
-constexpr int kPairRounds = 8;           // rounds of 64 union rows a wave gathers together (pairs):
-                                         // a quarter off the fill launch where queries are few and
-                                         // their blocks large, 2 % where occupancy hides the latency
+constexpr int kGatherRounds = 8;         // rounds of 64 union rows a wave gathers together (pairs;
+                                         // half as many for larger tuples): a quarter off the fill
+                                         // launch where queries are few and their blocks large, 2 %
+                                         // where occupancy hides the latency
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {
@@ -327,45 +328,19 @@ __device__ __forceinline__ void join_one_query(
         // K*L/2 words in registers and stored at the row's place
         constexpr int kWords = K * LT / 2;
         uint32_t* out_words = reinterpret_cast<uint32_t*>(out_cnt) + off * kWords;
-        if constexpr (K != 2) {
-            // larger tuples: most vectors are absent, so a lane loads only those its row has
-            for (int r = lane; r < n_out; r += kWave) {
-                uint16_t v[K * LT];
-                uint32_t id = 0;
-#pragma unroll
-                for (int j = K - 1; j >= 0; --j) {
-                    const uint16_t sj = src[j * src_stride + r];
-                    // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
-                    const bool present = (int)sj < n[j];
-                    const uint16_t* from = rpe_cnt + (lo[j] + (present ? sj : 0)) * LT;
-#pragma unroll
-                    for (int e = 0; e < LT; ++e) v[j * LT + e] = 0;
-                    if (present) {
-                        id = ids_lds[j * max_set + sj];
-#pragma unroll
-                        for (int e = 0; e < LT; ++e) v[j * LT + e] = from[e];
-                    }
-                }
-                out_ids[off + r] = (int32_t)id;
-                uint32_t* row_words = out_words + (int64_t)r * kWords;
-#pragma unroll
-                for (int d = 0; d < kWords; ++d)
-                    row_words[d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
-            }
-            return;
-        }
-        // pairs: kPairRounds rounds of 64 rows are gathered together (all their loads are in
+        // kRounds rounds of 64 rows are gathered together (all their loads are in
         // flight before the first is waited for: a wave's time is a chain of memory round
         // trips), then the rounds go out one after the other
+        constexpr int kRounds = K == 2 ? kGatherRounds : kGatherRounds / 2;
         const uint32_t* cnt_words = reinterpret_cast<const uint32_t*>(rpe_cnt);
-        for (int r0 = 0; r0 < n_out; r0 += kPairRounds * kWave) {
+        for (int r0 = 0; r0 < n_out; r0 += kRounds * kWave) {
             constexpr int kCover = LT / 2 + 1;  // aligned words that cover a vector
-            uint32_t raw[kPairRounds][K][kCover + 1];
-            uint32_t shift[kPairRounds][K];
-            bool present[kPairRounds][K];
-            uint32_t id[kPairRounds];
+            uint32_t raw[kRounds][K][kCover + 1];
+            uint32_t shift[kRounds][K];
+            bool present[kRounds][K];
+            uint32_t id[kRounds];
 #pragma unroll
-            for (int g = 0; g < kPairRounds; ++g) {
+            for (int g = 0; g < kRounds; ++g) {
                 if (r0 + g * kWave >= n_out) break;  // wave-uniform: no round past the last row
                 const int r = min(r0 + g * kWave + lane, n_out - 1);
                 id[g] = 0;
@@ -392,7 +367,7 @@ __device__ __forceinline__ void join_one_query(
                 }
             }
 #pragma unroll
-            for (int g = 0; g < kPairRounds; ++g) {
+            for (int g = 0; g < kRounds; ++g) {
                 if (r0 + g * kWave >= n_out) break;
                 uint16_t v[K * LT];
 #pragma unroll
