@@ -323,6 +323,23 @@ def main() -> int:
             "ms": round(ms, 4), "walk_positions_per_s": Q * k * M * L / (ms * 1e-3),
             "algorithmic_bytes": q_bytes,
             "hbm_frac": round(q_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if args.prune:
+            # the same with the rows' codes from surel_prune_rpe: RPE-IDs into the pruned array
+            cap_T = 1 << 20
+            T = torch.empty((cap_T, L), dtype=torch.uint16, device="cuda")
+            code = torch.empty(R, dtype=torch.int32, device="cuda")
+            rc, n_T = binding.prune_rpe_raw(ctx, rpe_cnt[:R], cap_T, T, code)
+            assert rc == binding.OK, rc
+            binding.query_rpe_ids(ctx, walks, rpe_off, rpe_ids[:R], d_q, max_set, out=qid, code=code)
+            ctx.profile(True)
+            for _ in range(args.steps):
+                binding.query_rpe_ids(ctx, walks, rpe_off, rpe_ids[:R], d_q, max_set, out=qid,
+                                      code=code)
+            ms_c = ctx.profile_read()["query_ids"][0] / args.steps
+            ctx.profile(False)
+            assert ctx.check() == 0
+            out["query_rpe_ids"]["with_codes_ms"] = round(ms_c, 4)
+            del T, code
         del qid
     if args.prune:
         cap_T = 1 << 20

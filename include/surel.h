@@ -216,17 +216,21 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
  *                surel_build_rpe / surel_sample_walks_rpe over one seed list).
  *   d_rpe_off, d_rpe_ids   the RPE table (device, read-only); table_rows = its number of rows
  *                (d_rpe_off[n_blocks]), at most 2^31 - 1 so that a row index fits int32.
+ *   d_code       NULL, or int32[table_rows] (device, read-only), the rows' codes from
+ *                surel_prune_rpe: the outputs are then d_code[row] instead of row, i.e. the
+ *                RPE-IDs of Sec. 3.3 after pruning, indices into the pruned array T (what the
+ *                paper ships to the GPU, where X = T[RPE-ID] is one indexing step).
  *   max_set, d_queries, n_queries, k   as in surel_join_queries.
  *   d_out        int32[n_queries][k][M][m+1][k] (device, written):
- *                d_out[q][j][w][s][j2] = row of node d_walks[queries[q][j]][w][s] in block
- *                queries[q][j2], or -1.
+ *                d_out[q][j][w][s][j2] = row (or code of the row) of node
+ *                d_walks[queries[q][j]][w][s] in block queries[q][j2], or -1.
  * Limits: 1 <= M <= SUREL_MAX_WALKS, 1 <= m <= SUREL_MAX_STEPS, M*(m+1) < 2^31 / 9,
  * 2 <= k <= SUREL_MAX_TUPLE, 1 <= max_set <= SUREL_MAX_SET, 0 <= table_rows < 2^31.
  * Device-detected: BAD_QUERY, BAD_TABLE, SET_TOO_LARGE (that query's entries are all -1). */
 int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d_rpe_off,
-                        const int32_t* d_rpe_ids, int64_t n_blocks, int64_t table_rows, int32_t M,
-                        int32_t m, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
-                        int32_t k, int32_t* d_out);
+                        const int32_t* d_rpe_ids, const int32_t* d_code, int64_t n_blocks,
+                        int64_t table_rows, int32_t M, int32_t m, int32_t max_set,
+                        const int32_t* d_queries, int64_t n_queries, int32_t k, int32_t* d_out);
 
 /* Sec. 3.3, last paragraph / Algorithm 1, last step ("prune T"): the count vectors of the RPE
  * table repeat a lot, so they are stored once.  d_T receives the distinct vectors, sorted

@@ -48,8 +48,8 @@ SIGNATURES = {
                                               ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
-    "surel_query_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp,
-                                           _i64, _i32, _vp]),
+    "surel_query_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i32, _i32,
+                                           _vp, _i64, _i32, _vp]),
     "surel_prune_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i64, _vp, _vp,
                                        ctypes.POINTER(_i64)]),
     "surel_query_incidence": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _vp]),
@@ -306,8 +306,12 @@ def join_queries(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
 
 
 def query_rpe_ids(ctx: Context, walks: torch.Tensor, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
-                  queries: torch.Tensor, max_set: int, out: torch.Tensor | None = None):
-    """int32[n_q][k][M][m+1][k] on the GPU: the query-level RPE-IDs of every walk position."""
+                  queries: torch.Tensor, max_set: int, out: torch.Tensor | None = None,
+                  code: torch.Tensor | None = None):
+    """int32[n_q][k][M][m+1][k] on the GPU: the query-level RPE-IDs of every walk position (table
+    rows; with `code` from prune_rpe, the rows' codes, i.e. indices into the pruned array T)."""
+    if code is not None and code.numel() != rpe_ids.numel():
+        raise ValueError("code must have one entry per table row")
     n_blocks, M, L = walks.shape
     n_q, k = queries.shape
     if out is None:
@@ -316,8 +320,9 @@ def query_rpe_ids(ctx: Context, walks: torch.Tensor, rpe_off: torch.Tensor, rpe_
         raise ValueError("out has the wrong size")
     rc = load().surel_query_rpe_ids(
         ctx.handle, _ptr(walks, torch.int32, "walks"), _ptr(rpe_off, torch.int64, "rpe_off"),
-        _ptr(rpe_ids, torch.int32, "rpe_ids"), n_blocks, rpe_ids.numel(), M, L - 1, max_set,
-        _ptr(queries, torch.int32, "queries"), n_q, k, _ptr(out, torch.int32, "out"))
+        _ptr(rpe_ids, torch.int32, "rpe_ids"), _ptr(code, torch.int32, "code"), n_blocks,
+        rpe_ids.numel(), M, L - 1, max_set, _ptr(queries, torch.int32, "queries"), n_q, k,
+        _ptr(out, torch.int32, "out"))
     if rc != OK:
         raise SurelError(rc, "surel_query_rpe_ids")
     return out

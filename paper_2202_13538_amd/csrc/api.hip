@@ -431,9 +431,9 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
 }
 
 int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d_rpe_off,
-                        const int32_t* d_rpe_ids, int64_t n_blocks, int64_t table_rows, int32_t M,
-                        int32_t m, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
-                        int32_t k, int32_t* d_out) {
+                        const int32_t* d_rpe_ids, const int32_t* d_code, int64_t n_blocks,
+                        int64_t table_rows, int32_t M, int32_t m, int32_t max_set,
+                        const int32_t* d_queries, int64_t n_queries, int32_t k, int32_t* d_out) {
     if (M < 1 || M > SUREL_MAX_WALKS || m < 1 || m > SUREL_MAX_STEPS) return SUREL_E_RANGE;
     if ((int64_t)M * (m + 1) >= (int64_t)0x7FFFFFFF / 9) return SUREL_E_RANGE;
     if (k < 2 || k > SUREL_MAX_TUPLE) return SUREL_E_RANGE;
@@ -448,7 +448,7 @@ int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d
     if (!guard.ok) return SUREL_E_HIP;
     KernelSpan span(ctx, SUREL_K_QUERY_IDS);
     hipError_t hrc = surel::launch_query_ids(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_walks,
-                                             d_rpe_off, d_rpe_ids, n_blocks, M, m, max_set,
+                                             d_rpe_off, d_rpe_ids, d_code, n_blocks, M, m, max_set,
                                              table_rows, d_queries, n_queries, k, d_out,
                                              ctx->d_err);
     if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;

@@ -28,10 +28,13 @@ struct __attribute__((aligned(4))) RowIds {
 
 // kQiEntries: walk entries a lane looks up at a time (1, 2, 4 or 8: enough for a whole walk block
 // of up to 512 entries in one round).
-template <int K, int WPB, int kQiEntries>
+// kCode: the rows' codes (their RPE-IDs in the pruned array of Sec. 3.3) are staged next to the
+// ids and go out instead of the row indices.
+template <int K, int WPB, int kQiEntries, bool kCode>
 __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
     const int32_t* __restrict__ walks, const int64_t* __restrict__ rpe_off,
-    const int32_t* __restrict__ rpe_ids, int64_t n_blocks, int32_t n_key, int32_t max_set,
+    const int32_t* __restrict__ rpe_ids, const int32_t* __restrict__ code, int64_t n_blocks,
+    int32_t n_key, int32_t max_set,
     int64_t table_rows, const int32_t* __restrict__ queries, int64_t n_queries,
     int32_t* __restrict__ out, uint32_t* __restrict__ err) {
     extern __shared__ uint32_t lds32[];
@@ -40,7 +43,8 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
     // list j at [j*(max_set+1) + 1 ...); the word in front of it (index -1 of the list) is
     // never smaller than a node id, so a search may read it
     const int list_stride = max_set + 1;
-    uint32_t* ids_lds = lds32 + wave * (K * list_stride);
+    uint32_t* ids_lds = lds32 + wave * ((kCode ? 2 : 1) * K * list_stride);
+    uint32_t* code_lds = ids_lds + K * list_stride;  // same places as the ids (kCode only)
     const int64_t stride = (int64_t)gridDim.x * WPB;
     for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
         // the K blocks of this query (wave-uniform)
@@ -88,11 +92,47 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
                 x_first[j][e] = (uint32_t)__builtin_nontemporal_load(W + min(e * kWave + lane, n_key - 1));
         }
         int top[K];  // largest power of two <= n[j] (0 for an empty list): the first step
+        if constexpr (!kCode) {
+            // ids only: list after list (asking for all of them together was measured and is
+            // 5 % slower here, though it is what makes the variant with codes fast)
+#pragma unroll
+            for (int j = 0; j < K; ++j)
+                stage_words<8>(ids_lds + j * list_stride + 1,
+                               reinterpret_cast<const uint32_t*>(rpe_ids + lo[j]), n[j], lane);
+        }
+        // with codes: the lists' first 512 entries (all of them, usually) are asked for together,
+        // ids and codes of all K blocks, before any of them is waited for
+        constexpr int kStageU = 8;
+        constexpr int kLists = kCode ? 2 * K : 0;
+        uint32_t staged[kLists > 0 ? kLists : 1][kStageU];
+#pragma unroll
+        for (int l = 0; l < kLists; ++l) {
+            const int j = l % K;
+            const int32_t* from = (l < K ? rpe_ids : code) + lo[j];
+#pragma unroll
+            for (int u = 0; u < kStageU; ++u) {
+                const int t = u * kWave + lane;
+                staged[l][u] = t < n[j] ? (uint32_t)from[t] : 0u;
+            }
+        }
+#pragma unroll
+        for (int l = 0; l < kLists; ++l) {
+            const int j = l % K;
+            uint32_t* to = (l < K ? ids_lds : code_lds) + j * list_stride + 1;
+#pragma unroll
+            for (int u = 0; u < kStageU; ++u) {
+                const int t = u * kWave + lane;
+                if (t < n[j]) to[t] = staged[l][u];
+            }
+            if (n[j] > kStageU * kWave)  // the rest of a long list
+                stage_words<8>(to + kStageU * kWave,
+                               reinterpret_cast<const uint32_t*>((l < K ? rpe_ids : code) + lo[j]) +
+                                   kStageU * kWave,
+                               n[j] - kStageU * kWave, lane);
+        }
 #pragma unroll
         for (int j = 0; j < K; ++j) {
             if (lane == 0) ids_lds[j * list_stride] = 0xFFFFFFFFu;
-            stage_words<8>(ids_lds + j * list_stride + 1,
-                           reinterpret_cast<const uint32_t*>(rpe_ids + lo[j]), n[j], lane);
             top[j] = n[j] > 0 ? 1 << (31 - __builtin_clz((unsigned)n[j])) : 0;
         }
         int top_max = 0;
@@ -136,7 +176,12 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
                         const int p = pos[e][j2];
                         const uint32_t at = ids_lds[j2 * list_stride + 1 + min(p, max(n[j2] - 1, 0))];
                         const bool found = p < n[j2] && at == x[e];
-                        row[j2] = found ? (int32_t)(lo[j2] + p) : -1;
+                        if constexpr (kCode) {
+                            const uint32_t c = code_lds[j2 * list_stride + 1 + min(p, max(n[j2] - 1, 0))];
+                            row[j2] = found ? (int32_t)c : -1;
+                        } else {
+                            row[j2] = found ? (int32_t)(lo[j2] + p) : -1;
+                        }
                     }
                     if (t < n_key) {
                         // the K indices of an entry as one 4*K-byte store
@@ -152,14 +197,15 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
     }
 }
 
-template <int K, int WPB, int QE>
+template <int K, int WPB, int QE, bool kCode>
 static hipError_t launch_query_ids_kwe(hipStream_t stream, int n_cu, const int32_t* walks,
                                       const int64_t* rpe_off, const int32_t* rpe_ids,
+                                      const int32_t* code,
                                       int64_t n_blocks, int32_t M, int32_t m, int32_t max_set,
                                       int64_t table_rows, const int32_t* queries,
                                       int64_t n_queries, int32_t* out, uint32_t* err) {
-    const size_t lds_bytes = (size_t)WPB * K * (max_set + 1) * 4;
-    const void* fn = reinterpret_cast<const void*>(query_ids_kernel<K, WPB, QE>);
+    const size_t lds_bytes = (size_t)WPB * (kCode ? 2 : 1) * K * (max_set + 1) * 4;
+    const void* fn = reinterpret_cast<const void*>(query_ids_kernel<K, WPB, QE, kCode>);
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)lds_bytes);
@@ -171,22 +217,24 @@ static hipError_t launch_query_ids_kwe(hipStream_t stream, int n_cu, const int32
     if (per_cu < 1) return hipErrorInvalidValue;
     int64_t blocks = (n_queries + WPB - 1) / WPB;
     if (blocks > (int64_t)per_cu * n_cu) blocks = (int64_t)per_cu * n_cu;
-    hipLaunchKernelGGL((query_ids_kernel<K, WPB, QE>), dim3((unsigned)blocks), dim3(WPB * kWave),
-                       lds_bytes, stream, walks, rpe_off, rpe_ids, n_blocks, M * (m + 1), max_set,
+    hipLaunchKernelGGL((query_ids_kernel<K, WPB, QE, kCode>), dim3((unsigned)blocks),
+                       dim3(WPB * kWave), lds_bytes, stream, walks, rpe_off, rpe_ids, code, n_blocks,
+                       M * (m + 1), max_set,
                        table_rows, queries, n_queries, out, err);
     return hipGetLastError();
 }
 
-template <int K, int WPB>
+template <int K, int WPB, bool kCode>
 static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_t* walks,
                                       const int64_t* rpe_off, const int32_t* rpe_ids,
-                                      int64_t n_blocks, int32_t M, int32_t m, int32_t max_set,
-                                      int64_t table_rows, const int32_t* queries,
+                                      const int32_t* code, int64_t n_blocks, int32_t M, int32_t m,
+                                      int32_t max_set, int64_t table_rows, const int32_t* queries,
                                       int64_t n_queries, int32_t* out, uint32_t* err) {
     const int64_t n_key = (int64_t)M * (m + 1);
-#define SUREL_QI_ENTRIES(QE_)                                                                     \
-    return launch_query_ids_kwe<K, WPB, QE_>(stream, n_cu, walks, rpe_off, rpe_ids, n_blocks, M, \
-                                             m, max_set, table_rows, queries, n_queries, out, err)
+#define SUREL_QI_ENTRIES(QE_)                                                                  \
+    return launch_query_ids_kwe<K, WPB, QE_, kCode>(stream, n_cu, walks, rpe_off, rpe_ids, code, \
+                                                    n_blocks, M, m, max_set, table_rows, queries, \
+                                                    n_queries, out, err)
     if (n_key <= kWave) SUREL_QI_ENTRIES(1);
     if (n_key <= 2 * kWave) SUREL_QI_ENTRIES(2);
     if (n_key <= 4 * kWave) SUREL_QI_ENTRIES(4);
@@ -194,13 +242,14 @@ static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_
 #undef SUREL_QI_ENTRIES
 }
 
-template <int K>
+template <int K, bool kCode>
 static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int n_cu,
                                      const int32_t* walks, const int64_t* rpe_off,
-                                     const int32_t* rpe_ids, int64_t n_blocks, int32_t M, int32_t m,
+                                     const int32_t* rpe_ids, const int32_t* code, int64_t n_blocks,
+                                     int32_t M, int32_t m,
                                      int32_t max_set, int64_t table_rows, const int32_t* queries,
                                      int64_t n_queries, int32_t* out, uint32_t* err) {
-    const size_t per_wave = (size_t)K * (max_set + 1) * 4;
+    const size_t per_wave = (size_t)(kCode ? 2 : 1) * K * (max_set + 1) * 4;
     // waves per workgroup: the choice that lets a compute unit hold the most waves
     int best = 1, best_waves = 0;
     for (int w = 4; w >= 1; w /= 2) {
@@ -215,8 +264,9 @@ static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int 
     }
 #define SUREL_QI_CASE(W_)                                                                        \
     if (best == (W_))                                                                            \
-        return launch_query_ids_kw<K, W_>(stream, n_cu, walks, rpe_off, rpe_ids, n_blocks, M, m, \
-                                          max_set, table_rows, queries, n_queries, out, err);
+        return launch_query_ids_kw<K, W_, kCode>(stream, n_cu, walks, rpe_off, rpe_ids, code,   \
+                                                 n_blocks, M, m, max_set, table_rows, queries,  \
+                                                 n_queries, out, err);
     SUREL_QI_CASE(4)
     SUREL_QI_CASE(2)
     SUREL_QI_CASE(1)
@@ -225,17 +275,21 @@ static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int 
 }
 
 hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* walks,
-                            const int64_t* rpe_off, const int32_t* rpe_ids, int64_t n_blocks,
+                            const int64_t* rpe_off, const int32_t* rpe_ids, const int32_t* code,
+                            int64_t n_blocks,
                             int32_t M, int32_t m, int32_t max_set, int64_t table_rows,
                             const int32_t* queries, int64_t n_queries, int32_t k, int32_t* out,
                             uint32_t* err) {
     if (n_queries == 0) return hipSuccess;
-    if ((size_t)k * (max_set + 1) * 4 > (size_t)max_lds_bytes) return hipErrorInvalidValue;
+    if ((size_t)(code ? 2 : 1) * k * (max_set + 1) * 4 > (size_t)max_lds_bytes)
+        return hipErrorInvalidValue;
 #define SUREL_QI_ARGS \
-    stream, max_lds_bytes, n_cu, walks, rpe_off, rpe_ids, n_blocks, M, m, max_set, table_rows, \
-        queries, n_queries, out, err
-    if (k == 2) return launch_query_ids_k<2>(SUREL_QI_ARGS);
-    if (k == 3) return launch_query_ids_k<3>(SUREL_QI_ARGS);
+    stream, max_lds_bytes, n_cu, walks, rpe_off, rpe_ids, code, n_blocks, M, m, max_set, \
+        table_rows, queries, n_queries, out, err
+    if (k == 2 && !code) return launch_query_ids_k<2, false>(SUREL_QI_ARGS);
+    if (k == 3 && !code) return launch_query_ids_k<3, false>(SUREL_QI_ARGS);
+    if (k == 2) return launch_query_ids_k<2, true>(SUREL_QI_ARGS);
+    if (k == 3) return launch_query_ids_k<3, true>(SUREL_QI_ARGS);
 #undef SUREL_QI_ARGS
     return hipErrorInvalidValue;
 }

@@ -183,15 +183,16 @@ def test_sample_walks_rpe_argument_checks(lib, kw, want):
 
 
 def ids_args(**kw):
-    a = dict(ctx=NULL, walks=P, off=P, ids=P, n_blocks=100, table_rows=5000, M=50, m=4,
+    a = dict(ctx=NULL, walks=P, off=P, ids=P, code=NULL, n_blocks=100, table_rows=5000, M=50, m=4,
              max_set=201, queries=P, n_q=10, k=2, out=P)
     a.update(kw)
-    return [a[k] for k in ("ctx", "walks", "off", "ids", "n_blocks", "table_rows", "M", "m",
+    return [a[k] for k in ("ctx", "walks", "off", "ids", "code", "n_blocks", "table_rows", "M", "m",
                            "max_set", "queries", "n_q", "k", "out")]
 
 
 @pytest.mark.parametrize("kw,want", [
     (dict(), binding.E_CTX),
+    (dict(code=P), binding.E_CTX),
     (dict(M=0), binding.E_RANGE),
     (dict(m=16), binding.E_RANGE),
     (dict(k=1), binding.E_RANGE),

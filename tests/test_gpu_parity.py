@@ -95,6 +95,12 @@ def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
         assert ctx.check() == 0
         want = oracle.query_rpe_ids(w, table[0], table[1], queries)
         assert np.array_equal(got.cpu().numpy().astype(np.int64), want), "query RPE-IDs differ"
+        # the same as indices into the pruned array: the code of the row, -1 where there is none
+        got = binding.query_rpe_ids(ctx, f_walks, f_off, f_ids, dev(np.asarray(queries, np.int32)),
+                                    max_set=1 + M * m, code=code)
+        assert ctx.check() == 0
+        want_ids = np.where(want < 0, -1, want_code.astype(np.int64)[np.maximum(want, 0)])
+        assert np.array_equal(got.cpu().numpy().astype(np.int64), want_ids), "pruned RPE-IDs differ"
     return out
 
 
@@ -641,11 +647,20 @@ def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
     assert ranks == sorted(ranks)
     assert np.array_equal(np.asarray(ranks)[s_code], code[rows_d].cpu().numpy())
     print(f"[{name}] pruning ok: {T.shape[0]} distinct vectors for {R} rows", flush=True)
-    del T, code, code_l
+    del T, code_l
 
     # query-level RPE-IDs: the sampled queries against the oracle, invariants over all
     qids = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m)
     assert ctx.check() == 0
+    # the same call with the rows' codes: everywhere the code of the row it names without them
+    qcodes = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m, code=code)
+    assert ctx.check() == 0
+    for s in range(0, qids.shape[0], 1 << 16):
+        rows_part = qids[s:s + (1 << 16)].long()
+        want_part = torch.where(rows_part < 0, torch.full_like(rows_part, -1),
+                                code[rows_part.clamp(min=0)].long())
+        assert torch.equal(qcodes[s:s + (1 << 16)].long(), want_part), "pruned RPE-IDs differ"
+    del qcodes, code
     sub_w = oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m, wl.rng_seed)
     w_ids = oracle.query_rpe_ids(sub_w, sub_table[0], sub_table[1], local)
     # the oracle's rows index the sub-table; turn both sides into (block, row inside block)
