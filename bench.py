@@ -128,6 +128,10 @@ def main() -> int:
     ap.add_argument("--prune", action="store_true",
                     help="also time surel_prune_rpe (Sec. 3.3: distinct count vectors stored once) "
                          "after the timed region; reported under 'prune_rpe', not part of 'value'")
+    ap.add_argument("--join-ids", action="store_true",
+                    help="also time surel_join_query_ids (the union join over RPE-IDs into the "
+                         "pruned array instead of count vectors) after the timed region; reported "
+                         "under 'join_query_ids', not part of 'value'")
     ap.add_argument("--batches", action="store_true",
                     help="also time surel_query_incidence + surel_bfs_batches (Sec. 3.6: mini-batches "
                          "of queries that share nodes) after the timed region, and the join over "
@@ -359,6 +363,30 @@ def main() -> int:
             "algorithmic_bytes": p_bytes,
             "hbm_frac": round(p_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del T, code
+    if args.join_ids:
+        cap_T = 1 << 20
+        T = torch.empty((cap_T, L), dtype=torch.uint16, device="cuda")
+        code = torch.empty(R, dtype=torch.int32, device="cuda")
+        rc, n_T = binding.prune_rpe_raw(ctx, rpe_cnt[:R], cap_T, T, code)
+        assert rc == binding.OK, rc
+        j_codes = torch.empty((J, k), dtype=torch.int32, device="cuda")
+        rc, rows = binding.join_query_ids_raw(ctx, rpe_off, rpe_ids, code, d_q, max_set, J, join_off,
+                                              join_ids, j_codes)
+        assert rc == binding.OK and rows == J
+        ctx.profile(True)
+        for _ in range(args.steps):
+            binding.join_query_ids_raw(ctx, rpe_off, rpe_ids, code, d_q, max_set, J, join_off,
+                                       join_ids, j_codes)
+        pr = ctx.profile_read()
+        ctx.profile(False)
+        assert ctx.check() == 0
+        ms = (pr["join_count"][0] + pr["join_fill"][0] + pr["scan"][0]) / args.steps
+        i_bytes = in_rows * 8 + J * (4 + 4 * k)            # ids + codes read, ids + k codes written
+        out["join_query_ids"] = {
+            "ms": round(ms, 4), "joined_rows_per_s": J / (ms * 1e-3), "algorithmic_bytes": i_bytes,
+            "hbm_frac": round(i_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "join_over_counts_ms": round(stage_ms["join"], 4)}
+        del T, code, j_codes
     if args.batches:
         B2 = args.batch_size
         B1 = args.batch_nodes or B2 * k   # default: the batch size is the limit that binds

@@ -11,8 +11,9 @@
  *                        node x of it the query-level RPE X_{Q,x} = [X_{u,x}]_{u in Q},
  *                        zeros where x is not in V_u (Sec. 3.4, set-union form).
  * Beside them: surel_sample_walks_rpe (the first two in one kernel), surel_query_rpe_ids
- * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values) and
- * surel_prune_rpe (Sec. 3.3: the distinct count vectors stored once, rows re-indexed), and
+ * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values),
+ * surel_prune_rpe (Sec. 3.3: the distinct count vectors stored once, rows re-indexed),
+ * surel_join_query_ids (the union join over those RPE-IDs), and
  * surel_query_incidence + surel_bfs_batches (Sec. 3.6 "Mini-batching for Training";
  * Algorithm 2: mini-batches of queries that share nodes, by breadth-first search).
  *
@@ -206,6 +207,21 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                        int32_t k, int64_t cap_rows, int64_t* d_join_off,
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
+
+/* surel_join_queries with RPE-IDs instead of RPE values (Sec. 3.3: "the table carries RPE-IDs";
+ * Sec. 3.4's closing remarks on shipping IDs instead of values): the same union rows, and for
+ * every row and tuple member the code of the member's table row for that node, i.e. its index
+ * in the pruned array T of surel_prune_rpe, or -1 where the member's set does not hold the
+ * node (the all-zero vector).  12 bytes a row for pairs instead of 24 at m = 4.
+ *   d_code       int32[table rows] (device, read-only): the codes surel_prune_rpe wrote.
+ *   d_join_codes int32[cap_rows][k] (device, written; may be NULL together with d_join_ids).
+ *   everything else as in surel_join_queries (whose row layout and d_join_off this call
+ *   reproduces exactly).  Device-detected: as surel_join_queries. */
+int surel_join_query_ids(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                         const int32_t* d_code, int64_t n_blocks, int32_t max_set,
+                         const int32_t* d_queries, int64_t n_queries, int32_t k, int64_t cap_rows,
+                         int64_t* d_join_off, int32_t* d_join_ids, int32_t* d_join_codes,
+                         int64_t* h_rows);
 
 /* Sec. 3.4, the per-walk-position form: the walks of a query's blocks are concatenated, and
  * every node occurrence x in them gets its query-level RPE-ID, the tuple of the RPE table's row

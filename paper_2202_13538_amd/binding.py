@@ -48,6 +48,8 @@ SIGNATURES = {
                                               ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "surel_join_query_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _i64,
+                                            _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_query_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i32, _i32,
                                            _vp, _i64, _i32, _vp]),
     "surel_prune_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i64, _vp, _vp,
@@ -303,6 +305,41 @@ def join_queries(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
     if rc != OK:
         raise SurelError(rc, "surel_join_queries")
     return off, ids[:rows], cnt[:rows]
+
+
+def join_query_ids_raw(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
+                       code: torch.Tensor, queries: torch.Tensor, max_set: int, cap_rows: int,
+                       join_off: torch.Tensor, join_ids: torch.Tensor | None,
+                       join_codes: torch.Tensor | None, want_rows: bool = True):
+    """One call of surel_join_query_ids into caller buffers.  Returns (status, rows or None)."""
+    n_q, k = queries.shape
+    rows = _i64(-1)
+    rc = load().surel_join_query_ids(
+        ctx.handle, _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(code, torch.int32, "code"), rpe_off.numel() - 1, max_set,
+        _ptr(queries, torch.int32, "queries"), n_q, k, cap_rows,
+        _ptr(join_off, torch.int64, "join_off"), _ptr(join_ids, torch.int32, "join_ids"),
+        _ptr(join_codes, torch.int32, "join_codes"), ctypes.byref(rows) if want_rows else None)
+    return rc, (rows.value if want_rows else None)
+
+
+def join_query_ids(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor, code: torch.Tensor,
+                   queries: torch.Tensor, max_set: int):
+    """(join_off int64[n_q+1], join_ids int32[J], join_codes int32[J][k]) on the GPU: the union
+    join with the rows' codes (indices into the pruned array T, -1 = absent) instead of counts."""
+    n_q, k = queries.shape
+    dev = queries.device
+    off = torch.empty(n_q + 1, dtype=torch.int64, device=dev)
+    rc, rows = join_query_ids_raw(ctx, rpe_off, rpe_ids, code, queries, max_set, 0, off, None, None)
+    if rc != OK:
+        raise SurelError(rc, "surel_join_query_ids")
+    ids = torch.empty(rows, dtype=torch.int32, device=dev)
+    codes = torch.empty((rows, k), dtype=torch.int32, device=dev)
+    rc, rows2 = join_query_ids_raw(ctx, rpe_off, rpe_ids, code, queries, max_set, rows, off, ids,
+                                   codes)
+    if rc != OK:
+        raise SurelError(rc, "surel_join_query_ids")
+    return off, ids, codes
 
 
 def query_rpe_ids(ctx: Context, walks: torch.Tensor, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,

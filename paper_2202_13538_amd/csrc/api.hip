@@ -379,11 +379,13 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
     return SUREL_OK;
 }
 
-int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
-                       const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m,
-                       int32_t max_set, const int32_t* d_queries, int64_t n_queries,
-                       int32_t k, int64_t cap_rows, int64_t* d_join_off,
-                       int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows) {
+// The join over vectors of m+1 16-bit entries per table row; absent16 fills the vector of a
+// list that has no row for a node (0 for counts; 0xFFFF for 32-bit codes seen as two halves).
+static int join_vectors(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                        const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+                        const int32_t* d_queries, int64_t n_queries, int32_t k, int64_t cap_rows,
+                        int64_t* d_join_off, int32_t* d_join_ids, uint16_t* d_join_cnt,
+                        uint16_t absent16, int64_t* h_rows) {
     if (m < 1 || m > SUREL_MAX_STEPS) return SUREL_E_RANGE;
     if (k < 2 || k > SUREL_MAX_TUPLE) return SUREL_E_RANGE;
     if (max_set < 1 || max_set > SUREL_MAX_SET) return SUREL_E_RANGE;
@@ -406,7 +408,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
         KernelSpan span(ctx, SUREL_K_JOIN_COUNT);
         hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off, d_rpe_ids, d_rpe_cnt,
                                  n_blocks, m, max_set, d_queries, n_queries, k, counts, nullptr, 0,
-                                 nullptr, nullptr, ctx->d_err);
+                                 nullptr, nullptr, absent16, ctx->d_err);
     }
     if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
     if (hrc != hipSuccess) return SUREL_E_HIP;
@@ -419,7 +421,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
         KernelSpan span(ctx, SUREL_K_JOIN_FILL);
         hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off, d_rpe_ids, d_rpe_cnt,
                                  n_blocks, m, max_set, d_queries, n_queries, k, nullptr, d_join_off,
-                                 cap_rows, d_join_ids, d_join_cnt, ctx->d_err);
+                                 cap_rows, d_join_ids, d_join_cnt, absent16, ctx->d_err);
         if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
         if (hrc != hipSuccess) return SUREL_E_HIP;
     }
@@ -428,6 +430,26 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
         if (d_join_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
     }
     return SUREL_OK;
+}
+
+int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                       const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m,
+                       int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                       int32_t k, int64_t cap_rows, int64_t* d_join_off,
+                       int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows) {
+    return join_vectors(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
+                        n_queries, k, cap_rows, d_join_off, d_join_ids, d_join_cnt, 0, h_rows);
+}
+
+int surel_join_query_ids(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                         const int32_t* d_code, int64_t n_blocks, int32_t max_set,
+                         const int32_t* d_queries, int64_t n_queries, int32_t k, int64_t cap_rows,
+                         int64_t* d_join_off, int32_t* d_join_ids, int32_t* d_join_codes,
+                         int64_t* h_rows) {
+    // a 32-bit code is a vector of two 16-bit entries; absent = 0xFFFF 0xFFFF = -1
+    return join_vectors(ctx, d_rpe_off, d_rpe_ids, reinterpret_cast<const uint16_t*>(d_code),
+                        n_blocks, 1, max_set, d_queries, n_queries, k, cap_rows, d_join_off,
+                        d_join_ids, reinterpret_cast<uint16_t*>(d_join_codes), 0xFFFFu, h_rows);
 }
 
 int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d_rpe_off,

@@ -234,12 +234,12 @@ __device__ __forceinline__ void copy_vector(uint16_t* dst, const uint16_t* from,
     }
 }
 template <int LT>
-__device__ __forceinline__ void zero_vector(uint16_t* dst, int L) {
+__device__ __forceinline__ void fill_vector(uint16_t* dst, int L, uint16_t value) {
     if constexpr (LT > 0) {
 #pragma unroll
-        for (int s = 0; s < LT; ++s) dst[s] = 0;
+        for (int s = 0; s < LT; ++s) dst[s] = value;
     } else {
-        for (int s = 0; s < L; ++s) dst[s] = 0;
+        for (int s = 0; s < L; ++s) dst[s] = value;
     }
 }
 
@@ -252,7 +252,8 @@ __device__ __forceinline__ void join_one_query(
     const int32_t* __restrict__ rpe_ids, const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks,
     int32_t m, int32_t max_set, const int32_t* __restrict__ queries,
     int32_t* __restrict__ counts, const int64_t* __restrict__ join_off, int64_t cap_rows,
-    int32_t* __restrict__ out_ids, uint16_t* __restrict__ out_cnt, uint32_t* __restrict__ err) {
+    int32_t* __restrict__ out_ids, uint16_t* __restrict__ out_cnt, uint16_t absent16,
+    uint32_t* __restrict__ err) {
 
     const int L = LT > 0 ? LT : m + 1;
     const JoinLds lay = join_lds_layout(K, max_set, L, kFill, join_uses_tile(K, LT));
@@ -377,7 +378,7 @@ __device__ __forceinline__ void join_one_query(
                         const uint32_t word = __builtin_amdgcn_alignbyte(
                             raw[g][j][e / 2 + 1], raw[g][j][e / 2], shift[g][j]);
                         const uint32_t c = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
-                        v[j * LT + e] = present[g][j] ? (uint16_t)c : (uint16_t)0;
+                        v[j * LT + e] = present[g][j] ? (uint16_t)c : absent16;
                     }
                 }
                 const int r = r0 + g * kWave + lane;
@@ -448,7 +449,7 @@ __device__ __forceinline__ void join_one_query(
             if ((int)sj < len) {
                 copy_vector<LT>(dst, rpe_cnt + (first + sj) * L, L);
             } else {
-                zero_vector<LT>(dst, L);
+                fill_vector<LT>(dst, L, absent16);
             }
         }
         wave_sync();
@@ -481,7 +482,7 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
     const int32_t* __restrict__ queries, int64_t n_queries, int32_t* __restrict__ counts,
     const int64_t* __restrict__ join_off, int64_t cap_rows, int32_t* __restrict__ out_ids,
-    uint16_t* __restrict__ out_cnt, uint32_t* __restrict__ err) {
+    uint16_t* __restrict__ out_cnt, uint16_t absent16, uint32_t* __restrict__ err) {
     extern __shared__ uint32_t lds32[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
         join_one_query<K, WPB, kFill, LT>(lds32, lane, wave, q, rpe_off, rpe_ids, rpe_cnt, n_blocks,
                                           m, max_set, queries, counts, join_off, cap_rows, out_ids,
-                                          out_cnt, err);
+                                          out_cnt, absent16, err);
         wave_sync();  // the next query reuses the LDS words
     }
 }
@@ -498,10 +499,10 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     hipStream_t stream, int n_cu, const int64_t *rpe_off, const int32_t *rpe_ids, const uint16_t *rpe_cnt,  \
         int64_t n_blocks, int32_t m, int32_t max_set, const int32_t *queries, int64_t n_queries,  \
         int32_t *counts, const int64_t *join_off, int64_t cap_rows, int32_t *out_ids,             \
-        uint16_t *out_cnt, uint32_t *err
+        uint16_t *out_cnt, uint16_t absent16, uint32_t *err
 #define SUREL_JOIN_ARGS                                                                          \
     stream, n_cu, rpe_off, rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off, \
-        cap_rows, out_ids, out_cnt, err
+        cap_rows, out_ids, out_cnt, absent16, err
 
 template <int K, int WPB, bool kFill, int LT>
 static hipError_t launch_join_cfg(SUREL_JOIN_PARAMS) {
@@ -524,7 +525,7 @@ static hipError_t launch_join_cfg(SUREL_JOIN_PARAMS) {
     const dim3 grid((unsigned)blocks), block(WPB * kWave);
     hipLaunchKernelGGL((join_kernel<K, WPB, kFill, LT>), grid, block, lds_bytes, stream, rpe_off,
                        rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off,
-                       cap_rows, out_ids, out_cnt, err);
+                       cap_rows, out_ids, out_cnt, absent16, err);
     return hipGetLastError();
 }
 
@@ -532,6 +533,7 @@ template <int K, int WPB, bool kFill>
 static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
     if (kFill && m + 1 == 5) return launch_join_cfg<K, WPB, kFill, 5>(SUREL_JOIN_ARGS);
     if (kFill && m + 1 == 4) return launch_join_cfg<K, WPB, kFill, 4>(SUREL_JOIN_ARGS);
+    if (kFill && m + 1 == 2) return launch_join_cfg<K, WPB, kFill, 2>(SUREL_JOIN_ARGS);
     return launch_join_cfg<K, WPB, kFill, 0>(SUREL_JOIN_ARGS);
 }
 
@@ -539,7 +541,7 @@ static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
 template <int K>
 static hipError_t launch_join_k(int max_lds_bytes, SUREL_JOIN_PARAMS) {
     const bool fill = counts == nullptr;
-    const int LT = (fill && (m + 1 == 5 || m + 1 == 4)) ? m + 1 : 0;  // as launch_join_kwf picks
+    const int LT = (fill && (m + 1 == 5 || m + 1 == 4 || m + 1 == 2)) ? m + 1 : 0;  // as launch_join_kwf picks
     const size_t per_wave =
         (size_t)join_lds_layout(K, max_set, m + 1, fill, join_uses_tile(K, LT)).total * 4;
 #define SUREL_JOIN_CASE(W_)                                                \
@@ -558,7 +560,7 @@ hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const in
                        const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                        int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
                        int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
-                       int32_t* out_ids, uint16_t* out_cnt, uint32_t* err) {
+                       int32_t* out_ids, uint16_t* out_cnt, uint16_t absent16, uint32_t* err) {
     if (n_queries == 0) return hipSuccess;
     if (k == 2) return launch_join_k<2>(max_lds_bytes, SUREL_JOIN_ARGS);
     if (k == 3) return launch_join_k<3>(max_lds_bytes, SUREL_JOIN_ARGS);

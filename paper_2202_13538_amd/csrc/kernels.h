@@ -46,12 +46,13 @@ hipError_t launch_rpe_fill(hipStream_t stream, int max_lds_bytes, const int32_t*
                            uint32_t* err);
 
 // join.hip.  counts != nullptr: counting launch (counts[q] = union rows of query q);
-// counts == nullptr: writing launch at join_off[q].
+// counts == nullptr: writing launch at join_off[q].  absent16: what the entries of a vector
+// hold where a list has no row for the node (0 for counts).
 hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
                        const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                        int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
                        int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
-                       int32_t* out_ids, uint16_t* out_cnt, uint32_t* err);
+                       int32_t* out_ids, uint16_t* out_cnt, uint16_t absent16, uint32_t* err);
 
 // query_ids.hip.  out int32[n_queries][k][M][m+1][k]: for every entry of the walk blocks of a
 // query's k table blocks, the table rows that hold its node in each of the k blocks (-1 where

@@ -182,6 +182,34 @@ def test_sample_walks_rpe_argument_checks(lib, kw, want):
     assert lib.surel_sample_walks_rpe(*fused_args(**kw)) == want
 
 
+def join_ids_args(**kw):
+    a = dict(ctx=NULL, off=P, ids=P, code=P, n_blocks=100, max_set=201, queries=P, n_q=10, k=2,
+             cap_rows=1000, joff=P, jids=P, jcodes=P, h_rows=NULL)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "off", "ids", "code", "n_blocks", "max_set", "queries", "n_q", "k",
+                           "cap_rows", "joff", "jids", "jcodes", "h_rows")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(k=3), binding.E_CTX),
+    (dict(k=1), binding.E_RANGE),
+    (dict(max_set=0), binding.E_RANGE),
+    (dict(max_set=binding.MAX_SET + 1), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(joff=NULL), binding.E_NULL),
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(code=NULL), binding.E_NULL),
+    (dict(jids=NULL), binding.E_NULL),
+    (dict(jcodes=NULL), binding.E_NULL),
+    (dict(jids=NULL, jcodes=NULL, code=NULL), binding.E_CTX),
+])
+def test_join_query_ids_argument_checks(lib, kw, want):
+    assert lib.surel_join_query_ids(*join_ids_args(**kw)) == want
+
+
 def ids_args(**kw):
     a = dict(ctx=NULL, walks=P, off=P, ids=P, code=NULL, n_blocks=100, table_rows=5000, M=50, m=4,
              max_set=201, queries=P, n_q=10, k=2, out=P)

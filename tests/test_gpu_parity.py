@@ -101,6 +101,18 @@ def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
         assert ctx.check() == 0
         want_ids = np.where(want < 0, -1, want_code.astype(np.int64)[np.maximum(want, 0)])
         assert np.array_equal(got.cpu().numpy().astype(np.int64), want_ids), "pruned RPE-IDs differ"
+        # the union join over the codes: the same rows, every count vector replaced by its index
+        # in the oracle's pruned array (-1 for the all-zero vector of an absent node)
+        j_off, j_ids, j_codes = binding.join_query_ids(ctx, f_off, f_ids, code,
+                                                       dev(np.asarray(queries, np.int32)),
+                                                       max_set=1 + M * m)
+        assert ctx.check() == 0
+        index_of = {tuple(v): i for i, v in enumerate(want_T.tolist())}
+        want_codes = np.array([[index_of.get(tuple(vec), -1) if any(vec) else -1 for vec in row]
+                               for row in joined[2].tolist()], dtype=np.int32).reshape(-1, len(queries[0]))
+        assert np.array_equal(j_off.cpu().numpy(), joined[0]), "join offsets differ (ids form)"
+        assert np.array_equal(j_ids.cpu().numpy(), joined[1]), "join ids differ (ids form)"
+        assert np.array_equal(j_codes.cpu().numpy(), want_codes), "joined RPE-IDs differ"
     return out
 
 
@@ -647,7 +659,20 @@ def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
     assert ranks == sorted(ranks)
     assert np.array_equal(np.asarray(ranks)[s_code], code[rows_d].cpu().numpy())
     print(f"[{name}] pruning ok: {T.shape[0]} distinct vectors for {R} rows", flush=True)
-    del T, code_l
+    del code_l
+    # the union join over the codes: same offsets and ids as the join over counts, and every code
+    # names, in T, the count vector that the join over counts holds there (-1 <-> all zeros)
+    i_off, i_ids, i_codes = binding.join_query_ids(ctx, off, ids, code, d_q, max_set=1 + M * m)
+    assert ctx.check() == 0
+    assert torch.equal(i_off, joff) and torch.equal(i_ids, jids), "ids form: rows differ"
+    T_ext = torch.cat([T.view(torch.int16), torch.zeros((1, L), dtype=torch.int16, device="cuda")])
+    for s in range(0, J, 1 << 25):
+        e = min(J, s + (1 << 25))
+        c = i_codes[s:e].long()
+        c = torch.where(c < 0, torch.full_like(c, T.shape[0]), c)        # -1 -> the zero row
+        assert torch.equal(T_ext[c], jcnt.view(torch.int16)[s:e]), "ids form: a code names another vector"
+    del i_off, i_ids, i_codes, T, T_ext
+    print(f"[{name}] join over RPE-IDs ok", flush=True)
 
     # query-level RPE-IDs: the sampled queries against the oracle, invariants over all
     qids = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m)
