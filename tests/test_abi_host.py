@@ -395,3 +395,26 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
                     "-I", os.path.dirname(HEADER), str(src), "-o", str(exe),
                     "-L", lib_dir, "-lsurel", f"-Wl,-rpath,{lib_dir}", "-Wl,--allow-shlib-undefined"],
                    check=True)
+
+
+def test_the_product_never_reaches_for_the_oracle():
+    """Only tests, smoke() and the benchmark's cpu_baseline leg may use oracle/: no file of the
+    package names it, the benchmark imports it inside cpu_baseline only, and the oracle imports
+    nothing of the package."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2202_13538_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath or "__pycache__" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".c", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f"{f} imports the oracle"
+                assert "surel_oracle" not in text and "oracle_" not in text, f"{f} names oracle code"
+    bench = open(os.path.join(root, "bench.py")).read()
+    assert bench.count("import oracle") == 1
+    start = bench.index("def cpu_baseline")
+    assert start < bench.index("import oracle") < bench.index("def main")
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith((".py", ".c")):
+            assert "paper_2202_13538_amd" not in open(os.path.join(root, "oracle", f)).read()
