@@ -534,6 +534,8 @@ static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
     if (kFill && m + 1 == 5) return launch_join_cfg<K, WPB, kFill, 5>(SUREL_JOIN_ARGS);
     if (kFill && m + 1 == 4) return launch_join_cfg<K, WPB, kFill, 4>(SUREL_JOIN_ARGS);
     if (kFill && m + 1 == 2) return launch_join_cfg<K, WPB, kFill, 2>(SUREL_JOIN_ARGS);
+    if (kFill && m + 1 == 3) return launch_join_cfg<K, WPB, kFill, 3>(SUREL_JOIN_ARGS);
+    if (kFill && m + 1 == 6) return launch_join_cfg<K, WPB, kFill, 6>(SUREL_JOIN_ARGS);
     return launch_join_cfg<K, WPB, kFill, 0>(SUREL_JOIN_ARGS);
 }
 
@@ -541,7 +543,7 @@ static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
 template <int K>
 static hipError_t launch_join_k(int max_lds_bytes, SUREL_JOIN_PARAMS) {
     const bool fill = counts == nullptr;
-    const int LT = (fill && (m + 1 == 5 || m + 1 == 4 || m + 1 == 2)) ? m + 1 : 0;  // as launch_join_kwf picks
+    const int LT = (fill && m + 1 >= 2 && m + 1 <= 6) ? m + 1 : 0;  // as launch_join_kwf picks
     const size_t per_wave =
         (size_t)join_lds_layout(K, max_set, m + 1, fill, join_uses_tile(K, LT)).total * 4;
 #define SUREL_JOIN_CASE(W_)                                                \
