@@ -14,11 +14,12 @@
 //   - triples: ranks.  A row is owned by the first list that holds its node; its position is
 //     #{a in list 0 : a < x} + sum over j >= 1 of #{b in list j : b < x, b in no earlier list},
 //     each term a lower bound in LDS plus a lookup in a prefix count of "new" elements.
-// Count vectors.  For the common walk lengths (m + 1 = 4 or 5 counts per vector) a lane takes
+// Count vectors.  For the usual walk lengths (m + 1 = 2 .. 6 entries per vector) a lane takes
 // one union row: it gathers the row's K vectors from the table (zeros where the node is
 // absent), packs them into the row's K*L/2 words in registers, and the row goes out either
 // straight from the registers (vectors of whole words) or through a small LDS tile that is
-// streamed out as whole words (pairs of 5-count vectors, whose rows straddle words).  Other
+// streamed out as whole words (pairs of vectors with an odd number of entries, whose rows
+// straddle words).  Other
 // shapes take a generic path: a lane moves one (row, list) vector into an LDS tile laid out
 // like the output.  The kernel keeps its LDS footprint small on purpose: the vectors are read
 // in place, and it is the number of waves in flight that hides the latency.
@@ -245,7 +246,7 @@ __device__ __forceinline__ void fill_vector(uint16_t* dst, int L, uint16_t value
 
 // K = tuple size, WPB = waves per workgroup (as many as the LDS a wave needs allows),
 // kFill = false: write counts[q] only; kFill = true: join_off is complete, write the rows.
-// LT = m+1 at compile time for the common walk lengths, 0 = any.
+// LT = m+1 at compile time for the usual walk lengths (2 .. 6), 0 = any.
 template <int K, int WPB, bool kFill, int LT>
 __device__ __forceinline__ void join_one_query(
     uint32_t* lds32, int lane, int wave, int64_t q, const int64_t* __restrict__ rpe_off,
