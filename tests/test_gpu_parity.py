@@ -1,9 +1,8 @@
 """Parity of the HIP path with the CPU oracle, through the C ABI, on a real MI355X.
 
-Bit-exact comparison of walks, RPE tables and joins: element by element on small and
-medium inputs (several tiles, ragged tails, the degenerate cases), and at the full workload
-sizes on sampled seeds / queries that the oracle computes one by one plus invariants that
-hold at any size.
+Bit-exact comparison of walks, RPE tables and joins, element by element, on small and
+medium inputs (several tiles, ragged tails, the degenerate cases) and of the device-detected
+problems.  The workloads at their full sizes are in test_gpu_full_size.py.
 """
 import os
 
@@ -535,252 +534,3 @@ def test_join_problems_are_flagged(ctx):
     assert ctx.check() == binding.DEV_CAPACITY
     assert np.array_equal(jids.cpu().numpy()[:cap], want[1][:cap])
     assert (jids.cpu().numpy()[cap:] == -7).all()
-
-
-# --------------------------------------------------------------------------- #
-# full workload sizes: sampled blocks against the oracle + invariants at any size
-# --------------------------------------------------------------------------- #
-def segment_sums(flat_u16, off, chunk=1 << 24):
-    """Per-segment column sums of a uint16 [rows][cols] tensor, segments given by ``off``."""
-    n_seg = off.numel() - 1
-    rows, cols = flat_u16.shape
-    sizes = off[1:] - off[:-1]
-    seg_of_row = torch.repeat_interleave(torch.arange(n_seg, device=off.device), sizes)
-    sums = torch.zeros((n_seg, cols), dtype=torch.int64, device=off.device)
-    as_i16 = flat_u16.view(torch.int16)
-    for s in range(0, rows, chunk):
-        e = min(rows, s + chunk)
-        sums.index_add_(0, seg_of_row[s:e], as_i16[s:e].to(torch.int64) & 0xFFFF)
-    return sums
-
-
-def rows_u16(t, rows_d):
-    """Selected rows of a uint16 device tensor as a host uint16 array."""
-    return t.view(torch.int16)[rows_d].cpu().numpy().view(np.uint16)
-
-
-def check_workload(ctx, name, n_sample_seeds=1500, n_sample_queries=600):
-    wl = synth.WORKLOADS[name]
-    rp, ci = synth.make_graph(wl)
-    queries = synth.make_queries(wl, rp, ci)
-    N, M, m, k = wl.n_nodes, wl.M, wl.m, wl.k
-    L = m + 1
-    d_rp, d_ci = dev(rp), dev(ci)
-    d_seeds = torch.arange(N, dtype=torch.int32, device="cuda")
-    print(f"[{name}] graph ready: N={N} E2={ci.size} M={M} m={m} queries={queries.shape}",
-          flush=True)
-
-    sizes = torch.empty(N, dtype=torch.int32, device="cuda")
-    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, set_sizes=sizes)
-    off, ids, cnt = binding.build_rpe(ctx, walks, N, cap_rows=binding.rpe_rows_bound(N, M, m),
-                                      set_sizes=sizes)
-    assert ctx.check() == 0
-    # the RPE builder's own counting pass gives the same layout
-    off2 = torch.empty_like(off)
-    rc, rows2 = binding.build_rpe_raw(ctx, walks, N, 0, off2, None, None)
-    assert rc == binding.OK and torch.equal(off, off2) and rows2 == int(off[-1])
-    R = int(off[-1])
-    print(f"[{name}] walks + rpe done: R={R} rows", flush=True)
-    # the fused kernel, whole output against the two-call path
-    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, d_seeds, M, m,
-                                                            wl.rng_seed)
-    assert ctx.check() == 0
-    assert torch.equal(f_walks, walks), "fused: walks differ"
-    assert torch.equal(f_off, off), "fused: offsets differ"
-    assert torch.equal(f_ids, ids[:R]), "fused: ids differ"
-    assert torch.equal(f_cnt.view(torch.int16), cnt[:R].view(torch.int16)), "fused: counts differ"
-    del f_walks, f_off, f_ids, f_cnt
-    print(f"[{name}] fused walk+rpe equals the two-call path", flush=True)
-
-    rng = np.random.default_rng(12345)
-    deg = np.diff(rp)
-    pick = np.unique(np.concatenate([
-        [0, 1, N - 2, N - 1], rng.integers(0, N, size=n_sample_seeds),
-        np.argsort(deg)[-8:], np.nonzero(deg == 0)[0][:8]])).astype(np.int32)
-    w_or = oracle.sample_walks(rp, ci, pick, M, m, wl.rng_seed)
-    assert np.array_equal(walks[torch.from_numpy(pick).long().cuda()].cpu().numpy(), w_or), \
-        "sampled walks differ"
-    t_off, t_ids, t_cnt = oracle.build_rpe(w_or)
-    off_h = off.cpu().numpy()
-    assert np.array_equal(off_h[pick + 1] - off_h[pick], np.diff(t_off)), "block sizes differ"
-    rows = np.concatenate([np.arange(off_h[u], off_h[u + 1]) for u in pick])
-    rows_d = torch.from_numpy(rows).cuda()
-    assert np.array_equal(ids[rows_d].cpu().numpy(), t_ids), "sampled rpe ids differ"
-    assert np.array_equal(rows_u16(cnt, rows_d), t_cnt), "sampled rpe counts differ"
-
-    # invariants over the whole table
-    assert int(off[0]) == 0 and bool((off[1:] > off[:-1]).all())
-    assert bool((segment_sums(cnt, off) == M).all()), "a step's counts do not sum to M"
-    inner = torch.ones(R, dtype=torch.bool, device="cuda")
-    inner[off[:-1]] = False                                  # first row of every block
-    assert bool((ids[1:] > ids[:-1])[inner[1:]].all()), "ids not ascending inside a block"
-    slot0 = cnt.view(torch.int16)[:, 0].to(torch.int32) & 0xFFFF
-    assert int((slot0 > 0).sum()) == N and bool((slot0[slot0 > 0] == M).all())
-    del inner, slot0
-    print(f"[{name}] rpe parity + invariants ok", flush=True)
-
-    d_q = dev(queries)
-    joff, jids, jcnt = binding.join_queries(ctx, off, ids, cnt, d_q, max_set=1 + M * m)
-    assert ctx.check() == 0
-    J = int(joff[-1])
-    print(f"[{name}] join done: J={J} rows", flush=True)
-    qpick = np.unique(np.concatenate([[0, wl.n_queries - 1],
-                                      rng.integers(0, wl.n_queries, size=n_sample_queries)]))
-    sub_q = queries[qpick]
-    nodes, local = np.unique(sub_q, return_inverse=True)
-    local = local.reshape(sub_q.shape).astype(np.int32)
-    sub_table = oracle.build_rpe(oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m,
-                                                     wl.rng_seed))
-    w_joff, w_jids, w_jcnt = oracle.join_queries(*sub_table, local)
-    joff_h = joff.cpu().numpy()
-    assert np.array_equal(joff_h[qpick + 1] - joff_h[qpick], np.diff(w_joff)), "join sizes differ"
-    jrows = torch.from_numpy(np.concatenate(
-        [np.arange(joff_h[q], joff_h[q + 1]) for q in qpick])).cuda()
-    assert np.array_equal(jids[jrows].cpu().numpy(), w_jids), "sampled join ids differ"
-    assert np.array_equal(rows_u16(jcnt, jrows), w_jcnt), "sampled join counts differ"
-
-    # pruning: T is strictly ascending, every row finds its vector through its code, every entry
-    # of T is used, and on the sampled blocks the oracle's distinct vectors are all in T with
-    # the same order; together that is the sorted set of distinct vectors, which is unique
-    T, code = binding.prune_rpe(ctx, cnt[:R])
-    assert ctx.check() == 0
-    T_h = host_u16(T)
-    as_tuples = [tuple(r) for r in T_h.tolist()]
-    assert all(a < b for a, b in zip(as_tuples, as_tuples[1:])), "T is not strictly ascending"
-    code_l = code.long()
-    for s in range(0, R, 1 << 26):
-        e = min(R, s + (1 << 26))
-        assert torch.equal(T.view(torch.int16)[code_l[s:e]], cnt.view(torch.int16)[s:e]), \
-            "a row's code does not name its vector"
-    assert int(torch.bincount(code_l, minlength=T.shape[0]).min()) > 0, "unused entry in T"
-    s_T, s_code = oracle.prune_rpe(t_cnt)
-    pos = {v: i for i, v in enumerate(as_tuples)}
-    ranks = [pos[tuple(r)] for r in s_T.tolist()]
-    assert ranks == sorted(ranks)
-    assert np.array_equal(np.asarray(ranks)[s_code], code[rows_d].cpu().numpy())
-    print(f"[{name}] pruning ok: {T.shape[0]} distinct vectors for {R} rows", flush=True)
-    del code_l
-    # the union join over the codes: same offsets and ids as the join over counts, and every code
-    # names, in T, the count vector that the join over counts holds there (-1 <-> all zeros)
-    i_off, i_ids, i_codes = binding.join_query_ids(ctx, off, ids, code, d_q, max_set=1 + M * m)
-    assert ctx.check() == 0
-    assert torch.equal(i_off, joff) and torch.equal(i_ids, jids), "ids form: rows differ"
-    T_ext = torch.cat([T.view(torch.int16), torch.zeros((1, L), dtype=torch.int16, device="cuda")])
-    for s in range(0, J, 1 << 25):
-        e = min(J, s + (1 << 25))
-        c = i_codes[s:e].long()
-        c = torch.where(c < 0, torch.full_like(c, T.shape[0]), c)        # -1 -> the zero row
-        assert torch.equal(T_ext[c], jcnt.view(torch.int16)[s:e]), "ids form: a code names another vector"
-    del i_off, i_ids, i_codes, T, T_ext
-    print(f"[{name}] join over RPE-IDs ok", flush=True)
-
-    # query-level RPE-IDs: the sampled queries against the oracle, invariants over all
-    qids = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m)
-    assert ctx.check() == 0
-    # the same call with the rows' codes: everywhere the code of the row it names without them
-    qcodes = binding.query_rpe_ids(ctx, walks, off, ids, d_q, max_set=1 + M * m, code=code)
-    assert ctx.check() == 0
-    for s in range(0, qids.shape[0], 1 << 16):
-        rows_part = qids[s:s + (1 << 16)].long()
-        want_part = torch.where(rows_part < 0, torch.full_like(rows_part, -1),
-                                code[rows_part.clamp(min=0)].long())
-        assert torch.equal(qcodes[s:s + (1 << 16)].long(), want_part), "pruned RPE-IDs differ"
-    del qcodes, code
-    sub_w = oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m, wl.rng_seed)
-    w_ids = oracle.query_rpe_ids(sub_w, sub_table[0], sub_table[1], local)
-    # the oracle's rows index the sub-table; turn both sides into (block, row inside block)
-    sub_off = sub_table[0]
-    got_ids = qids[torch.from_numpy(qpick).cuda()].cpu().numpy().astype(np.int64)
-    for col in range(k):
-        g_loc = got_ids[..., col] - off_h[sub_q[:, col]][:, None, None, None]
-        w_loc = w_ids[..., col] - sub_off[local[:, col]][:, None, None, None]
-        absent = w_ids[..., col] < 0
-        assert np.array_equal(got_ids[..., col] < 0, absent), "RPE-ID presence differs"
-        assert np.array_equal(g_loc[~absent], w_loc[~absent]), "sampled RPE-IDs differ"
-    own = torch.stack([qids[:, j, :, :, j] for j in range(k)], dim=1)      # [Q][k][M][L]
-    assert bool((own >= 0).all()), "a walk entry is missing from its own block"
-    assert bool((ids[own.long()] == walks[d_q.long()]).all()), "own RPE-ID names another node"
-    del qids, own
-    print(f"[{name}] query RPE-IDs parity + invariants ok", flush=True)
-
-    # invariants over the whole join: sizes bounded by the parts, every half sums to M
-    sizes = (off[1:] - off[:-1])[d_q.long()]
-    jn = joff[1:] - joff[:-1]
-    assert bool((jn >= sizes.max(dim=1).values).all()) and bool((jn <= sizes.sum(dim=1)).all())
-    half_sums = segment_sums(jcnt.reshape(J, k * L), joff)
-    assert bool((half_sums == M).all()), "a joined half does not sum to M per step"
-    print(f"[{name}] join parity + invariants ok", flush=True)
-
-
-def test_cl235k_full_size(ctx):
-    check_workload(ctx, "cl235k")
-
-
-def test_rmat512k_full_size(ctx):
-    check_workload(ctx, "rmat512k")
-
-
-def test_cl2900k_full_size(ctx):
-    check_workload(ctx, "cl2900k", n_sample_seeds=1200, n_sample_queries=500)
-
-
-def test_cl1m_triples_full_size(ctx):
-    check_workload(ctx, "cl1m_triples")
-
-
-def test_table_with_more_than_2_31_rows(ctx):
-    # the 2.9M-node graph with M = 330: 2.35 G table rows, so row numbers and byte offsets pass
-    # 2^31 and 2^32; fused kernel against the two calls in full, then seeds (mostly from the far
-    # end of the table) and queries against the oracle
-    wl = synth.WORKLOADS["cl2900k"]
-    M, m = 330, 4
-    L = m + 1
-    rp, ci = synth.make_graph(wl)
-    queries = synth.make_queries(wl, rp, ci)[:200000]
-    N = wl.n_nodes
-    d_rp, d_ci, d_q = dev(rp), dev(ci), dev(queries)
-    seeds = torch.arange(N, dtype=torch.int32, device="cuda")
-    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, seeds, M, m, 0)
-    assert ctx.check() == 0
-    R = int(f_off[-1])
-    assert R > 2 ** 31 and bool((f_off[1:] > f_off[:-1]).all())
-    print(f"[2^31] fused done: R={R}", flush=True)
-    sizes = torch.empty(N, dtype=torch.int32, device="cuda")
-    walks = binding.sample_walks(ctx, d_rp, d_ci, seeds, M, m, 0, set_sizes=sizes)
-    assert torch.equal(walks, f_walks)
-    del walks
-    off = torch.empty(N + 1, dtype=torch.int64, device="cuda")
-    ids = torch.empty(R, dtype=torch.int32, device="cuda")
-    cnt = torch.empty((R, L), dtype=torch.uint16, device="cuda")
-    rc, R2 = binding.build_rpe_raw(ctx, f_walks, N, R, off, ids, cnt, set_sizes=sizes)
-    assert rc == binding.OK and R2 == R and ctx.check() == 0
-    assert torch.equal(off, f_off) and torch.equal(ids, f_ids)
-    for s in range(0, R, 1 << 28):
-        e = min(R, s + (1 << 28))
-        assert torch.equal(cnt.view(torch.int16)[s:e], f_cnt.view(torch.int16)[s:e])
-    del ids, cnt, off
-    print("[2^31] the two-call path equals the fused kernel", flush=True)
-    rng = np.random.default_rng(1)
-    pick = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 200),
-                                     rng.integers(N - 5000, N, 200)])).astype(np.int32)
-    w = oracle.sample_walks(rp, ci, pick, M, m, 0)
-    assert np.array_equal(f_walks[torch.from_numpy(pick).long().cuda()].cpu().numpy(), w)
-    t_off, t_ids, t_cnt = oracle.build_rpe(w)
-    off_h = f_off.cpu().numpy()
-    assert np.array_equal(off_h[pick + 1] - off_h[pick], np.diff(t_off))
-    rows = torch.from_numpy(np.concatenate([np.arange(off_h[u], off_h[u + 1]) for u in pick])).cuda()
-    assert int(rows.max()) > 2 ** 31
-    assert np.array_equal(f_ids[rows].cpu().numpy(), t_ids)
-    assert np.array_equal(rows_u16(f_cnt, rows), t_cnt)
-    joff, jids, jcnt = binding.join_queries(ctx, f_off, f_ids, f_cnt, d_q, max_set=1 + M * m)
-    assert ctx.check() == 0
-    qp = np.unique(rng.integers(0, queries.shape[0], 150))
-    sub = queries[qp]
-    nodes, local = np.unique(sub, return_inverse=True)
-    tab = oracle.build_rpe(oracle.sample_walks(rp, ci, nodes.astype(np.int32), M, m, 0))
-    w_off, w_ids, w_cnt = oracle.join_queries(*tab, local.reshape(sub.shape).astype(np.int32))
-    joff_h = joff.cpu().numpy()
-    assert np.array_equal(joff_h[qp + 1] - joff_h[qp], np.diff(w_off))
-    jr = torch.from_numpy(np.concatenate([np.arange(joff_h[q], joff_h[q + 1]) for q in qp])).cuda()
-    assert np.array_equal(jids[jr].cpu().numpy(), w_ids)
-    assert np.array_equal(rows_u16(jcnt, jr), w_cnt)
