@@ -41,7 +41,17 @@
  *   - No function throws, prints, or touches errno.
  *
  *   - The uint16 count arrays (d_rpe_cnt, d_join_cnt) must start on a 4-byte boundary
- *     (SUREL_E_RANGE otherwise): they are moved as 32-bit words wherever possible.
+ *     (SUREL_E_RANGE otherwise): they are moved as 32-bit words wherever possible.  The join
+ *     READS d_rpe_cnt (and d_code) as the aligned 32-bit words that cover a vector, so the word
+ *     that holds the table's last count is read whole: when rows * (m+1) is odd that is 2 bytes
+ *     past the last count (never past that word).  Any buffer whose size is a multiple of 4
+ *     bytes, which includes every allocation of hipMalloc or torch, satisfies this; the extra
+ *     half word is discarded.
+ *   - Sizing.  The variable-size outputs (RPE table, join) come in three forms each: a
+ *     counting call (surel_build_rpe_count, surel_join_count: offsets and total only), a filling
+ *     call that trusts the caller's offsets and launches nothing else (surel_build_rpe_fill,
+ *     surel_join_fill), and a call that does both into buffers of cap_rows rows
+ *     (surel_build_rpe, surel_join_queries; with NULL outputs they are counting calls too).
  *
  * Layouts (row-major, densely packed, no padding)
  *   CSR      d_row_ptr int32[n_nodes+1], d_col_idx int32[n_edges]; entries of a row are the
@@ -82,8 +92,9 @@ extern "C" {
 #define SUREL_DEV_SET_TOO_LARGE 0x10u  /* a block of the RPE table has more than max_set rows */
 #define SUREL_DEV_CAPACITY      0x20u  /* rows beyond cap_rows were not written             */
 #define SUREL_DEV_BAD_TABLE     0x40u  /* d_rpe_off is not non-decreasing at a queried block */
-#define SUREL_DEV_BAD_SIZES     0x80u  /* a seed's d_set_sizes entry is not its number of
-                                          distinct nodes; that seed's rows are not written   */
+#define SUREL_DEV_BAD_SIZES     0x80u  /* a seed's d_set_sizes entry (or the offsets given to a
+                                          filling call) do not match its number of rows; that
+                                          seed's / query's rows are not written              */
 #define SUREL_DEV_STALL         0x100u /* a bounded wait inside surel_sample_walks_rpe ran out
                                           (see surel_set_spin_limit), or a bounded probe of a
                                           hash table of surel_bfs_batches; outputs are
@@ -169,11 +180,30 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
  * Limits: as for surel_sample_walks, and M*(m+1) <= SUREL_MAX_WALK_ENTRIES.
  * Returns SUREL_E_CAPACITY if h_rows is given and the total exceeds cap_rows; rows at or
  * beyond cap_rows are never written (blocks that do not fit entirely are skipped).
- * Device-detected: BAD_WALK (the entry counts as node 0), CAPACITY, BAD_SIZES. */
+ * Device-detected: BAD_WALK (an entry outside [0, n_nodes) is left out of the counts, so the
+ * block of a seed that surel_sample_walks rejected, all -1, yields no rows), CAPACITY,
+ * BAD_SIZES. */
 int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
                     int32_t m, int32_t n_nodes, const int32_t* d_set_sizes, int64_t cap_rows,
                     int64_t* d_rpe_off, int32_t* d_rpe_ids, uint16_t* d_rpe_cnt,
                     int64_t* h_rows);
+
+/* The two phases of surel_build_rpe as calls of their own (Algorithm 1's RPE step has a
+ * data-dependent output size: V_u = set(W_u)).
+ * surel_build_rpe_count: the layout only.  Writes d_rpe_off[0 .. n_seeds] and, if h_rows is
+ * given, waits and stores the row total.  d_set_sizes as above (NULL: counted here).
+ * surel_build_rpe_fill: the rows only.  d_rpe_off (device, READ-only) must hold the offsets of
+ * these walks, from surel_build_rpe_count or kept from an earlier call; nothing is counted or
+ * scanned again, one kernel is launched and nothing is waited for.  A seed whose walks do not
+ * have d_rpe_off[i+1] - d_rpe_off[i] distinct nodes is skipped and flagged (BAD_SIZES), as is
+ * a block that would pass cap_rows (CAPACITY).
+ * Arguments, limits and the other device-detected problems as for surel_build_rpe. */
+int surel_build_rpe_count(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
+                          int32_t m, int32_t n_nodes, const int32_t* d_set_sizes,
+                          int64_t* d_rpe_off, int64_t* h_rows);
+int surel_build_rpe_fill(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
+                         int32_t m, int32_t n_nodes, const int64_t* d_rpe_off, int64_t cap_rows,
+                         int32_t* d_rpe_ids, uint16_t* d_rpe_cnt);
 
 /* Sec. 3.2: "the RPE is computed on the fly as walks get sampled" (Algorithm 1, walk and RPE
  * steps in one pass).  Exactly the results of surel_sample_walks followed by surel_build_rpe
@@ -183,7 +213,8 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
  * Limits: those of both calls (M*(m+1) <= SUREL_MAX_WALK_ENTRIES).  n_seeds = 0 writes
  * d_rpe_off[0] = 0.
  * Device-detected: BAD_SEED (that seed's walks are filled with -1 and it gets no rows),
- * BAD_GRAPH (the walker stays in place for that step), CAPACITY, STALL. */
+ * BAD_GRAPH (the walker stays in place for that step), CAPACITY, STALL (the offsets are then
+ * incomplete; a call that was given h_rows returns SUREL_E_DEVICE instead of a total). */
 int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
                            int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
                            int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
@@ -207,6 +238,25 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                        int32_t k, int64_t cap_rows, int64_t* d_join_off,
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
+
+/* The two phases of the join as calls of their own (Sec. 3.4: the size of a query's union is
+ * data-dependent).
+ * surel_join_count: the layout only, from the id lists alone.  Writes d_join_off[0 .. n_queries]
+ * and, if h_rows is given, waits and stores the row total.
+ * surel_join_fill: the rows only.  d_join_off (device, READ-only) must hold the offsets of these
+ * queries over this table, from surel_join_count or kept from an earlier call; nothing is
+ * counted or scanned again, one kernel is launched and nothing is waited for.  A query whose
+ * union does not have d_join_off[q+1] - d_join_off[q] rows is skipped and flagged (BAD_SIZES),
+ * as are rows that would pass cap_rows (CAPACITY).
+ * Arguments, limits and the other device-detected problems as for surel_join_queries. */
+int surel_join_count(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                     int64_t n_blocks, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                     int32_t k, int64_t* d_join_off, int64_t* h_rows);
+int surel_join_fill(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                    const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+                    const int32_t* d_queries, int64_t n_queries, int32_t k,
+                    const int64_t* d_join_off, int64_t cap_rows, int32_t* d_join_ids,
+                    uint16_t* d_join_cnt);
 
 /* surel_join_queries with RPE-IDs instead of RPE values (Sec. 3.3: "the table carries RPE-IDs";
  * Sec. 3.4's closing remarks on shipping IDs instead of values): the same union rows, and for

@@ -43,11 +43,18 @@ SIGNATURES = {
                                           _u64, _vp, _vp]),
     "surel_build_rpe": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _vp, _vp,
                                        _vp, ctypes.POINTER(_i64)]),
+    "surel_build_rpe_count": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp,
+                                             ctypes.POINTER(_i64)]),
+    "surel_build_rpe_fill": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _vp, _vp]),
     "surel_sample_walks_rpe": (ctypes.c_int, [_vp, _vp, _vp, _i32, _i64, _vp, _i64, _i32, _i32,
                                               _u64, _vp, _i64, _vp, _vp, _vp,
                                               ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "surel_join_count": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _vp,
+                                        ctypes.POINTER(_i64)]),
+    "surel_join_fill": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp,
+                                       _i64, _vp, _vp]),
     "surel_join_query_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _i64,
                                             _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_query_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i32, _i32,
@@ -231,6 +238,28 @@ def build_rpe(ctx: Context, walks: torch.Tensor, n_nodes: int, cap_rows: int | N
     return off, ids[:rows], cnt[:rows]
 
 
+def build_rpe_count(ctx: Context, walks: torch.Tensor, n_nodes: int, rpe_off: torch.Tensor,
+                    set_sizes: torch.Tensor | None = None, want_rows: bool = True):
+    """surel_build_rpe_count: the table's layout only.  Returns (status, rows or None)."""
+    n_seeds, M, L = walks.shape
+    rows = _i64(-1)
+    rc = load().surel_build_rpe_count(
+        ctx.handle, _ptr(walks, torch.int32, "walks"), n_seeds, M, L - 1, n_nodes,
+        _ptr(set_sizes, torch.int32, "set_sizes"), _ptr(rpe_off, torch.int64, "rpe_off"),
+        ctypes.byref(rows) if want_rows else None)
+    return rc, (rows.value if want_rows else None)
+
+
+def build_rpe_fill(ctx: Context, walks: torch.Tensor, n_nodes: int, rpe_off: torch.Tensor,
+                   cap_rows: int, rpe_ids: torch.Tensor, rpe_cnt: torch.Tensor) -> int:
+    """surel_build_rpe_fill: the rows only, at the offsets given.  Returns the status."""
+    n_seeds, M, L = walks.shape
+    return load().surel_build_rpe_fill(
+        ctx.handle, _ptr(walks, torch.int32, "walks"), n_seeds, M, L - 1, n_nodes,
+        _ptr(rpe_off, torch.int64, "rpe_off"), cap_rows, _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(rpe_cnt, torch.uint16, "rpe_cnt"))
+
+
 def sample_walks_rpe_raw(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
                          seeds: torch.Tensor, M: int, m: int, rng_seed: int, walks: torch.Tensor,
                          cap_rows: int, rpe_off: torch.Tensor, rpe_ids: torch.Tensor | None,
@@ -305,6 +334,31 @@ def join_queries(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
     if rc != OK:
         raise SurelError(rc, "surel_join_queries")
     return off, ids[:rows], cnt[:rows]
+
+
+def join_count(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor, queries: torch.Tensor,
+               max_set: int, join_off: torch.Tensor, want_rows: bool = True):
+    """surel_join_count: the join's layout only.  Returns (status, rows or None)."""
+    n_q, k = queries.shape
+    rows = _i64(-1)
+    rc = load().surel_join_count(
+        ctx.handle, _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        rpe_off.numel() - 1, max_set, _ptr(queries, torch.int32, "queries"), n_q, k,
+        _ptr(join_off, torch.int64, "join_off"), ctypes.byref(rows) if want_rows else None)
+    return rc, (rows.value if want_rows else None)
+
+
+def join_fill(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor, rpe_cnt: torch.Tensor,
+              queries: torch.Tensor, max_set: int, join_off: torch.Tensor, cap_rows: int,
+              join_ids: torch.Tensor, join_cnt: torch.Tensor) -> int:
+    """surel_join_fill: the joined rows only, at the offsets given.  Returns the status."""
+    n_q, k = queries.shape
+    L = rpe_cnt.shape[1]
+    return load().surel_join_fill(
+        ctx.handle, _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), rpe_off.numel() - 1, L - 1, max_set,
+        _ptr(queries, torch.int32, "queries"), n_q, k, _ptr(join_off, torch.int64, "join_off"),
+        cap_rows, _ptr(join_ids, torch.int32, "join_ids"), _ptr(join_cnt, torch.uint16, "join_cnt"))
 
 
 def join_query_ids_raw(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,

@@ -286,49 +286,104 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     return rc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
 }
 
+// Argument checks shared by the three forms of the RPE builder.
+static int check_rpe_args(int32_t n_nodes, int64_t n_seeds, int32_t M, int32_t m,
+                          const int32_t* d_walks) {
+    if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
+    if ((int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
+    if (n_seeds > 0 && !d_walks) return SUREL_E_NULL;
+    return SUREL_OK;
+}
+
+// Waits for the stream and reports the row total that a scan or a scanner wave left at off[n]
+// (-1: the kernel gave up on a bounded wait before it got there).
+static int report_total(surel_ctx* ctx, const int64_t* d_off, int64_t n, bool has_outputs,
+                        int64_t cap_rows, int64_t* h_rows) {
+    if (int rc = read_total(ctx, d_off, n, h_rows)) return rc;
+    if (*h_rows < 0) return SUREL_E_DEVICE;
+    if (has_outputs && *h_rows > cap_rows) return SUREL_E_CAPACITY;
+    return SUREL_OK;
+}
+
+// Phase A of the RPE builder: per-seed set sizes (the caller's, or counted here) -> rpe_off.
+static int rpe_layout(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M, int32_t m,
+                      int32_t n_nodes, const int32_t* d_set_sizes, int64_t* d_rpe_off) {
+    int32_t* counts = nullptr;
+    int64_t* partials = nullptr;
+    if (int rc = ensure_workspace(ctx, n_seeds, &counts, &partials)) return rc;
+    const int32_t* sizes = d_set_sizes;
+    if (!sizes) {
+        KernelSpan span(ctx, SUREL_K_RPE_COUNT);
+        if (surel::launch_rpe_count(ctx->stream, d_walks, n_seeds, M, m, n_nodes, counts,
+                                    ctx->d_err) != hipSuccess)
+            return SUREL_E_HIP;
+        sizes = counts;
+    }
+    KernelSpan span(ctx, SUREL_K_SCAN);
+    if (surel::launch_exclusive_scan(ctx->stream, sizes, n_seeds, d_rpe_off, partials) != hipSuccess)
+        return SUREL_E_HIP;
+    return SUREL_OK;
+}
+
+// Phase B: the rows, at the offsets given.
+static int rpe_rows(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M, int32_t m,
+                    int32_t n_nodes, const int64_t* d_rpe_off, int64_t cap_rows,
+                    int32_t* d_rpe_ids, uint16_t* d_rpe_cnt) {
+    KernelSpan span(ctx, SUREL_K_RPE_FILL);
+    hipError_t hrc = surel::launch_rpe_fill(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m,
+                                            n_nodes, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt,
+                                            ctx->d_err);
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    return hrc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
+}
+
+int surel_build_rpe_count(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
+                          int32_t m, int32_t n_nodes, const int32_t* d_set_sizes,
+                          int64_t* d_rpe_off, int64_t* h_rows) {
+    if (int rc = check_rpe_args(n_nodes, n_seeds, M, m, d_walks)) return rc;
+    if (!d_rpe_off) return SUREL_E_NULL;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (int rc = rpe_layout(ctx, d_walks, n_seeds, M, m, n_nodes, d_set_sizes, d_rpe_off)) return rc;
+    if (h_rows) return report_total(ctx, d_rpe_off, n_seeds, false, 0, h_rows);
+    return SUREL_OK;
+}
+
+int surel_build_rpe_fill(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
+                         int32_t m, int32_t n_nodes, const int64_t* d_rpe_off, int64_t cap_rows,
+                         int32_t* d_rpe_ids, uint16_t* d_rpe_cnt) {
+    if (int rc = check_rpe_args(n_nodes, n_seeds, M, m, d_walks)) return rc;
+    if (cap_rows < 0) return SUREL_E_RANGE;
+    if (!d_rpe_off) return SUREL_E_NULL;
+    if (n_seeds > 0 && cap_rows > 0 && (!d_rpe_ids || !d_rpe_cnt)) return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
+    if (!ctx) return SUREL_E_CTX;
+    if (n_seeds == 0) return SUREL_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    return rpe_rows(ctx, d_walks, n_seeds, M, m, n_nodes, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt);
+}
+
 int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int32_t M,
                     int32_t m, int32_t n_nodes, const int32_t* d_set_sizes, int64_t cap_rows,
                     int64_t* d_rpe_off,
                     int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows) {
-    if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
-    if ((int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
+    if (int rc = check_rpe_args(n_nodes, n_seeds, M, m, d_walks)) return rc;
     if (cap_rows < 0) return SUREL_E_RANGE;
-    if (!d_rpe_off || (n_seeds > 0 && !d_walks)) return SUREL_E_NULL;
+    if (!d_rpe_off) return SUREL_E_NULL;
     if ((d_rpe_ids == nullptr) != (d_rpe_cnt == nullptr)) return SUREL_E_NULL;
     if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
     if (!ctx) return SUREL_E_CTX;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
-
-    int32_t* counts = nullptr;
-    int64_t* partials = nullptr;
-    if (int rc = ensure_workspace(ctx, n_seeds, &counts, &partials)) return rc;
-    hipError_t hrc = hipSuccess;
-    const int32_t* sizes = d_set_sizes;
-    if (!sizes) {
-        KernelSpan span(ctx, SUREL_K_RPE_COUNT);
-        hrc = surel::launch_rpe_count(ctx->stream, d_walks, n_seeds, M, m, n_nodes, counts,
-                                      ctx->d_err);
-        sizes = counts;
+    if (int rc = rpe_layout(ctx, d_walks, n_seeds, M, m, n_nodes, d_set_sizes, d_rpe_off)) return rc;
+    if (d_rpe_ids && n_seeds > 0) {
+        if (int rc = rpe_rows(ctx, d_walks, n_seeds, M, m, n_nodes, d_rpe_off, cap_rows, d_rpe_ids,
+                              d_rpe_cnt))
+            return rc;
     }
-    if (hrc != hipSuccess) return SUREL_E_HIP;
-    {
-        KernelSpan span(ctx, SUREL_K_SCAN);
-        hrc = surel::launch_exclusive_scan(ctx->stream, sizes, n_seeds, d_rpe_off, partials);
-    }
-    if (hrc != hipSuccess) return SUREL_E_HIP;
-    if (d_rpe_ids) {
-        KernelSpan span(ctx, SUREL_K_RPE_FILL);
-        hrc = surel::launch_rpe_fill(ctx->stream, ctx->max_lds_bytes, d_walks, n_seeds, M, m,
-                                     n_nodes, d_rpe_off, cap_rows, d_rpe_ids, d_rpe_cnt,
-                                     ctx->d_err);
-        if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
-        if (hrc != hipSuccess) return SUREL_E_HIP;
-    }
-    if (h_rows) {
-        if (int rc = read_total(ctx, d_rpe_off, n_seeds, h_rows)) return rc;
-        if (d_rpe_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
-    }
+    if (h_rows) return report_total(ctx, d_rpe_off, n_seeds, d_rpe_ids != nullptr, cap_rows, h_rows);
     return SUREL_OK;
 }
 
@@ -361,7 +416,7 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
     if (int rc = make_edge_records(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, n_seeds, M, m,
                                    &records))
         return rc;
-    const size_t lb_need = (size_t)surel::walk_rpe_lookback_words(n_seeds) * sizeof(uint64_t);
+    const size_t lb_need = (size_t)surel::lookback_words(n_seeds) * sizeof(uint64_t);
     if (int rc = grow_buffer(ctx, &ctx->d_lb, &ctx->lb_bytes, lb_need)) return rc;
     {
         KernelSpan span(ctx, SUREL_K_WALK_RPE);
@@ -372,64 +427,155 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
         if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
         if (hrc != hipSuccess) return SUREL_E_HIP;
     }
-    if (h_rows) {
-        if (int rc = read_total(ctx, d_rpe_off, n_seeds, h_rows)) return rc;
-        if (d_rpe_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
-    }
+    if (h_rows) return report_total(ctx, d_rpe_off, n_seeds, d_rpe_ids != nullptr, cap_rows, h_rows);
     return SUREL_OK;
 }
 
 // The join over vectors of m+1 16-bit entries per table row; absent16 fills the vector of a
 // list that has no row for a node (0 for counts; 0xFFFF for 32-bit codes seen as two halves).
-static int join_vectors(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
-                        const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
-                        const int32_t* d_queries, int64_t n_queries, int32_t k, int64_t cap_rows,
-                        int64_t* d_join_off, int32_t* d_join_ids, uint16_t* d_join_cnt,
-                        uint16_t absent16, int64_t* h_rows) {
+static int check_join_args(int32_t m, int32_t max_set, int64_t n_blocks, int64_t n_queries,
+                           int32_t k, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                           const int32_t* d_queries, const int64_t* d_join_off) {
     if (m < 1 || m > SUREL_MAX_STEPS) return SUREL_E_RANGE;
     if (k < 2 || k > SUREL_MAX_TUPLE) return SUREL_E_RANGE;
     if (max_set < 1 || max_set > SUREL_MAX_SET) return SUREL_E_RANGE;
-    if (n_blocks < 0 || n_queries < 0 || n_queries > 0x7FFFFFFFll || cap_rows < 0)
-        return SUREL_E_RANGE;
+    if (n_blocks < 0 || n_queries < 0 || n_queries > 0x7FFFFFFFll) return SUREL_E_RANGE;
     if (!d_join_off) return SUREL_E_NULL;
     if (n_queries > 0 && (!d_queries || !d_rpe_off || !d_rpe_ids)) return SUREL_E_NULL;
+    return SUREL_OK;
+}
+
+// Device scratch of a join call: the queries' row counts and the partials of their scan.
+struct JoinScratch {
+    int32_t* counts = nullptr;
+    int64_t* partials = nullptr;
+};
+
+// Phase A: union sizes -> join_off.
+static int join_layout(surel_ctx* ctx, const JoinScratch& ws, const int64_t* d_rpe_off,
+                       const int32_t* d_rpe_ids, int64_t n_blocks, int32_t max_set,
+                       const int32_t* d_queries, int64_t n_queries, int32_t k,
+                       int64_t* d_join_off) {
+    hipError_t hrc;
+    {
+        KernelSpan span(ctx, SUREL_K_JOIN_COUNT);
+        hrc = surel::launch_join_count(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off,
+                                       d_rpe_ids, n_blocks, max_set, d_queries, n_queries, k,
+                                       ws.counts, ctx->d_err);
+    }
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    if (hrc != hipSuccess) return SUREL_E_HIP;
+    KernelSpan span(ctx, SUREL_K_SCAN);
+    if (surel::launch_exclusive_scan(ctx->stream, ws.counts, n_queries, d_join_off, ws.partials) !=
+        hipSuccess)
+        return SUREL_E_HIP;
+    return SUREL_OK;
+}
+
+// Phase B: the rows, at the offsets given.
+static int join_rows(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                     const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+                     const int32_t* d_queries, int64_t n_queries, int32_t k,
+                     const int64_t* d_join_off, int64_t cap_rows, int32_t* d_join_ids,
+                     uint16_t* d_join_cnt, uint16_t absent16) {
+    KernelSpan span(ctx, SUREL_K_JOIN_FILL);
+    hipError_t hrc = surel::launch_join_fill(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off,
+                                             d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
+                                             n_queries, k, d_join_off, cap_rows, d_join_ids,
+                                             d_join_cnt, absent16, ctx->d_err);
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    return hrc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
+}
+
+// The whole join with the scratch given: layout, then (unless the outputs are NULL) the rows.
+static int join_vectors(surel_ctx* ctx, const JoinScratch& ws, const int64_t* d_rpe_off,
+                        const int32_t* d_rpe_ids, const uint16_t* d_rpe_cnt, int64_t n_blocks,
+                        int32_t m, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                        int32_t k, int64_t cap_rows, int64_t* d_join_off, int32_t* d_join_ids,
+                        uint16_t* d_join_cnt, uint16_t absent16, int64_t* h_rows) {
+    if (int rc = join_layout(ctx, ws, d_rpe_off, d_rpe_ids, n_blocks, max_set, d_queries, n_queries,
+                             k, d_join_off))
+        return rc;
+    if (d_join_ids && n_queries > 0) {
+        if (int rc = join_rows(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
+                               n_queries, k, d_join_off, cap_rows, d_join_ids, d_join_cnt, absent16))
+            return rc;
+    }
+    if (h_rows)
+        return report_total(ctx, d_join_off, n_queries, d_join_ids != nullptr, cap_rows, h_rows);
+    return SUREL_OK;
+}
+
+// Argument checks of the calls that do the whole join.
+static int check_whole_join(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                            const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+                            const int32_t* d_queries, int64_t n_queries, int32_t k, int64_t cap_rows,
+                            const int64_t* d_join_off, const int32_t* d_join_ids,
+                            const uint16_t* d_join_cnt) {
+    if (int rc = check_join_args(m, max_set, n_blocks, n_queries, k, d_rpe_off, d_rpe_ids,
+                                 d_queries, d_join_off))
+        return rc;
+    if (cap_rows < 0) return SUREL_E_RANGE;
     if ((d_join_ids == nullptr) != (d_join_cnt == nullptr)) return SUREL_E_NULL;
     if (n_queries > 0 && d_join_ids && !d_rpe_cnt) return SUREL_E_NULL;
     if (misaligned4(d_rpe_cnt) || misaligned4(d_join_cnt)) return SUREL_E_RANGE;
     if (!ctx) return SUREL_E_CTX;
+    return SUREL_OK;
+}
+
+static int join_checked(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                        const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+                        const int32_t* d_queries, int64_t n_queries, int32_t k, int64_t cap_rows,
+                        int64_t* d_join_off, int32_t* d_join_ids, uint16_t* d_join_cnt,
+                        uint16_t absent16, int64_t* h_rows) {
+    if (int rc = check_whole_join(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set,
+                                  d_queries, n_queries, k, cap_rows, d_join_off, d_join_ids,
+                                  d_join_cnt))
+        return rc;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
+    JoinScratch ws;
+    if (int rc = ensure_workspace(ctx, n_queries, &ws.counts, &ws.partials)) return rc;
+    return join_vectors(ctx, ws, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
+                        n_queries, k, cap_rows, d_join_off, d_join_ids, d_join_cnt, absent16, h_rows);
+}
 
-    int32_t* counts = nullptr;
-    int64_t* partials = nullptr;
-    if (int rc = ensure_workspace(ctx, n_queries, &counts, &partials)) return rc;
-    hipError_t hrc;
-    {
-        KernelSpan span(ctx, SUREL_K_JOIN_COUNT);
-        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off, d_rpe_ids, d_rpe_cnt,
-                                 n_blocks, m, max_set, d_queries, n_queries, k, counts, nullptr, 0,
-                                 nullptr, nullptr, absent16, ctx->d_err);
-    }
-    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
-    if (hrc != hipSuccess) return SUREL_E_HIP;
-    {
-        KernelSpan span(ctx, SUREL_K_SCAN);
-        hrc = surel::launch_exclusive_scan(ctx->stream, counts, n_queries, d_join_off, partials);
-    }
-    if (hrc != hipSuccess) return SUREL_E_HIP;
-    if (d_join_ids) {
-        KernelSpan span(ctx, SUREL_K_JOIN_FILL);
-        hrc = surel::launch_join(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off, d_rpe_ids, d_rpe_cnt,
-                                 n_blocks, m, max_set, d_queries, n_queries, k, nullptr, d_join_off,
-                                 cap_rows, d_join_ids, d_join_cnt, absent16, ctx->d_err);
-        if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
-        if (hrc != hipSuccess) return SUREL_E_HIP;
-    }
-    if (h_rows) {
-        if (int rc = read_total(ctx, d_join_off, n_queries, h_rows)) return rc;
-        if (d_join_ids && *h_rows > cap_rows) return SUREL_E_CAPACITY;
-    }
+int surel_join_count(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                     int64_t n_blocks, int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                     int32_t k, int64_t* d_join_off, int64_t* h_rows) {
+    if (int rc = check_join_args(1, max_set, n_blocks, n_queries, k, d_rpe_off, d_rpe_ids,
+                                 d_queries, d_join_off))
+        return rc;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    JoinScratch ws;
+    if (int rc = ensure_workspace(ctx, n_queries, &ws.counts, &ws.partials)) return rc;
+    if (int rc = join_layout(ctx, ws, d_rpe_off, d_rpe_ids, n_blocks, max_set, d_queries, n_queries,
+                             k, d_join_off))
+        return rc;
+    if (h_rows) return report_total(ctx, d_join_off, n_queries, false, 0, h_rows);
     return SUREL_OK;
+}
+
+int surel_join_fill(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                    const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
+                    const int32_t* d_queries, int64_t n_queries, int32_t k,
+                    const int64_t* d_join_off, int64_t cap_rows, int32_t* d_join_ids,
+                    uint16_t* d_join_cnt) {
+    if (int rc = check_join_args(m, max_set, n_blocks, n_queries, k, d_rpe_off, d_rpe_ids,
+                                 d_queries, d_join_off))
+        return rc;
+    if (cap_rows < 0) return SUREL_E_RANGE;
+    if (n_queries > 0 && cap_rows > 0 && (!d_join_ids || !d_join_cnt || !d_rpe_cnt))
+        return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt) || misaligned4(d_join_cnt)) return SUREL_E_RANGE;
+    if (!ctx) return SUREL_E_CTX;
+    if (n_queries == 0) return SUREL_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    return join_rows(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
+                     n_queries, k, d_join_off, cap_rows, d_join_ids, d_join_cnt, 0);
 }
 
 int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
@@ -437,7 +583,7 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t max_set, const int32_t* d_queries, int64_t n_queries,
                        int32_t k, int64_t cap_rows, int64_t* d_join_off,
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows) {
-    return join_vectors(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
+    return join_checked(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
                         n_queries, k, cap_rows, d_join_off, d_join_ids, d_join_cnt, 0, h_rows);
 }
 
@@ -447,7 +593,7 @@ int surel_join_query_ids(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t
                          int64_t* d_join_off, int32_t* d_join_ids, int32_t* d_join_codes,
                          int64_t* h_rows) {
     // a 32-bit code is a vector of two 16-bit entries; absent = 0xFFFF 0xFFFF = -1
-    return join_vectors(ctx, d_rpe_off, d_rpe_ids, reinterpret_cast<const uint16_t*>(d_code),
+    return join_checked(ctx, d_rpe_off, d_rpe_ids, reinterpret_cast<const uint16_t*>(d_code),
                         n_blocks, 1, max_set, d_queries, n_queries, k, cap_rows, d_join_off,
                         d_join_ids, reinterpret_cast<uint16_t*>(d_join_codes), 0xFFFFu, h_rows);
 }

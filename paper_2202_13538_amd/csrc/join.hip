@@ -2,10 +2,16 @@
 // (b_1..b_K) the ascending union of the K node sets, and per union node the K count
 // vectors in tuple order, zeros where the node is absent from a set.
 //
-// Two launches of one kernel: the first only counts every query's union rows, an exclusive
-// scan turns the counts into join_off, the second writes the rows.  A wavefront handles one
-// query at a time and loops over the queries (the grid is as large as the device holds at
-// once); the K sorted id lists are staged in LDS.
+// Two launches of one kernel body.  Counting: every query's union rows (an exclusive scan then
+// turns the counts into join_off).  Filling: join_off is given (by that scan, or kept by the
+// caller from an earlier call), the rows are written.  A wavefront handles one query at a time
+// and loops over the queries (the grid is as large as the device holds at once); the K sorted id
+// lists are staged in LDS.  (Doing both in one launch, with the offsets from a scanner wave
+// inside the kernel as the fused walk + RPE kernel has them, was built and measured: a wave has
+// to wait for its query's offset between uniting and writing, which took 10.0 ms against
+// 0.83 + 5.6 ms for the two launches on the 2.9M-node workload; holding one query back to hide
+// that wait doubles the LDS a wave needs, and the filling launch with that footprint alone
+// takes 8.9 ms.)
 //
 // Which union row a node lands in, and which table rows feed it ("sources"):
 //   - pairs: a merge path.  Lane l owns merged positions [l*VT, (l+1)*VT): a binary search on
@@ -31,10 +37,12 @@ namespace surel {
 constexpr uint16_t kNoSrc = 0xFFFFu;
 constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
 constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
-constexpr int kGatherRounds = 8;         // rounds of 64 union rows a wave gathers together (pairs;
-                                         // half as many for larger tuples): a quarter off the fill
-                                         // launch where queries are few and their blocks large, 2 %
-                                         // where occupancy hides the latency
+// Rounds of 64 union rows whose gathers a wave has in flight together: 5 for pairs, 4 for
+// larger tuples.  More rounds shorten a wave's chain of memory round trips but cost registers,
+// and the launch is bound by its waves in flight: 8 rounds (118 registers, 16 waves per compute
+// unit) took 5.75 ms on the 2.9M-node workload, 3 to 5 rounds (20 waves, what LDS allows) 5.59.
+constexpr int kGatherRoundsPairs = 5;
+constexpr int kGatherRoundsTuples = 4;
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {
@@ -244,37 +252,36 @@ __device__ __forceinline__ void fill_vector(uint16_t* dst, int L, uint16_t value
     }
 }
 
-// K = tuple size, WPB = waves per workgroup (as many as the LDS a wave needs allows),
-// kFill = false: write counts[q] only; kFill = true: join_off is complete, write the rows.
-// LT = m+1 at compile time for the usual walk lengths (2 .. 6), 0 = any.
-template <int K, int WPB, bool kFill, int LT>
-__device__ __forceinline__ void join_one_query(
-    uint32_t* lds32, int lane, int wave, int64_t q, const int64_t* __restrict__ rpe_off,
-    const int32_t* __restrict__ rpe_ids, const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks,
-    int32_t m, int32_t max_set, const int32_t* __restrict__ queries,
-    int32_t* __restrict__ counts, const int64_t* __restrict__ join_off, int64_t cap_rows,
-    int32_t* __restrict__ out_ids, uint16_t* __restrict__ out_cnt, uint16_t absent16,
-    uint32_t* __restrict__ err) {
+// The blocks of one query and where its union rows come from, as join_prepare leaves them.
+template <int K>
+struct JoinQuery {
+    int64_t lo[K];  // first table row of block j
+    int n[K];       // rows of block j
+};
 
+// First half of a query: looks its K blocks up, stages their id lists in LDS and unites them.
+// Returns the number of union rows, or -1 if the query is unusable (its problem is flagged and it
+// yields no rows).  With kSrc the sources of every union row are left in LDS for join_write.
+// K = tuple size, LT = m+1 at compile time for the usual walk lengths (2 .. 6), 0 = any.
+template <int K, bool kSrc, int LT>
+__device__ __forceinline__ int join_prepare(
+    uint32_t* base, int lane, int64_t q, const int64_t* __restrict__ rpe_off,
+    const int32_t* __restrict__ rpe_ids, int64_t n_blocks, int32_t m, int32_t max_set,
+    const int32_t* __restrict__ queries, JoinQuery<K>& jq, uint32_t* __restrict__ err) {
     const int L = LT > 0 ? LT : m + 1;
-    const JoinLds lay = join_lds_layout(K, max_set, L, kFill, join_uses_tile(K, LT));
-    uint32_t* base = lds32 + wave * lay.total;
+    const JoinLds lay = join_lds_layout(K, max_set, L, kSrc, join_uses_tile(K, LT));
     uint32_t* ids_lds = base + lay.ids;
     uint16_t* new_pre = reinterpret_cast<uint16_t*>(base + lay.new_pre);
     uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
-    uint32_t* tile32 = base + lay.tile;
-    uint16_t* tile = reinterpret_cast<uint16_t*>(tile32);
     const int src_stride = K * max_set;
 
     // the K blocks of this query (wave-uniform)
-    int64_t lo[K];
-    int n[K];
     uint32_t problem = 0;
 #pragma unroll
     for (int j = 0; j < K; ++j) {
         const int32_t b = queries[q * K + j];
-        lo[j] = 0;
-        n[j] = 0;
+        jq.lo[j] = 0;
+        jq.n[j] = 0;
         if (b < 0 || (int64_t)b >= n_blocks) {
             problem |= kDevBadQuery;
         } else {
@@ -285,44 +292,49 @@ __device__ __forceinline__ void join_one_query(
             } else if (len > (int64_t)max_set) {
                 problem |= kDevSetTooLarge;
             } else {
-                lo[j] = a;
-                n[j] = (int)len;
+                jq.lo[j] = a;
+                jq.n[j] = (int)len;
             }
         }
     }
     if (problem != 0) {
-        if (lane == 0) {
-            atomicOr(err, problem);
-            if (!kFill) counts[q] = 0;  // the query yields no rows
-        }
-        return;
+        if (lane == 0) atomicOr(err, problem);
+        return -1;
     }
 
     // stage the id lists
 #pragma unroll
     for (int j = 0; j < K; ++j)
-        stage_words<8>(ids_lds + j * max_set, reinterpret_cast<const uint32_t*>(rpe_ids + lo[j]),
-                       n[j], lane);
+        stage_words<8>(ids_lds + j * max_set, reinterpret_cast<const uint32_t*>(rpe_ids + jq.lo[j]),
+                       jq.n[j], lane);
     wave_sync();
 
     int n_out;
     if constexpr (K == 2) {
-        n_out = union_pair_merge_path<kFill>(ids_lds, n[0], ids_lds + max_set, n[1], src,
-                                             src_stride, lane);
+        n_out = union_pair_merge_path<kSrc>(ids_lds, jq.n[0], ids_lds + max_set, jq.n[1], src,
+                                            src_stride, lane);
     } else {
-        n_out = union_ranked<K, kFill>(ids_lds, n, max_set, new_pre, src, src_stride, lane);
+        n_out = union_ranked<K, kSrc>(ids_lds, jq.n, max_set, new_pre, src, src_stride, lane);
     }
+    return n_out;
+}
 
-    if (!kFill) {
-        if (lane == 0) counts[q] = n_out;
-        return;
-    }
-    const int64_t off = join_off[q];
-    if (n_out == 0) return;
-    if (off + n_out > cap_rows) {
-        if (lane == 0) atomicOr(err, kDevCapacity);
-        return;
-    }
+// Second half: writes the n_out > 0 union rows of the query that join_prepare<K, true, LT> left
+// in LDS to rows [off, off + n_out) of the output.
+template <int K, int LT>
+__device__ __forceinline__ void join_write(
+    uint32_t* base, int lane, const JoinQuery<K>& jq, int n_out, int64_t off,
+    const uint16_t* __restrict__ rpe_cnt, int32_t m, int32_t max_set,
+    int32_t* __restrict__ out_ids, uint16_t* __restrict__ out_cnt, uint16_t absent16) {
+    const int L = LT > 0 ? LT : m + 1;
+    const JoinLds lay = join_lds_layout(K, max_set, L, true, join_uses_tile(K, LT));
+    uint32_t* ids_lds = base + lay.ids;
+    uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
+    uint32_t* tile32 = base + lay.tile;
+    uint16_t* tile = reinterpret_cast<uint16_t*>(tile32);
+    const int src_stride = K * max_set;
+    const int (&n)[K] = jq.n;
+    const int64_t (&lo)[K] = jq.lo;
     wave_sync();
 
     if constexpr (join_rows_direct(K, LT)) {
@@ -333,7 +345,7 @@ __device__ __forceinline__ void join_one_query(
         // kRounds rounds of 64 rows are gathered together (all their loads are in
         // flight before the first is waited for: a wave's time is a chain of memory round
         // trips), then the rounds go out one after the other
-        constexpr int kRounds = K == 2 ? kGatherRounds : kGatherRounds / 2;
+        constexpr int kRounds = K == 2 ? kGatherRoundsPairs : kGatherRoundsTuples;
         const uint32_t* cnt_words = reinterpret_cast<const uint32_t*>(rpe_cnt);
         for (int r0 = 0; r0 < n_out; r0 += kRounds * kWave) {
             constexpr int kCover = LT / 2 + 1;  // aligned words that cover a vector
@@ -474,9 +486,12 @@ __device__ __forceinline__ void join_one_query(
     }
 }
 
-// Waves loop over the queries (wave w of the grid takes queries w, w + waves, ...): a query is
-// little work, and a grid of one short-lived wave per query is bound by how fast waves can be
-// launched.  No workgroup-wide barrier is used.
+// Counting and filling.  Waves loop over the queries (wave w of the grid takes queries w,
+// w + waves, ...): a query is little work, and a grid of one short-lived wave per query is bound
+// by how fast waves can be launched.  No workgroup-wide barrier is used.
+// kFill = false: write counts[q] only; kFill = true: join_off is complete (the caller's, or the
+// scan of a counting launch), write the rows.  A query whose union does not have the
+// join_off[q+1] - join_off[q] rows that the offsets give it is flagged and writes nothing.
 template <int K, int WPB, bool kFill, int LT>
 __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids,
@@ -487,87 +502,140 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     extern __shared__ uint32_t lds32[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int L = LT > 0 ? LT : m + 1;
+    uint32_t* base = lds32 + wave * join_lds_layout(K, max_set, L, kFill, join_uses_tile(K, LT)).total;
     const int64_t stride = (int64_t)gridDim.x * WPB;
     for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
-        join_one_query<K, WPB, kFill, LT>(lds32, lane, wave, q, rpe_off, rpe_ids, rpe_cnt, n_blocks,
-                                          m, max_set, queries, counts, join_off, cap_rows, out_ids,
-                                          out_cnt, absent16, err);
+        JoinQuery<K> jq;
+        const int n_out = join_prepare<K, kFill, LT>(base, lane, q, rpe_off, rpe_ids, n_blocks, m,
+                                                     max_set, queries, jq, err);
+        if constexpr (!kFill) {
+            if (lane == 0) counts[q] = n_out > 0 ? n_out : 0;  // an unusable query yields no rows
+        } else {
+            const int64_t off = join_off[q];
+            const int rows = n_out > 0 ? n_out : 0;
+            if (join_off[q + 1] - off != (int64_t)rows) {
+                if (lane == 0) atomicOr(err, kDevBadSizes);
+            } else if (rows > 0 && off + rows > cap_rows) {
+                if (lane == 0) atomicOr(err, kDevCapacity);
+            } else if (rows > 0) {
+                join_write<K, LT>(base, lane, jq, rows, off, rpe_cnt, m, max_set, out_ids, out_cnt,
+                                  absent16);
+            }
+        }
         wave_sync();  // the next query reuses the LDS words
     }
 }
 
-#define SUREL_JOIN_PARAMS                                                                         \
-    hipStream_t stream, int n_cu, const int64_t *rpe_off, const int32_t *rpe_ids, const uint16_t *rpe_cnt,  \
-        int64_t n_blocks, int32_t m, int32_t max_set, const int32_t *queries, int64_t n_queries,  \
-        int32_t *counts, const int64_t *join_off, int64_t cap_rows, int32_t *out_ids,             \
-        uint16_t *out_cnt, uint16_t absent16, uint32_t *err
-#define SUREL_JOIN_ARGS                                                                          \
-    stream, n_cu, rpe_off, rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off, \
-        cap_rows, out_ids, out_cnt, absent16, err
+// What a launch is asked to do.
+struct JoinJob {
+    hipStream_t stream;
+    int max_lds_bytes;
+    int n_cu;
+    const int64_t* rpe_off;
+    const int32_t* rpe_ids;
+    const uint16_t* rpe_cnt;
+    int64_t n_blocks;
+    int32_t m;
+    int32_t max_set;
+    const int32_t* queries;
+    int64_t n_queries;
+    int32_t* counts;          // counting launch: written
+    const int64_t* join_off;  // filling launch: read
+    int64_t cap_rows;
+    int32_t* out_ids;
+    uint16_t* out_cnt;
+    uint16_t absent16;
+    uint32_t* err;
+};
 
-template <int K, int WPB, bool kFill, int LT>
-static hipError_t launch_join_cfg(SUREL_JOIN_PARAMS) {
-    const size_t lds_bytes = (size_t)WPB * join_lds_layout(K, max_set, m + 1, kFill, join_uses_tile(K, LT)).total * 4;
+enum JoinMode { kJoinCount, kJoinFill };
+
+template <int K, int WPB, JoinMode kMode, int LT>
+static hipError_t launch_join_cfg(const JoinJob& j) {
+    constexpr bool kFill = kMode == kJoinFill;
+    const size_t lds_bytes =
+        (size_t)WPB * join_lds_layout(K, j.max_set, j.m + 1, kFill, join_uses_tile(K, LT)).total * 4;
+    const void* fn = reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>);
     if (lds_bytes > 48 * 1024) {
-        hipError_t rc = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)lds_bytes);
         if (rc != hipSuccess) return rc;
     }
     // no more workgroups than the device holds at once: their waves loop over the queries
     int per_cu = 0;
-    hipError_t orc = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-        &per_cu, reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>), WPB * kWave,
-        lds_bytes);
+    hipError_t orc = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, WPB * kWave, lds_bytes);
     if (orc != hipSuccess) return orc;
     if (per_cu < 1) return hipErrorInvalidValue;
-    int64_t blocks = (n_queries + WPB - 1) / WPB;
-    if (blocks > (int64_t)per_cu * n_cu) blocks = (int64_t)per_cu * n_cu;
+    int64_t blocks = (j.n_queries + WPB - 1) / WPB;
+    if (blocks > (int64_t)per_cu * j.n_cu) blocks = (int64_t)per_cu * j.n_cu;
     const dim3 grid((unsigned)blocks), block(WPB * kWave);
-    hipLaunchKernelGGL((join_kernel<K, WPB, kFill, LT>), grid, block, lds_bytes, stream, rpe_off,
-                       rpe_ids, rpe_cnt, n_blocks, m, max_set, queries, n_queries, counts, join_off,
-                       cap_rows, out_ids, out_cnt, absent16, err);
+    hipLaunchKernelGGL((join_kernel<K, WPB, kFill, LT>), grid, block, lds_bytes, j.stream, j.rpe_off,
+                       j.rpe_ids, j.rpe_cnt, j.n_blocks, j.m, j.max_set, j.queries, j.n_queries,
+                       j.counts, j.join_off, j.cap_rows, j.out_ids, j.out_cnt, j.absent16, j.err);
     return hipGetLastError();
 }
 
-template <int K, int WPB, bool kFill>
-static hipError_t launch_join_kwf(SUREL_JOIN_PARAMS) {
-    if (kFill && m + 1 == 5) return launch_join_cfg<K, WPB, kFill, 5>(SUREL_JOIN_ARGS);
-    if (kFill && m + 1 == 4) return launch_join_cfg<K, WPB, kFill, 4>(SUREL_JOIN_ARGS);
-    if (kFill && m + 1 == 2) return launch_join_cfg<K, WPB, kFill, 2>(SUREL_JOIN_ARGS);
-    if (kFill && m + 1 == 3) return launch_join_cfg<K, WPB, kFill, 3>(SUREL_JOIN_ARGS);
-    if (kFill && m + 1 == 6) return launch_join_cfg<K, WPB, kFill, 6>(SUREL_JOIN_ARGS);
-    return launch_join_cfg<K, WPB, kFill, 0>(SUREL_JOIN_ARGS);
+// m + 1 at compile time for the usual walk lengths (the counting launch moves no vectors)
+constexpr int join_static_len(JoinMode mode, int L) {
+    return (mode != kJoinCount && L >= 2 && L <= 6) ? L : 0;
 }
 
-// counts != nullptr: counting launch (writes counts[q]); else: writing launch.
-template <int K>
-static hipError_t launch_join_k(int max_lds_bytes, SUREL_JOIN_PARAMS) {
-    const bool fill = counts == nullptr;
-    const int LT = (fill && m + 1 >= 2 && m + 1 <= 6) ? m + 1 : 0;  // as launch_join_kwf picks
-    const size_t per_wave =
-        (size_t)join_lds_layout(K, max_set, m + 1, fill, join_uses_tile(K, LT)).total * 4;
-#define SUREL_JOIN_CASE(W_)                                                \
-    if (per_wave * (W_) <= (size_t)max_lds_bytes) {                        \
-        if (fill) return launch_join_kwf<K, W_, true>(SUREL_JOIN_ARGS);    \
-        return launch_join_kwf<K, W_, false>(SUREL_JOIN_ARGS);             \
+template <int K, int WPB, JoinMode kMode>
+static hipError_t launch_join_kw(const JoinJob& j) {
+    switch (join_static_len(kMode, j.m + 1)) {
+        case 2: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 2>(j);
+        case 3: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 3>(j);
+        case 4: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 4>(j);
+        case 5: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 5>(j);
+        case 6: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 6>(j);
+        default: return launch_join_cfg<K, WPB, kMode, 0>(j);
     }
-    SUREL_JOIN_CASE(4)
-    SUREL_JOIN_CASE(2)
-    SUREL_JOIN_CASE(1)
-#undef SUREL_JOIN_CASE
+}
+
+template <int K, JoinMode kMode>
+static hipError_t launch_join_k(const JoinJob& j) {
+    const int LT = join_static_len(kMode, j.m + 1);
+    const size_t per_wave = (size_t)join_lds_layout(K, j.max_set, j.m + 1, kMode != kJoinCount,
+                                                    join_uses_tile(K, LT)).total * 4;
+    // as many waves per workgroup as the LDS a wave needs allows
+    if (per_wave * 4 <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 4, kMode>(j);
+    if (per_wave * 2 <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 2, kMode>(j);
+    if (per_wave <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 1, kMode>(j);
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
-                       const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
-                       int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
-                       int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
-                       int32_t* out_ids, uint16_t* out_cnt, uint16_t absent16, uint32_t* err) {
-    if (n_queries == 0) return hipSuccess;
-    if (k == 2) return launch_join_k<2>(max_lds_bytes, SUREL_JOIN_ARGS);
-    if (k == 3) return launch_join_k<3>(max_lds_bytes, SUREL_JOIN_ARGS);
+template <JoinMode kMode>
+static hipError_t launch_join_mode(const JoinJob& j, int32_t k) {
+    if (j.n_queries == 0) return hipSuccess;
+    if (k == 2) return launch_join_k<2, kMode>(j);
+    if (k == 3) return launch_join_k<3, kMode>(j);
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+                             const int32_t* rpe_ids, int64_t n_blocks, int32_t max_set,
+                             const int32_t* queries, int64_t n_queries, int32_t k, int32_t* counts,
+                             uint32_t* err) {
+    JoinJob j{};
+    j.stream = stream, j.max_lds_bytes = max_lds_bytes, j.n_cu = n_cu;
+    j.rpe_off = rpe_off, j.rpe_ids = rpe_ids, j.n_blocks = n_blocks, j.m = 1, j.max_set = max_set;
+    j.queries = queries, j.n_queries = n_queries, j.counts = counts, j.err = err;
+    return launch_join_mode<kJoinCount>(j, k);
+}
+
+hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+                            const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
+                            int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
+                            int32_t k, const int64_t* join_off, int64_t cap_rows, int32_t* out_ids,
+                            uint16_t* out_cnt, uint16_t absent16, uint32_t* err) {
+    JoinJob j{};
+    j.stream = stream, j.max_lds_bytes = max_lds_bytes, j.n_cu = n_cu;
+    j.rpe_off = rpe_off, j.rpe_ids = rpe_ids, j.rpe_cnt = rpe_cnt, j.n_blocks = n_blocks, j.m = m;
+    j.max_set = max_set, j.queries = queries, j.n_queries = n_queries, j.join_off = join_off;
+    j.cap_rows = cap_rows, j.out_ids = out_ids, j.out_cnt = out_cnt, j.absent16 = absent16;
+    j.err = err;
+    return launch_join_mode<kJoinFill>(j, k);
 }
 
 }  // namespace surel

@@ -22,11 +22,10 @@ hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const
 
 // walk_rpe.hip.  Walks and the RPE table in one persistent kernel: writes walks,
 // rpe_off[0..n_seeds] and (unless ids is null) the rows.  lb: device scratch of
-// walk_rpe_lookback_words(n_seeds) 64-bit words (cleared by the launch itself).  n_cu: compute
+// lookback_words(n_seeds) 64-bit words (cleared by the launch itself).  n_cu: compute
 // units of the device.  spin_limit bounds every wait inside the kernel (kDevStall when one runs
-// out).  Needs M*(m+1) <= 2048 and n_seeds >= 1.
+// out; rpe_off[n_seeds] is then -1).  Needs M*(m+1) <= 2048 and n_seeds >= 1.
 // hipErrorInvalidValue = the shape does not fit the device's LDS.
-int64_t walk_rpe_lookback_words(int64_t n_seeds);
 hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* row_ptr,
                            const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
@@ -45,14 +44,20 @@ hipError_t launch_rpe_fill(hipStream_t stream, int max_lds_bytes, const int32_t*
                            const int64_t* rpe_off, int64_t cap_rows, int32_t* ids, uint16_t* cnt,
                            uint32_t* err);
 
-// join.hip.  counts != nullptr: counting launch (counts[q] = union rows of query q);
-// counts == nullptr: writing launch at join_off[q].  absent16: what the entries of a vector
-// hold where a list has no row for the node (0 for counts).
-hipError_t launch_join(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
-                       const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
-                       int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
-                       int32_t k, int32_t* counts, const int64_t* join_off, int64_t cap_rows,
-                       int32_t* out_ids, uint16_t* out_cnt, uint16_t absent16, uint32_t* err);
+// join.hip.  launch_join_count: counts[q] = union rows of query q.  launch_join_fill: writes the
+// rows of every query at join_off[q] (a query whose union does not have join_off[q+1]-join_off[q]
+// rows, or whose rows would pass cap_rows, is skipped and flagged).  absent16: what the entries
+// of a vector hold where a list has no row for the node (0 for counts).
+// hipErrorInvalidValue = the shape does not fit the device's LDS.
+hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+                             const int32_t* rpe_ids, int64_t n_blocks, int32_t max_set,
+                             const int32_t* queries, int64_t n_queries, int32_t k, int32_t* counts,
+                             uint32_t* err);
+hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+                            const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
+                            int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
+                            int32_t k, const int64_t* join_off, int64_t cap_rows, int32_t* out_ids,
+                            uint16_t* out_cnt, uint16_t absent16, uint32_t* err);
 
 // query_ids.hip.  out int32[n_queries][k][M][m+1][k]: for every entry of the walk blocks of a
 // query's k table blocks, the table rows that hold its node in each of the k blocks (-1 where
@@ -99,6 +104,14 @@ hipError_t launch_bfs_batches(hipStream_t stream, int n_cu, const int32_t* queri
                               const int32_t* inc_q, const int32_t* start, int64_t n_batches,
                               int32_t n_start, int32_t B1, int32_t B2, int32_t* vbar, int32_t* batch,
                               int32_t* tuples, int32_t* counts, void* scratch, uint32_t* err);
+
+// scan.hip.  Scratch of the kernels that lay their output out themselves (lookback.h): its
+// size in 64-bit words for n_items seeds or queries, and the small kernel that resets it before
+// such a launch (counters and counts to zero, group bases to "not yet") and presets *total_out,
+// where the scanner will leave the row total, to -1.
+int64_t lookback_words(int64_t n_items);
+hipError_t launch_lookback_clear(hipStream_t stream, uint64_t* lb, int64_t n_items,
+                                 int64_t* total_out);
 
 // scan.hip.  off[0..n] = exclusive prefix sums of counts[0..n-1] (off[n] = total).
 // partials: device scratch of scan_partials_len(n) int64.

@@ -35,11 +35,11 @@ __global__ __launch_bounds__(kRpeWaves* kWave) void rpe_count_kernel(
     bool bad_walk = false;
     for (int t0 = 0; t0 < n_key; t0 += kWave) {
         const int t = t0 + lane;
-        const bool active = t < n_key;
-        int32_t v = active ? __builtin_nontemporal_load(W + t) : 0;
-        if ((uint32_t)v >= (uint32_t)n_nodes) {
+        bool active = t < n_key;
+        const int32_t v = active ? __builtin_nontemporal_load(W + t) : 0;
+        if ((uint32_t)v >= (uint32_t)n_nodes) {  // not a node: flagged and left out
             bad_walk = true;
-            v = 0;
+            active = false;
         }
         n_distinct += distinct_insert(table, slots, (uint32_t)v, active);
     }
@@ -79,13 +79,13 @@ __global__ __launch_bounds__(kWaves* kWave) void rpe_fill_kernel(
     for (int r = 0; r < E; ++r) {
         const int idx = r * kWave + lane;
         if (idx < n_key) {
-            int32_t v = __builtin_nontemporal_load(W + idx);
-            if ((uint32_t)v >= (uint32_t)n_nodes) {
-                bad_walk = true;
-                v = 0;
-            }
+            const int32_t v = __builtin_nontemporal_load(W + idx);
             const uint32_t s = (uint32_t)idx - small_div((uint32_t)idx, magic_L) * (uint32_t)L;
             x[r] = ((uint32_t)v << 4) | s;
+            if ((uint32_t)v >= (uint32_t)n_nodes) {  // not a node: flagged and left out
+                bad_walk = true;
+                x[r] = kPadKey;
+            }
         } else {
             x[r] = kPadKey;
         }

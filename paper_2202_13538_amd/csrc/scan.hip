@@ -3,6 +3,7 @@
 // the tile sums by one workgroup, and a tile-local scan that adds the tile's base.
 #include "device_util.h"
 #include "kernels.h"
+#include "lookback.h"
 
 namespace surel {
 
@@ -99,6 +100,41 @@ __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(const int32_t* 
         run += item[j];
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) off[n] = partials[n_tiles];
+}
+
+// Before a launch that lays its output out itself: counters and counts to zero (the counts that
+// pad the last group to "no rows"), every group base to "not yet", the total to -1.  (A kernel,
+// not a memset, so that the call stays valid under stream capture.)
+__global__ void lookback_clear_kernel(uint64_t* __restrict__ lb, int64_t n_items,
+                                      int64_t* __restrict__ total_out) {
+    const LookbackScratch sc = lookback_scratch(n_items);
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) *total_out = -1;
+    if (t >= sc.total_words) return;
+    uint64_t v = 0ull;
+    if (t >= 2 && t < 2 + sc.base_words) {
+        v = ~0ull;  // -1
+    } else if (t >= 2 + sc.base_words) {
+        const int64_t first = (t - 2 - sc.base_words) * 4;  // first count of this word
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t j = first + q;
+            if (j >= n_items && j < sc.n_groups * kGroup) v |= 1ull << (16 * q);
+        }
+    }
+    lb[t] = v;
+}
+
+int64_t lookback_words(int64_t n_items) {
+    return lookback_scratch(n_items > 0 ? n_items : 0).total_words;
+}
+
+hipError_t launch_lookback_clear(hipStream_t stream, uint64_t* lb, int64_t n_items,
+                                 int64_t* total_out) {
+    const int64_t n_clear = lookback_scratch(n_items).total_words;
+    hipLaunchKernelGGL(lookback_clear_kernel, dim3((unsigned)((n_clear + 255) / 256)), dim3(256), 0,
+                       stream, lb, n_items, total_out);
+    return hipGetLastError();
 }
 
 int64_t scan_partials_len(int64_t n) { return (n + kScanTile - 1) / kScanTile + 1; }

@@ -363,6 +363,112 @@ def test_join_queries_argument_checks(lib, kw, want):
     assert lib.surel_join_queries(*join_args(**kw)) == want
 
 
+def rpe_count_args(**kw):
+    a = dict(ctx=NULL, walks=P, n_seeds=10, M=50, m=4, n_nodes=100, sizes=NULL, off=P, h_rows=NULL)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "walks", "n_seeds", "M", "m", "n_nodes", "sizes", "off", "h_rows")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(sizes=P), binding.E_CTX),
+    (dict(M=410, m=4), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(M=0), binding.E_RANGE),
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(n_seeds=-5), binding.E_RANGE),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(walks=NULL, n_seeds=0), binding.E_CTX),
+])
+def test_build_rpe_count_argument_checks(lib, kw, want):
+    assert lib.surel_build_rpe_count(*rpe_count_args(**kw)) == want
+
+
+def rpe_fill_args(**kw):
+    a = dict(ctx=NULL, walks=P, n_seeds=10, M=50, m=4, n_nodes=100, off=P, cap_rows=1000, ids=P,
+             cnt=P)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "walks", "n_seeds", "M", "m", "n_nodes", "off", "cap_rows", "ids",
+                           "cnt")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(M=410, m=4), binding.E_RANGE),
+    (dict(m=0), binding.E_RANGE),
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(off=NULL), binding.E_NULL),             # the offsets are an input here
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(cnt=NULL), binding.E_NULL),
+    (dict(ids=NULL, cnt=NULL, cap_rows=0), binding.E_CTX),   # room for nothing: nothing to write to
+    (dict(cnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
+])
+def test_build_rpe_fill_argument_checks(lib, kw, want):
+    assert lib.surel_build_rpe_fill(*rpe_fill_args(**kw)) == want
+
+
+def join_count_args(**kw):
+    a = dict(ctx=NULL, off=P, ids=P, n_blocks=100, max_set=201, queries=P, n_q=10, k=2, joff=P,
+             h_rows=NULL)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "off", "ids", "n_blocks", "max_set", "queries", "n_q", "k", "joff",
+                           "h_rows")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(k=3), binding.E_CTX),
+    (dict(k=1), binding.E_RANGE),
+    (dict(k=4), binding.E_RANGE),
+    (dict(max_set=0), binding.E_RANGE),
+    (dict(max_set=binding.MAX_SET + 1), binding.E_RANGE),
+    (dict(n_blocks=-1), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(joff=NULL), binding.E_NULL),
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(queries=NULL, off=NULL, ids=NULL, n_q=0), binding.E_CTX),
+])
+def test_join_count_argument_checks(lib, kw, want):
+    assert lib.surel_join_count(*join_count_args(**kw)) == want
+
+
+def join_fill_args(**kw):
+    a = dict(ctx=NULL, off=P, ids=P, cnt=P, n_blocks=100, m=4, max_set=201, queries=P, n_q=10, k=2,
+             joff=P, cap_rows=1000, jids=P, jcnt=P)
+    a.update(kw)
+    return [a[k] for k in ("ctx", "off", "ids", "cnt", "n_blocks", "m", "max_set", "queries", "n_q",
+                           "k", "joff", "cap_rows", "jids", "jcnt")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(k=3), binding.E_CTX),
+    (dict(k=1), binding.E_RANGE),
+    (dict(m=0), binding.E_RANGE),
+    (dict(m=16), binding.E_RANGE),
+    (dict(max_set=0), binding.E_RANGE),
+    (dict(n_blocks=-1), binding.E_RANGE),
+    (dict(n_q=-1), binding.E_RANGE),
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(joff=NULL), binding.E_NULL),            # the offsets are an input here
+    (dict(queries=NULL), binding.E_NULL),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(cnt=NULL), binding.E_NULL),
+    (dict(jids=NULL), binding.E_NULL),
+    (dict(jcnt=NULL), binding.E_NULL),
+    (dict(cnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
+    (dict(jcnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
+])
+def test_join_fill_argument_checks(lib, kw, want):
+    assert lib.surel_join_fill(*join_fill_args(**kw)) == want
+
+
 def test_check_and_destroy_tolerate_null(lib):
     assert lib.surel_check(NULL, NULL) == binding.E_CTX
     assert lib.surel_profile_enable(NULL, 1) == binding.E_CTX

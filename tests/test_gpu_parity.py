@@ -534,3 +534,129 @@ def test_join_problems_are_flagged(ctx):
     assert ctx.check() == binding.DEV_CAPACITY
     assert np.array_equal(jids.cpu().numpy()[:cap], want[1][:cap])
     assert (jids.cpu().numpy()[cap:] == -7).all()
+
+
+# --------------------------------------------------------------------------- #
+# the two phases as calls of their own: size, allocate, fill
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("M,m,k", [(50, 4, 2), (200, 3, 3), (33, 2, 2), (20, 7, 3)])
+def test_count_then_fill_calls_against_the_oracle(ctx, M, m, k):
+    wl = synth.Workload("t", "rmat", 2048, 12000, 0.0, M, m, 0, k, "uniform", graph_seed=21)
+    rp, ci = synth.make_graph(wl)
+    rng = np.random.default_rng(M + m)
+    seeds = rng.integers(0, wl.n_nodes, size=777).astype(np.int32)
+    queries = rng.integers(0, seeds.size, size=(1501, k)).astype(np.int32)
+    L = m + 1
+    w = oracle.sample_walks(rp, ci, seeds, M, m, 9)
+    table = oracle.build_rpe(w)
+    joined = oracle.join_queries(*table, queries)
+
+    walks = binding.sample_walks(ctx, dev(rp), dev(ci), dev(seeds), M, m, 9)
+    off = torch.empty(seeds.size + 1, dtype=torch.int64, device="cuda")
+    rc, R = binding.build_rpe_count(ctx, walks, wl.n_nodes, off)
+    assert rc == binding.OK and R == table[1].size
+    assert np.array_equal(off.cpu().numpy(), table[0])
+    ids = torch.empty(R, dtype=torch.int32, device="cuda")
+    cnt = torch.empty((R, L), dtype=torch.uint16, device="cuda")
+    kept = off.clone()
+    assert binding.build_rpe_fill(ctx, walks, wl.n_nodes, off, R, ids, cnt) == binding.OK
+    assert ctx.check() == 0
+    assert torch.equal(off, kept), "the filling call changed the offsets it was given"
+    assert_table_equal((off, ids, cnt), table, "rpe by count + fill")
+
+    d_q = dev(queries)
+    joff = torch.empty(queries.shape[0] + 1, dtype=torch.int64, device="cuda")
+    rc, J = binding.join_count(ctx, off, ids, d_q, 1 + M * m, joff)
+    assert rc == binding.OK and J == joined[1].size
+    jids = torch.empty(J, dtype=torch.int32, device="cuda")
+    jcnt = torch.empty((J, k, L), dtype=torch.uint16, device="cuda")
+    kept = joff.clone()
+    assert binding.join_fill(ctx, off, ids, cnt, d_q, 1 + M * m, joff, J, jids, jcnt) == binding.OK
+    assert ctx.check() == 0
+    assert torch.equal(joff, kept)
+    assert_table_equal((joff, jids, jcnt), joined, "join by count + fill")
+    # offsets kept from an earlier call fill again without any counting
+    jids.fill_(-7)
+    assert binding.join_fill(ctx, off, ids, cnt, d_q, 1 + M * m, joff, J, jids, jcnt) == binding.OK
+    assert ctx.check() == 0
+    assert np.array_equal(jids.cpu().numpy(), joined[1])
+
+
+def test_fill_calls_with_offsets_of_something_else_are_flagged(ctx):
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(40, dtype=np.int32)
+    walks, off, ids, cnt = binding.sample_walks_rpe(ctx, dev(rp), dev(ci), dev(seeds), wl.M, wl.m, 0)
+    table = oracle.build_rpe(walks.cpu().numpy())
+    q = np.array([[1, 2], [3, 4], [5, 6], [7, 8]], dtype=np.int32)
+    want = oracle.join_queries(*table, q)
+    joff = torch.from_numpy(want[0].copy()).cuda()
+    joff[2:] += 2                                      # query 1 is given two rows too many
+    total = int(joff[-1])
+    jids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    jcnt = torch.zeros((total, 2, 4), dtype=torch.int16, device="cuda").view(torch.uint16)
+    assert binding.join_fill(ctx, off, ids, cnt, dev(q), 61, joff, total, jids, jcnt) == binding.OK
+    assert ctx.check() == binding.DEV_BAD_SIZES
+    got = jids.cpu().numpy()
+    lo, hi = int(want[0][1]), int(want[0][2]) + 2
+    assert (got[lo:hi] == -7).all()                    # the mismatched query wrote nothing
+    assert np.array_equal(got[:lo], want[1][:lo])      # the others are where the offsets put them
+    assert np.array_equal(got[hi:], want[1][int(want[0][2]):])
+    # the same for the table's rows
+    roff = torch.from_numpy(table[0].copy()).cuda()
+    roff[6:] += 1
+    total = int(roff[-1])
+    rids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    rcnt = torch.zeros((total, 4), dtype=torch.int16, device="cuda").view(torch.uint16)
+    assert binding.build_rpe_fill(ctx, walks, wl.n_nodes, roff, total, rids, rcnt) == binding.OK
+    assert ctx.check() == binding.DEV_BAD_SIZES
+    got = rids.cpu().numpy()
+    lo, hi = int(table[0][5]), int(table[0][6]) + 1
+    assert (got[lo:hi] == -7).all()
+    assert np.array_equal(got[:lo], table[1][:lo]) and np.array_equal(got[hi:], table[1][int(table[0][6]):])
+
+
+def test_bad_seeds_give_the_same_table_on_both_paths(ctx):
+    # a seed that is not a node gets walks of -1 and no rows, whether the table is built by the
+    # fused kernel or by surel_build_rpe over those walks
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(50, dtype=np.int32)
+    seeds[[0, 17, 49]] = [-1, 256, 1 << 30]
+    good = np.ones(50, dtype=bool)
+    good[[0, 17, 49]] = False
+    d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(seeds)
+    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, d_seeds, wl.M, wl.m, 2)
+    assert ctx.check() == binding.DEV_BAD_SEED
+    for sizes in (None, torch.empty(50, dtype=torch.int32, device="cuda")):
+        walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, wl.M, wl.m, 2, set_sizes=sizes)
+        assert ctx.check() == binding.DEV_BAD_SEED
+        off, ids, cnt = binding.build_rpe(ctx, walks, wl.n_nodes, set_sizes=sizes)
+        assert ctx.check() == binding.DEV_BAD_WALK          # the -1 entries are left out, and said so
+        assert torch.equal(walks, f_walks) and torch.equal(off, f_off) and torch.equal(ids, f_ids)
+        assert torch.equal(cnt.view(torch.int16), f_cnt.view(torch.int16))
+    w = oracle.sample_walks(rp, ci, seeds[good], wl.M, wl.m, 2)
+    t_off, t_ids, t_cnt = oracle.build_rpe(w)
+    sizes_h = np.zeros(50, dtype=np.int64)
+    sizes_h[good] = np.diff(t_off)
+    assert np.array_equal(f_off.cpu().numpy(), np.concatenate([[0], np.cumsum(sizes_h)]))
+    assert np.array_equal(f_ids.cpu().numpy(), t_ids) and np.array_equal(host_u16(f_cnt), t_cnt)
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_join_query_counts_around_workgroup_and_scan_tile_sizes(ctx, k):
+    # 4 waves a workgroup, 2048 counts per tile of the offset scan: query counts on and around
+    # those sizes against the oracle
+    wl = synth.Workload("t", "rmat", 2048, 12000, 0.0, 50, 4, 0, k, "uniform", graph_seed=5)
+    rp, ci = synth.make_graph(wl)
+    seeds = np.arange(wl.n_nodes, dtype=np.int32)
+    walks, off, ids, cnt = binding.sample_walks_rpe(ctx, dev(rp), dev(ci), dev(seeds), wl.M, wl.m, 4)
+    table = oracle.build_rpe(walks.cpu().numpy())
+    rng = np.random.default_rng(k)
+    all_q = rng.integers(0, wl.n_nodes, size=(20000, k)).astype(np.int32)
+    for n in (1, 2, 7, 8, 9, 15, 16, 17, 31, 33, 64, 2047, 2048, 2049, 4104, 16391, 20000):
+        want = oracle.join_queries(*table, all_q[:n])
+        got = binding.join_queries(ctx, off, ids, cnt, dev(all_q[:n]), max_set=201,
+                                   cap_rows=int(want[0][-1]) + 5)
+        assert ctx.check() == 0
+        assert_table_equal(got, want, f"join of {n} queries")
