@@ -109,6 +109,7 @@ extern "C" {
 #define SUREL_MAX_TUPLE   3           /* join: k                                             */
 #define SUREL_MAX_DISTINCT 16777216   /* prune: cap_T (2^24 distinct count vectors)          */
 #define SUREL_MAX_BATCH   1048576     /* mini-batching: B1, B2 and the seed-set size (2^20)   */
+#define SUREL_NOALLOC_MAX_QUERIES 1048576  /* surel_join_queries_noalloc: n_queries (2^20)    */
 
 /* kernel groups for surel_profile_read */
 #define SUREL_K_WALK        0   /* walk kernel                                        */
@@ -257,6 +258,23 @@ int surel_join_fill(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_r
                     const int32_t* d_queries, int64_t n_queries, int32_t k,
                     const int64_t* d_join_off, int64_t cap_rows, int32_t* d_join_ids,
                     uint16_t* d_join_cnt);
+
+/* surel_join_queries for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * byte for byte, but the call never allocates or frees anything (no hipMalloc, no hipFree, no
+ * event creation: its launches are not timed by surel_profile_enable): its device scratch (one
+ * int32 per query and the partial sums of their scan) is a static array inside the library, 4 MiB
+ * + 8 KiB that every device the library runs on holds until the process ends, instead of the
+ * context's grow-only workspace.  Hence n_queries <= SUREL_NOALLOC_MAX_QUERIES (SUREL_E_RANGE
+ * beyond).  All calls on one device share that array, whichever context they use: calls that
+ * overlap on one device (two streams, two host threads) race on it and give wrong rows; calls
+ * one after the other on the same stream are safe, and nothing in the array needs clearing
+ * between them (every word a call reads it has written itself). */
+int surel_join_queries_noalloc(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                               const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m,
+                               int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                               int32_t k, int64_t cap_rows, int64_t* d_join_off,
+                               int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows);
 
 /* surel_join_queries with RPE-IDs instead of RPE values (Sec. 3.3: "the table carries RPE-IDs";
  * Sec. 3.4's closing remarks on shipping IDs instead of values): the same union rows, and for

@@ -22,6 +22,7 @@ MAX_NODES, MAX_STEPS, MAX_WALKS = 268435455, 15, 65535
 MAX_WALK_ENTRIES, MAX_SET, MAX_TUPLE = 2048, 2048, 3
 MAX_DISTINCT = 1 << 24
 MAX_BATCH = 1 << 20
+NOALLOC_MAX_QUERIES = 1 << 20
 
 (K_WALK, K_RPE_COUNT, K_RPE_FILL, K_JOIN_COUNT, K_JOIN_FILL, K_SCAN, K_WALK_RPE,
  K_EDGE_RECORDS, K_QUERY_IDS, K_PRUNE, K_BATCH, K_COUNT) = range(12)
@@ -51,6 +52,8 @@ SIGNATURES = {
                                               ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
+    "surel_join_queries_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64,
+                                                  _i32, _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_join_count": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _vp,
                                         ctypes.POINTER(_i64)]),
     "surel_join_fill": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp,
@@ -299,12 +302,15 @@ def sample_walks_rpe(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
 def join_queries_raw(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,
                      rpe_cnt: torch.Tensor, queries: torch.Tensor, max_set: int, cap_rows: int,
                      join_off: torch.Tensor, join_ids: torch.Tensor | None,
-                     join_cnt: torch.Tensor | None, want_rows: bool = True):
-    """One call of surel_join_queries into caller buffers.  Returns (status, rows or None)."""
+                     join_cnt: torch.Tensor | None, want_rows: bool = True, noalloc: bool = False):
+    """One call of surel_join_queries (noalloc: of surel_join_queries_noalloc, which takes its
+    device scratch from a static array inside the library) into caller buffers.  Returns
+    (status, rows or None)."""
     n_q, k = queries.shape
     L = rpe_cnt.shape[1]
     rows = _i64(-1)
-    rc = load().surel_join_queries(
+    fn = load().surel_join_queries_noalloc if noalloc else load().surel_join_queries
+    rc = fn(
         ctx.handle, _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
         _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), rpe_off.numel() - 1, L - 1, max_set,
         _ptr(queries, torch.int32, "queries"), n_q, k, cap_rows,

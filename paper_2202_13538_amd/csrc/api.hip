@@ -27,6 +27,8 @@ struct surel_ctx {
     size_t prune_bytes = 0;
     void* d_batch = nullptr;      // grow-only workspace: sort arrays of the incidence lists, hash
     size_t batch_bytes = 0;       // tables of the mini-batch search
+    void* d_scratch = nullptr;    // this device's copy of the file-scope `scratch` array below
+    bool no_spans = false;        // set while a call that must not allocate runs (no new events)
     // optional per-kernel timing (surel_profile_*)
     struct Span {
         int kernel;
@@ -38,6 +40,16 @@ struct surel_ctx {
     double prof_ms[SUREL_K_COUNT] = {};
     int64_t prof_launches[SUREL_K_COUNT] = {};
 };
+
+// Scratch of surel_join_queries_noalloc: a file-scope device array instead of a workspace from
+// hipMalloc, so that the call allocates nothing.  It holds the queries' row counts (int32 each)
+// and, behind them, the partial sums of their scan.  Every device that runs the library holds
+// its own copy until the process ends.  Host code never takes the array's name for an address:
+// surel_create asks hipGetSymbolAddress for the current device's copy and keeps that pointer in
+// the context.
+constexpr size_t kScratchCountsBytes = (size_t)SUREL_NOALLOC_MAX_QUERIES * sizeof(int32_t);
+constexpr size_t kScratchBytes = kScratchCountsBytes + 8192;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -64,7 +76,7 @@ bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) !
 class KernelSpan {
   public:
     KernelSpan(surel_ctx* ctx, int kernel) : ctx_(ctx) {
-        if (!ctx->profiling) return;
+        if (!ctx->profiling || ctx->no_spans) return;
         span_.kernel = kernel;
         span_.start = take();
         span_.stop = take();
@@ -214,6 +226,9 @@ int surel_create(surel_ctx** out, int device, void* hip_stream) {
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 2 * sizeof(int64_t),
                              hipHostMallocDefault) == hipSuccess;
     ok = ok && hipStreamSynchronize(ctx->stream) == hipSuccess;
+    // where THIS device keeps its copy of the static scratch array (the device is current here)
+    ok = ok && hipGetSymbolAddress(&ctx->d_scratch, HIP_SYMBOL(scratch)) == hipSuccess &&
+         ctx->d_scratch != nullptr;
     if (!ok) {
         if (ctx->d_err) (void)hipFree(ctx->d_err);
         if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
@@ -585,6 +600,37 @@ int surel_join_queries(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* 
                        int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows) {
     return join_checked(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
                         n_queries, k, cap_rows, d_join_off, d_join_ids, d_join_cnt, 0, h_rows);
+}
+
+int surel_join_queries_noalloc(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,
+                               const uint16_t* d_rpe_cnt, int64_t n_blocks, int32_t m,
+                               int32_t max_set, const int32_t* d_queries, int64_t n_queries,
+                               int32_t k, int64_t cap_rows, int64_t* d_join_off,
+                               int32_t* d_join_ids, uint16_t* d_join_cnt, int64_t* h_rows) {
+    if (int rc = check_whole_join(ctx, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set,
+                                  d_queries, n_queries, k, cap_rows, d_join_off, d_join_ids,
+                                  d_join_cnt))
+        return rc;
+    if (n_queries > SUREL_NOALLOC_MAX_QUERIES) return SUREL_E_RANGE;
+    static_assert(kScratchBytes >= kScratchCountsBytes +
+                      (SUREL_NOALLOC_MAX_QUERIES / 2048 + 2) * sizeof(int64_t),
+                  "the scan's partials must fit behind the counts");
+    if ((size_t)surel::scan_partials_len(n_queries) * sizeof(int64_t) >
+        kScratchBytes - kScratchCountsBytes)
+        return SUREL_E_RANGE;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    // the device's static array through the pointer that surel_create looked up, never through
+    // the array's name; every word the kernels read from it they have written in this call
+    JoinScratch ws;
+    ws.counts = static_cast<int32_t*>(ctx->d_scratch);
+    ws.partials = reinterpret_cast<int64_t*>(static_cast<char*>(ctx->d_scratch) + kScratchCountsBytes);
+    ctx->no_spans = true;  // timing a launch would create events
+    const int rc = join_vectors(ctx, ws, d_rpe_off, d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set,
+                                d_queries, n_queries, k, cap_rows, d_join_off, d_join_ids,
+                                d_join_cnt, 0, h_rows);
+    ctx->no_spans = false;
+    return rc;
 }
 
 int surel_join_query_ids(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_rpe_ids,

@@ -66,6 +66,7 @@ def test_header_constants_match_binding():
     assert val["SUREL_MAX_DISTINCT"] == binding.MAX_DISTINCT
     assert val["SUREL_MAX_BATCH"] == binding.MAX_BATCH
     assert val["SUREL_DEV_STALL"] == binding.DEV_STALL
+    assert val["SUREL_NOALLOC_MAX_QUERIES"] == binding.NOALLOC_MAX_QUERIES
 
 
 def test_strerror_and_bound(lib):
@@ -361,6 +362,15 @@ def join_args(**kw):
 ])
 def test_join_queries_argument_checks(lib, kw, want):
     assert lib.surel_join_queries(*join_args(**kw)) == want
+    # the variant that allocates nothing checks the same arguments the same way
+    assert lib.surel_join_queries_noalloc(*join_args(**kw)) == want
+
+
+def test_join_queries_noalloc_rejects_more_queries_than_its_static_scratch_holds(lib):
+    ctx = ctypes.c_void_p(0x2000)      # never dereferenced: the size check comes first
+    too_many = binding.NOALLOC_MAX_QUERIES + 1
+    assert lib.surel_join_queries_noalloc(*join_args(ctx=ctx, n_q=too_many)) == binding.E_RANGE
+    assert lib.surel_join_queries_noalloc(*join_args(n_q=binding.NOALLOC_MAX_QUERIES)) == binding.E_CTX
 
 
 def rpe_count_args(**kw):
