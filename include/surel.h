@@ -10,7 +10,8 @@
  *   surel_join_queries   per query tuple Q, the union of the V_u, u in Q, and for each
  *                        node x of it the query-level RPE X_{Q,x} = [X_{u,x}]_{u in Q},
  *                        zeros where x is not in V_u (Sec. 3.4, set-union form).
- * Beside them: surel_sample_walks_rpe (the first two in one kernel), surel_query_rpe_ids
+ * Beside them: surel_sample_walks_rpe (the first two in one kernel; surel_sample_walks_rpe_ids:
+ * with the pruning of Sec. 3.3 as well, so that table rows carry RPE-IDs), surel_query_rpe_ids
  * (Sec. 3.4's per-walk-position form of the join: RPE-IDs instead of RPE values),
  * surel_prune_rpe (Sec. 3.3: the distinct count vectors stored once, rows re-indexed),
  * surel_join_query_ids (the union join over those RPE-IDs), and
@@ -221,6 +222,31 @@ int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32
                            int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
                            int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
                            int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows);
+
+/* Algorithm 1 from end to end in one call: walks, RPE and the pruning of the central array
+ * (Sec. 3.2 "computed on the fly as walks get sampled"; Sec. 3.3 "the table carries RPE-IDs";
+ * Algorithm 1's last step).  The fused kernel of surel_sample_walks_rpe also looks every
+ * finished row's count vector up in the set of distinct vectors while the row is still on
+ * chip, so the table never has to be read back to prune it.  Results: exactly those of
+ * surel_sample_walks_rpe followed by surel_prune_rpe on its d_rpe_cnt.
+ *   d_walks, cap_rows, d_rpe_off, d_rpe_ids   as in surel_sample_walks_rpe (ids required unless
+ *                cap_rows is 0).
+ *   d_rpe_cnt    uint16[cap_rows][m+1] (device, written), or NULL: the table then carries
+ *                RPE-IDs only (4 bytes a row instead of 2(m+1)), the count vectors live in d_T.
+ *   d_code       int32[cap_rows] (device, written): d_T[d_code[r]] is row r's count vector.
+ *   cap_T, d_T   as in surel_prune_rpe: uint16[cap_T][m+1], the distinct vectors, sorted.
+ *   h_rows, h_n_T   host int64, both required: table rows and distinct vectors.  The call always
+ *                waits for its own work.
+ * Returns SUREL_E_CAPACITY when the table needs more than cap_rows rows or has more than cap_T
+ * distinct vectors (*h_rows / *h_n_T say how many; d_T and d_code are then undefined),
+ * SUREL_E_DEVICE when a bounded wait ran out.  Limits and device-detected problems: those of
+ * surel_sample_walks_rpe and surel_prune_rpe. */
+int surel_sample_walks_rpe_ids(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                               int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                               int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                               int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
+                               int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int32_t* d_code,
+                               int64_t cap_T, uint16_t* d_T, int64_t* h_rows, int64_t* h_n_T);
 
 /* Sec. 3.4, set-union form: for every query q with tuple (b_1..b_k) of table blocks, the
  * ascending union of the blocks' id lists and, per union node x and j < k, block b_j's count

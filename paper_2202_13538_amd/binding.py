@@ -50,6 +50,9 @@ SIGNATURES = {
     "surel_sample_walks_rpe": (ctypes.c_int, [_vp, _vp, _vp, _i32, _i64, _vp, _i64, _i32, _i32,
                                               _u64, _vp, _i64, _vp, _vp, _vp,
                                               ctypes.POINTER(_i64)]),
+    "surel_sample_walks_rpe_ids": (ctypes.c_int, [_vp, _vp, _vp, _i32, _i64, _vp, _i64, _i32, _i32,
+                                                  _u64, _vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp,
+                                                  ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
     "surel_join_queries": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64, _i32,
                                           _i64, _vp, _vp, _vp, ctypes.POINTER(_i64)]),
     "surel_join_queries_noalloc": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i64,
@@ -297,6 +300,47 @@ def sample_walks_rpe(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
     if rc != OK:
         raise SurelError(rc, "surel_sample_walks_rpe")
     return walks, off, ids[:rows], cnt[:rows]
+
+
+def sample_walks_rpe_ids_raw(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                             seeds: torch.Tensor, M: int, m: int, rng_seed: int,
+                             walks: torch.Tensor, cap_rows: int, rpe_off: torch.Tensor,
+                             rpe_ids: torch.Tensor, rpe_cnt: torch.Tensor | None,
+                             code: torch.Tensor, cap_T: int, T: torch.Tensor):
+    """One call of surel_sample_walks_rpe_ids into caller buffers.  Returns (status, rows, n_T)."""
+    n_seeds = seeds.numel()
+    if walks.numel() != n_seeds * M * (m + 1):
+        raise ValueError("walks has the wrong size")
+    rows, n_T = _i64(-1), _i64(-1)
+    rc = load().surel_sample_walks_rpe_ids(
+        ctx.handle, _ptr(row_ptr, torch.int32, "row_ptr"), _ptr(col_idx, torch.int32, "col_idx"),
+        row_ptr.numel() - 1, col_idx.numel(), _ptr(seeds, torch.int32, "seeds"), n_seeds, M, m,
+        _u64(rng_seed), _ptr(walks, torch.int32, "walks"), cap_rows,
+        _ptr(rpe_off, torch.int64, "rpe_off"), _ptr(rpe_ids, torch.int32, "rpe_ids"),
+        _ptr(rpe_cnt, torch.uint16, "rpe_cnt"), _ptr(code, torch.int32, "code"), cap_T,
+        _ptr(T, torch.uint16, "T"), ctypes.byref(rows), ctypes.byref(n_T))
+    return rc, rows.value, n_T.value
+
+
+def sample_walks_rpe_ids(ctx: Context, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                         seeds: torch.Tensor, M: int, m: int, rng_seed: int = 0,
+                         cap_T: int = 1 << 20, with_counts: bool = True):
+    """(walks, rpe_off, rpe_ids, rpe_cnt or None, code, T): walks, RPE table and pruned array from
+    one call (Algorithm 1 from end to end); rows carry T's index of their count vector."""
+    n_seeds = seeds.numel()
+    dev = row_ptr.device
+    walks = torch.empty((n_seeds, M, m + 1), dtype=torch.int32, device=dev)
+    cap_rows = rpe_rows_bound(n_seeds, M, m)
+    off = torch.empty(n_seeds + 1, dtype=torch.int64, device=dev)
+    ids = torch.empty(cap_rows, dtype=torch.int32, device=dev)
+    cnt = torch.empty((cap_rows, m + 1), dtype=torch.uint16, device=dev) if with_counts else None
+    code = torch.empty(cap_rows, dtype=torch.int32, device=dev)
+    T = torch.empty((cap_T, m + 1), dtype=torch.uint16, device=dev)
+    rc, rows, n_T = sample_walks_rpe_ids_raw(ctx, row_ptr, col_idx, seeds, M, m, rng_seed, walks,
+                                             cap_rows, off, ids, cnt, code, cap_T, T)
+    if rc != OK:
+        raise SurelError(rc, "surel_sample_walks_rpe_ids")
+    return walks, off, ids[:rows], (cnt[:rows] if with_counts else None), code[:rows], T[:n_T]
 
 
 def join_queries_raw(ctx: Context, rpe_off: torch.Tensor, rpe_ids: torch.Tensor,

@@ -1,8 +1,9 @@
 """Builds libsurel.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
 ``python -m paper_2202_13538_amd.build`` compiles every source under ``csrc/`` and links
-``paper_2202_13538_amd/libsurel.so``.  hipcc cross-compiles for gfx950, so no GPU is needed
-to build.
+``paper_2202_13538_amd/libsurel.so``, then the memory-system micro-benchmarks of
+``membench/`` into ``libsurel_membench.so`` (benchmark tooling that ``bench.py --membench``
+loads; the hot path does not).  hipcc cross-compiles for gfx950, so no GPU is needed to build.
 """
 from __future__ import annotations
 
@@ -14,6 +15,8 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsurel.so")
+MEMBENCH_SRC = os.path.join(PKG_DIR, "membench", "membench.hip")
+MEMBENCH_LIB_PATH = os.path.join(PKG_DIR, "libsurel_membench.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -43,21 +46,31 @@ def _compile(src: str, extra: list[str]) -> str:
     return obj
 
 
-def build(extra_flags: list[str] | None = None, verbose: bool = False) -> str:
-    """Compile and link unconditionally.  Returns the library path."""
-    os.makedirs(BUILD_DIR, exist_ok=True)
-    extra = list(extra_flags or [])
-    srcs = sources()
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
-        objs = list(pool.map(lambda s: _compile(s, extra), srcs))
-    tmp = LIB_PATH + f".tmp{os.getpid()}"
+def _link(objs: list[str], lib_path: str) -> None:
+    tmp = lib_path + f".tmp{os.getpid()}"
     cmd = [HIPCC, "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
-    os.replace(tmp, LIB_PATH)
+    os.replace(tmp, lib_path)
+
+
+def build(extra_flags: list[str] | None = None, verbose: bool = False) -> str:
+    """Compile and link unconditionally.  Returns the path of libsurel.so."""
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    extra = list(extra_flags or [])
+    srcs = sources()
+    all_srcs = srcs + [MEMBENCH_SRC]
+    wanted = {os.path.basename(s) + ".o" for s in all_srcs}
+    for f in os.listdir(BUILD_DIR):           # objects of sources that no longer exist
+        if f.endswith(".o") and f not in wanted:
+            os.remove(os.path.join(BUILD_DIR, f))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(all_srcs))) as pool:
+        objs = list(pool.map(lambda s: _compile(s, extra), all_srcs))
+    _link(objs[:-1], LIB_PATH)
+    _link(objs[-1:], MEMBENCH_LIB_PATH)
     if verbose:
-        print(f"built {LIB_PATH} from {len(srcs)} sources")
+        print(f"built {LIB_PATH} from {len(srcs)} sources, {MEMBENCH_LIB_PATH} from 1")
     return LIB_PATH
 
 

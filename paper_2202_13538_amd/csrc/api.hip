@@ -402,47 +402,140 @@ int surel_build_rpe(surel_ctx* ctx, const int32_t* d_walks, int64_t n_seeds, int
     return SUREL_OK;
 }
 
-int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
-                           int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
-                           int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
-                           int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
-                           int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows) {
+// Argument checks shared by the two fused walk + RPE calls.
+static int check_fused_args(const int32_t* d_row_ptr, const int32_t* d_col_idx, int32_t n_nodes,
+                            int64_t n_edges, const int32_t* d_seeds, int64_t n_seeds, int32_t M,
+                            int32_t m, const int32_t* d_walks, int64_t cap_rows,
+                            const int64_t* d_rpe_off) {
     if (int rc = check_walk_shape(n_nodes, n_seeds, M, m)) return rc;
     if (n_edges < 0 || n_edges > 0x7FFFFFFFll) return SUREL_E_RANGE;
     if ((int64_t)M * (m + 1) > SUREL_MAX_WALK_ENTRIES) return SUREL_E_RANGE;
     if (cap_rows < 0) return SUREL_E_RANGE;
     if (!d_row_ptr || (n_edges > 0 && !d_col_idx) || !d_rpe_off) return SUREL_E_NULL;
     if (n_seeds > 0 && (!d_seeds || !d_walks)) return SUREL_E_NULL;
-    if ((d_rpe_ids == nullptr) != (d_rpe_cnt == nullptr)) return SUREL_E_NULL;
-    if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
-    if (!ctx) return SUREL_E_CTX;
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return SUREL_E_HIP;
-    if (n_seeds == 0) {  // rpe_off[0] = 0, by the scan's own kernels (valid under stream capture)
-        int32_t* counts = nullptr;
-        int64_t* partials = nullptr;
-        if (int rc = ensure_workspace(ctx, 0, &counts, &partials)) return rc;
-        if (surel::launch_exclusive_scan(ctx->stream, counts, 0, d_rpe_off, partials) != hipSuccess)
-            return SUREL_E_HIP;
-        if (h_rows) return read_total(ctx, d_rpe_off, 0, h_rows);
-        return SUREL_OK;
-    }
+    return SUREL_OK;
+}
+
+// The fused kernel (n_seeds >= 1): edge records if the job wants them, look-back scratch, launch.
+// code / slots / counters: the hash set of distinct count vectors, or null.
+static int fused_launch(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                        int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds, int64_t n_seeds,
+                        int32_t M, int32_t m, uint64_t rng_seed, int32_t* d_walks, int64_t cap_rows,
+                        int64_t* d_rpe_off, int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int32_t* d_code,
+                        uint32_t* slots, int64_t cap_T, unsigned long long* counters) {
     void* records = nullptr;
     if (int rc = make_edge_records(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, n_seeds, M, m,
                                    &records))
         return rc;
     const size_t lb_need = (size_t)surel::lookback_words(n_seeds) * sizeof(uint64_t);
     if (int rc = grow_buffer(ctx, &ctx->d_lb, &ctx->lb_bytes, lb_need)) return rc;
-    {
-        KernelSpan span(ctx, SUREL_K_WALK_RPE);
-        hipError_t hrc = surel::launch_walk_rpe(
-            ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_row_ptr, d_col_idx, n_nodes, n_edges,
-            d_seeds, n_seeds, M, m, rng_seed, d_walks, cap_rows, d_rpe_off, d_rpe_ids, d_rpe_cnt,
-            records, static_cast<uint64_t*>(ctx->d_lb), ctx->spin_limit, ctx->d_err);
-        if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
-        if (hrc != hipSuccess) return SUREL_E_HIP;
+    KernelSpan span(ctx, SUREL_K_WALK_RPE);
+    hipError_t hrc = surel::launch_walk_rpe(
+        ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_row_ptr, d_col_idx, n_nodes, n_edges, d_seeds,
+        n_seeds, M, m, rng_seed, d_walks, cap_rows, d_rpe_off, d_rpe_ids, d_rpe_cnt, records,
+        static_cast<uint64_t*>(ctx->d_lb), ctx->spin_limit, ctx->d_err, d_code, slots, cap_T,
+        counters);
+    if (hrc == hipErrorInvalidValue) return SUREL_E_RANGE;
+    return hrc == hipSuccess ? SUREL_OK : SUREL_E_HIP;
+}
+
+// rpe_off[0] = 0 of an empty seed list, by the scan's own kernels (valid under stream capture).
+static int empty_table(surel_ctx* ctx, int64_t* d_rpe_off) {
+    int32_t* counts = nullptr;
+    int64_t* partials = nullptr;
+    if (int rc = ensure_workspace(ctx, 0, &counts, &partials)) return rc;
+    if (surel::launch_exclusive_scan(ctx->stream, counts, 0, d_rpe_off, partials) != hipSuccess)
+        return SUREL_E_HIP;
+    return SUREL_OK;
+}
+
+int surel_sample_walks_rpe(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                           int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                           int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                           int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
+                           int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int64_t* h_rows) {
+    if (int rc = check_fused_args(d_row_ptr, d_col_idx, n_nodes, n_edges, d_seeds, n_seeds, M, m,
+                                  d_walks, cap_rows, d_rpe_off))
+        return rc;
+    if ((d_rpe_ids == nullptr) != (d_rpe_cnt == nullptr)) return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    if (n_seeds == 0) {
+        if (int rc = empty_table(ctx, d_rpe_off)) return rc;
+    } else if (int rc = fused_launch(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, d_seeds, n_seeds,
+                                     M, m, rng_seed, d_walks, cap_rows, d_rpe_off, d_rpe_ids,
+                                     d_rpe_cnt, nullptr, nullptr, 0, nullptr)) {
+        return rc;
     }
     if (h_rows) return report_total(ctx, d_rpe_off, n_seeds, d_rpe_ids != nullptr, cap_rows, h_rows);
+    return SUREL_OK;
+}
+
+// The scratch of the pruning calls inside the context's workspace.
+struct PruneScratch {
+    uint32_t* slots;
+    uint32_t* list;
+    unsigned long long* counters;
+};
+static int prune_scratch(surel_ctx* ctx, int64_t cap_T, PruneScratch* out) {
+    const size_t slot_bytes = surel::prune_slot_bytes(cap_T);
+    const size_t list_bytes = align_up(surel::prune_list_bytes(cap_T), 256);
+    if (int rc = grow_buffer(ctx, &ctx->d_prune, &ctx->prune_bytes, slot_bytes + list_bytes + 256))
+        return rc;
+    char* ws = static_cast<char*>(ctx->d_prune);
+    out->slots = reinterpret_cast<uint32_t*>(ws);
+    out->list = reinterpret_cast<uint32_t*>(ws + slot_bytes);
+    out->counters = reinterpret_cast<unsigned long long*>(ws + slot_bytes + list_bytes);
+    return SUREL_OK;
+}
+
+int surel_sample_walks_rpe_ids(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
+                               int32_t n_nodes, int64_t n_edges, const int32_t* d_seeds,
+                               int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,
+                               int32_t* d_walks, int64_t cap_rows, int64_t* d_rpe_off,
+                               int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int32_t* d_code,
+                               int64_t cap_T, uint16_t* d_T, int64_t* h_rows, int64_t* h_n_T) {
+    if (int rc = check_fused_args(d_row_ptr, d_col_idx, n_nodes, n_edges, d_seeds, n_seeds, M, m,
+                                  d_walks, cap_rows, d_rpe_off))
+        return rc;
+    if (cap_T < 1 || cap_T > SUREL_MAX_DISTINCT) return SUREL_E_RANGE;
+    if (!d_T || !h_rows || !h_n_T) return SUREL_E_NULL;
+    if (cap_rows > 0 && (!d_rpe_ids || !d_code)) return SUREL_E_NULL;
+    if (misaligned4(d_rpe_cnt)) return SUREL_E_RANGE;
+    if (!ctx) return SUREL_E_CTX;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return SUREL_E_HIP;
+    *h_n_T = 0;
+    if (n_seeds == 0) {
+        if (int rc = empty_table(ctx, d_rpe_off)) return rc;
+        return report_total(ctx, d_rpe_off, 0, true, cap_rows, h_rows);
+    }
+    PruneScratch ps;
+    if (int rc = prune_scratch(ctx, cap_T, &ps)) return rc;
+    if (surel::launch_prune_clear(ctx->stream, cap_T, ps.slots, ps.counters) != hipSuccess)
+        return SUREL_E_HIP;
+    if (int rc = fused_launch(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, d_seeds, n_seeds, M, m,
+                              rng_seed, d_walks, cap_rows, d_rpe_off, d_rpe_ids, d_rpe_cnt, d_code,
+                              ps.slots, cap_T, ps.counters))
+        return rc;
+    // the two totals in one read-back: table rows, distinct vectors
+    if (hipMemcpyAsync(ctx->h_pinned + 1, ps.counters, sizeof(int64_t), hipMemcpyDeviceToHost,
+                       ctx->stream) != hipSuccess)
+        return SUREL_E_HIP;
+    if (int rc = report_total(ctx, d_rpe_off, n_seeds, true, cap_rows, h_rows)) {
+        *h_n_T = ctx->h_pinned[1];
+        return rc;  // rows that did not fit have no codes: nothing to finish
+    }
+    const int64_t n_T = ctx->h_pinned[1];
+    *h_n_T = n_T;
+    if (n_T > cap_T) return SUREL_E_CAPACITY;
+    KernelSpan span(ctx, SUREL_K_PRUNE);
+    if (surel::launch_prune_finish(ctx->stream, ctx->n_cu, *h_rows, m, cap_T, n_T, ps.slots,
+                                   ps.counters, ps.list, d_T, d_code) != hipSuccess)
+        return SUREL_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SUREL_E_HIP;
     return SUREL_OK;
 }
 
@@ -677,14 +770,11 @@ int surel_prune_rpe(surel_ctx* ctx, const uint16_t* d_rpe_cnt, int64_t n_rows, i
     if (!ctx) return SUREL_E_CTX;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
-    const size_t slot_bytes = surel::prune_slot_bytes(cap_T);
-    const size_t list_bytes = align_up(surel::prune_list_bytes(cap_T), 256);
-    const size_t need = slot_bytes + list_bytes + 256;
-    if (int rc = grow_buffer(ctx, &ctx->d_prune, &ctx->prune_bytes, need)) return rc;
-    char* ws = static_cast<char*>(ctx->d_prune);
-    uint32_t* slots = reinterpret_cast<uint32_t*>(ws);
-    uint32_t* list = reinterpret_cast<uint32_t*>(ws + slot_bytes);
-    unsigned long long* counters = reinterpret_cast<unsigned long long*>(ws + slot_bytes + list_bytes);
+    PruneScratch ps;
+    if (int rc = prune_scratch(ctx, cap_T, &ps)) return rc;
+    uint32_t* slots = ps.slots;
+    uint32_t* list = ps.list;
+    unsigned long long* counters = ps.counters;
     KernelSpan span(ctx, SUREL_K_PRUNE);
     if (surel::launch_prune_collect(ctx->stream, ctx->n_cu, d_rpe_cnt, n_rows, m, cap_T, slots,
                                     counters, d_code, ctx->spin_limit, ctx->d_err) != hipSuccess)

@@ -26,12 +26,19 @@ hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const
 // units of the device.  spin_limit bounds every wait inside the kernel (kDevStall when one runs
 // out; rpe_off[n_seeds] is then -1).  Needs M*(m+1) <= 2048 and n_seeds >= 1.
 // hipErrorInvalidValue = the shape does not fit the device's LDS.
+// With `code` (int32 per table row) the kernel also looks every finished row's count vector up
+// in the hash set of prune.hip (slots of prune_slot_bytes(cap_T) bytes, emptied by
+// launch_prune_clear; counters as for launch_prune_collect) and writes the row's slot number to
+// code[row]; launch_prune_finish then turns slot numbers into indices of the sorted array T.
+// cnt may then be null (rows carry RPE-IDs only).
 hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* row_ptr,
                            const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
                            uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
                            int32_t* ids, uint16_t* cnt, const void* edge_records, uint64_t* lb,
-                           uint32_t spin_limit, uint32_t* err);
+                           uint32_t spin_limit, uint32_t* err, int32_t* code = nullptr,
+                           uint32_t* slots = nullptr, int64_t cap_T = 0,
+                           unsigned long long* counters = nullptr);
 
 // rpe.hip.  launch_rpe_count: set_sizes[i] = distinct nodes in walks[i].  launch_rpe_fill:
 // writes the rows of every seed at rpe_off[i] (seeds whose block would pass cap_rows, or whose
@@ -77,6 +84,10 @@ hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, con
 // launch_prune_finish with it.
 size_t prune_slot_bytes(int64_t cap_T);
 size_t prune_list_bytes(int64_t cap_T);
+uint32_t prune_slot_mask(int64_t cap_T);
+// empties the hash set and its counters (memsets: not for stream capture)
+hipError_t launch_prune_clear(hipStream_t stream, int64_t cap_T, uint32_t* slots,
+                              unsigned long long* counters);
 hipError_t launch_prune_collect(hipStream_t stream, int n_cu, const uint16_t* cnt, int64_t n_rows,
                                 int32_t m, int64_t cap_T, uint32_t* slots,
                                 unsigned long long* counters, int32_t* code, uint32_t spin_limit,

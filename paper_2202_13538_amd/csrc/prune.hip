@@ -21,13 +21,9 @@
 // all the same.
 #include "device_util.h"
 #include "kernels.h"
+#include "prune_set.h"
 
 namespace surel {
-
-constexpr uint32_t kSlotEmpty = 0u, kSlotLocked = 1u, kSlotFull = 2u;
-constexpr int kSlotWords = 16;    // 64-byte slots: [0] state, [1] rank, [2..3] unused, [4..11] vector
-constexpr int kSlotVector = 4;    // first word of the vector inside a slot
-constexpr int kMaxVecWords = 8;   // m + 1 <= 16 counts of 16 bits
 
 // The count vector of a row as NW words, entry 2k in the upper half of word k, so that
 // comparing words in order compares the counts in order.  L = m + 1 entries.
@@ -43,76 +39,7 @@ __device__ __forceinline__ void load_vector(const uint16_t* __restrict__ cnt, in
     }
 }
 
-template <int NW>
-__device__ __forceinline__ uint32_t hash_vector(const uint32_t (&w)[NW]) {
-    uint32_t h = 0x811C9DC5u;
-#pragma unroll
-    for (int k = 0; k < NW; ++k) {
-        h = (h ^ w[k]) * 0x9E3779B1u;
-        h ^= h >> 15;
-    }
-    return h;
-}
-
-// Finds (or inserts) vector w, first probe at slot h; returns its slot number, or -1 if a wait
-// ran out or the table is full.  *n_inserted counts the vectors inserted so far (the size of T
-// when collect has ended).
-template <int NW>
-__device__ __forceinline__ int32_t find_or_insert(const uint32_t (&w)[NW], uint32_t h,
-                                                  uint32_t* __restrict__ slots, uint32_t slot_mask,
-                                                  int64_t cap_T,
-                                                  unsigned long long* __restrict__ n_inserted,
-                                                  uint32_t spin_limit, uint32_t* __restrict__ err) {
-    uint32_t spins = 0;
-    for (uint32_t probe = 0; probe <= slot_mask;) {
-        uint32_t* slot = slots + (size_t)h * kSlotWords;
-        // a slot that reads as full is final, and its vector lies in the same cache line
-        uint32_t st = slot[0];
-        if (st != kSlotFull) {
-            st = atomicCAS(slot, kSlotEmpty, kSlotLocked);
-            if (st == kSlotEmpty) {
-                // this lane owns the slot: is there still room in T?
-                const unsigned long long before = atomicAdd(n_inserted, 1ull);
-                if ((int64_t)before >= cap_T) atomicOr(err, kDevCapacity);
-#pragma unroll
-                for (int k = 0; k < NW; ++k)
-                    __hip_atomic_store(slot + kSlotVector + k, w[k], __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(slot, kSlotFull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                return (int32_t)h;
-            }
-            if (st == kSlotLocked) {
-                // somebody is writing this slot's vector: look again
-                if (++spins > spin_limit) {
-                    atomicOr(err, kDevStall);
-                    return -1;
-                }
-                __builtin_amdgcn_s_sleep(1);
-                continue;
-            }
-            // full, but the plain load may have come from a stale line: read past it
-            bool same = true;
-#pragma unroll
-            for (int k = 0; k < NW; ++k)
-                same = same && __hip_atomic_load(slot + kSlotVector + k, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT) == w[k];
-            if (same) return (int32_t)h;
-        } else {
-            bool same = true;
-#pragma unroll
-            for (int k = 0; k < NW; ++k) same = same && slot[kSlotVector + k] == w[k];
-            if (same) return (int32_t)h;
-        }
-        h = (h + 1u) & slot_mask;
-        probe += 1;
-    }
-    return -1;
-}
-
 constexpr int kPruneRows = 4;        // rows a lane works on at once
-constexpr int kCacheEntries = 256;   // per-workgroup LDS cache of (vector -> slot), direct mapped
-constexpr int kCacheWords = 12;      // [0] state, [1] slot, [2..3] unused, [4..11] vector
-
 // A workgroup takes tiles of 256 * kPruneRows consecutive rows; a lane has kPruneRows of them in
 // flight.  A few vectors make up nearly all rows, and all compute units asking the same few
 // cache lines of the global table for them would queue up at those lines' L2 channels; so every
@@ -126,7 +53,7 @@ __global__ __launch_bounds__(256) void prune_collect_kernel(
     uint32_t slot_mask, int64_t cap_T, unsigned long long* __restrict__ n_inserted,
     int32_t* __restrict__ code, uint32_t spin_limit, uint32_t* __restrict__ err) {
     __shared__ uint32_t cache[kCacheEntries * kCacheWords];
-    for (int t = threadIdx.x; t < kCacheEntries; t += 256) cache[t * kCacheWords] = 0u;
+    prune_cache_clear(cache, (int)threadIdx.x, 256);
     __syncthreads();
     const int64_t tile_rows = 256 * kPruneRows;
     const int64_t stride = (int64_t)gridDim.x * tile_rows;
@@ -141,26 +68,8 @@ __global__ __launch_bounds__(256) void prune_collect_kernel(
         for (int u = 0; u < kPruneRows; ++u) {
             const int64_t row = tile + u * 256 + (int64_t)threadIdx.x;
             if (row >= n_rows) continue;
-            const uint32_t hv = hash_vector<NW>(w[u]);
-            uint32_t* entry = cache + ((hv >> 20) & (kCacheEntries - 1)) * kCacheWords;
-            int32_t found = -1;
-            if (entry[0] == 2u) {
-                bool same = true;
-#pragma unroll
-                for (int k = 0; k < NW; ++k) same = same && entry[4 + k] == w[u][k];
-                if (same) found = (int32_t)entry[1];
-            }
-            if (found < 0) {
-                found = find_or_insert<NW>(w[u], hv & slot_mask, slots, slot_mask, cap_T,
-                                           n_inserted, spin_limit, err);
-                if (found >= 0 && atomicCAS(entry, 0u, 1u) == 0u) {
-#pragma unroll
-                    for (int k = 0; k < NW; ++k) entry[4 + k] = w[u][k];
-                    entry[1] = (uint32_t)found;
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                    __hip_atomic_store(entry, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
-            }
+            const int32_t found = prune_lookup<NW>(w[u], cache, slots, slot_mask, cap_T, n_inserted,
+                                                   spin_limit, err);
             code[row] = found;
         }
     }
@@ -239,14 +148,14 @@ __global__ __launch_bounds__(256) void prune_rank_kernel(const uint32_t* __restr
     }
 }
 
-// code[row]: slot number -> rank of that slot (-1 stays -1).
+// code[row]: slot number -> rank of that slot (-1, or anything that is no slot number, becomes -1).
 __global__ __launch_bounds__(256) void prune_codes_kernel(const uint32_t* __restrict__ slots,
-                                                          int64_t n_rows,
+                                                          uint32_t n_slots, int64_t n_rows,
                                                           int32_t* __restrict__ code) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; row < n_rows; row += stride) {
-        const int32_t s = code[row];
-        if (s >= 0) code[row] = (int32_t)slots[(size_t)s * kSlotWords + 1];
+        const uint32_t s = (uint32_t)code[row];
+        code[row] = s < n_slots ? (int32_t)slots[(size_t)s * kSlotWords + 1] : -1;
     }
 }
 
@@ -265,16 +174,23 @@ size_t prune_list_bytes(int64_t cap_T) {
     return (size_t)prune_list_len(cap_T) * (kMaxVecWords + 1) * 4;
 }
 
+uint32_t prune_slot_mask(int64_t cap_T) { return (uint32_t)(prune_slots(cap_T) - 1); }
+
+hipError_t launch_prune_clear(hipStream_t stream, int64_t cap_T, uint32_t* slots,
+                              unsigned long long* counters) {
+    // empty table, counters to zero (the calls that use it read a total back on the host in any
+    // case, so they cannot be captured into a graph, and plain memsets do)
+    hipError_t rc = hipMemsetAsync(slots, 0, (size_t)prune_slots(cap_T) * kSlotWords * 4, stream);
+    if (rc != hipSuccess) return rc;
+    return hipMemsetAsync(counters, 0, 2 * sizeof(unsigned long long), stream);
+}
+
 hipError_t launch_prune_collect(hipStream_t stream, int n_cu, const uint16_t* cnt, int64_t n_rows,
                                 int32_t m, int64_t cap_T, uint32_t* slots,
                                 unsigned long long* counters, int32_t* code, uint32_t spin_limit,
                                 uint32_t* err) {
     const int64_t n_slots = prune_slots(cap_T);
-    // empty table, counters to zero (the call reads a total back on the host in any case, so it
-    // cannot be captured into a graph, and plain memsets do)
-    hipError_t rc = hipMemsetAsync(slots, 0, (size_t)n_slots * kSlotWords * 4, stream);
-    if (rc != hipSuccess) return rc;
-    rc = hipMemsetAsync(counters, 0, 2 * sizeof(unsigned long long), stream);
+    hipError_t rc = launch_prune_clear(stream, cap_T, slots, counters);
     if (rc != hipSuccess) return rc;
     if (n_rows == 0) return hipSuccess;
     const int L = m + 1;
@@ -323,7 +239,7 @@ hipError_t launch_prune_finish(hipStream_t stream, int n_cu, int64_t n_rows, int
         int64_t blocks = (n_rows + 255) / 256;
         if (blocks > (int64_t)n_cu * 16) blocks = (int64_t)n_cu * 16;
         hipLaunchKernelGGL(prune_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, slots,
-                           n_rows, code);
+                           (uint32_t)prune_slots(cap_T), n_rows, code);
     }
     return hipGetLastError();
 }

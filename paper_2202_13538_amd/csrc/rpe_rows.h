@@ -76,7 +76,8 @@ __device__ __forceinline__ void rpe_assemble_rows(const uint32_t (&x)[E], const 
 }
 
 // Streams an assembled block out to rows [off, off + n_rows) of the table: ids as dwords,
-// counts as dwords where the destination's alignment allows.
+// counts (unless cnt is null: a table that carries RPE-IDs only) as dwords where the
+// destination's alignment allows.
 __device__ __forceinline__ void rpe_stream_rows(int n_rows, int lane, int L, const uint32_t* ids_lds,
                                                 const uint32_t* cnt_lds32, int64_t off,
                                                 int32_t* __restrict__ ids,
@@ -85,6 +86,7 @@ __device__ __forceinline__ void rpe_stream_rows(int n_rows, int lane, int L, con
     const int n_cnt = n_rows * L;
     int32_t* out_ids = ids + off;
     for (int t = lane; t < n_rows; t += kWave) out_ids[t] = (int32_t)ids_lds[t];
+    if (cnt == nullptr) return;
 
     const int64_t d0 = off * L;  // first destination element (uint16 units)
     const int head = (int)(d0 & 1);

@@ -17,6 +17,7 @@
 #include "device_util.h"
 #include "kernels.h"
 #include "lookback.h"
+#include "prune_set.h"
 #include "rpe_rows.h"
 #include "walk_core.h"
 #include "wave_sort.h"
@@ -25,9 +26,21 @@ namespace surel {
 
 constexpr int kFusedChains = 2;  // walks a lane moves at a time
 
+// The hash set of distinct count vectors that a kernel with kCodes feeds (prune_set.h).
+struct CodeSet {
+    int32_t* code;                      // int32 per table row: the row's slot number
+    uint32_t* slots;
+    uint32_t slot_mask;
+    int64_t cap_T;
+    unsigned long long* n_inserted;
+};
+
 // E = sort keys per lane (64*E >= M*(m+1)).  The waves of a workgroup share the LDS
-// allocation and the chunk word, nothing else.
-template <int E, bool kRec>
+// allocation and the chunk word (with kCodes also a cache of the hash set), nothing else.
+// kCodes: every finished row's count vector is looked up in the hash set while the row still
+// lies in LDS (Algorithm 1's last step, pruning, done on the fly as well), and its slot number
+// goes to cs.code; cnt may then be null.
+template <int E, bool kRec, bool kCodes>
 __global__ __launch_bounds__(1024) void walk_rpe_kernel(
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
     const int4* __restrict__ rec, int32_t n_nodes, int64_t n_edges,
@@ -35,13 +48,15 @@ __global__ __launch_bounds__(1024) void walk_rpe_kernel(
     uint32_t key1, uint32_t magic_L, int32_t* __restrict__ walks, int64_t cap_rows,
     int64_t* __restrict__ rpe_off, int32_t* __restrict__ ids, uint16_t* __restrict__ cnt,
     int32_t lds_words_per_wave, uint64_t* __restrict__ lb, uint32_t spin_limit,
-    uint32_t* __restrict__ err) {
+    uint32_t* __restrict__ err, CodeSet cs) {
     extern __shared__ uint32_t lds32[];
     __shared__ unsigned long long chunk;
+    __shared__ uint32_t set_cache[kCodes ? kFusedCacheWords : 1];
 
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (threadIdx.x == 0) chunk = 0ull;  // empty
+    if constexpr (kCodes) fused_cache_clear(set_cache, (m + 2) / 2, (int)threadIdx.x, (int)blockDim.x);
     __syncthreads();                     // the only workgroup-wide barrier of the kernel
     const LookbackScratch scr = lookback_scratch(n_seeds);
     int64_t* base = lookback_base(lb);
@@ -76,7 +91,36 @@ __global__ __launch_bounds__(1024) void walk_rpe_kernel(
         if (off + sc.n_rows > cap_rows) {
             if (lane == 0) atomicOr(err, kDevCapacity);
         } else {
-            rpe_write_rows<E>(x, sc, lane, L, wave_lds, wave_lds + sc.n_rows, off, ids, cnt);
+            uint32_t* ids_lds = wave_lds;
+            uint32_t* cnt_lds32 = wave_lds + sc.n_rows;
+            rpe_assemble_rows<E>(x, sc, lane, L, ids_lds, cnt_lds32);
+            if constexpr (kCodes) {
+                // a lane per row: the row's vector as words (entry 2k in the upper half of word
+                // k, absent entries zero), then its slot in the set of distinct vectors.  The L
+                // 16-bit counts of row t start at halfword t*L of the LDS rows: they are read as
+                // the aligned words that cover them and shifted into place.
+                const int n_words = (sc.n_rows * L + 1) / 2;  // words the rows occupy in LDS
+                for (int t = lane; t < sc.n_rows; t += kWave) {
+                    const int first = t * L;
+                    const uint32_t shift = (uint32_t)(first & 1) * 2u;
+                    uint32_t raw[kMaxVecWords + 1];
+#pragma unroll
+                    for (int k = 0; k <= kMaxVecWords; ++k)
+                        raw[k] = 2 * k <= L ? cnt_lds32[min((first >> 1) + k, n_words - 1)] : 0u;
+                    uint32_t w[kMaxVecWords];
+#pragma unroll
+                    for (int k = 0; k < kMaxVecWords; ++k) {
+                        // entries 2k (low half) and 2k+1 (high half) as they lie in memory
+                        uint32_t pair = __builtin_amdgcn_alignbyte(raw[k + 1], raw[k], shift);
+                        if (2 * k + 1 >= L) pair &= 0xFFFFu;  // the high half is the next row's
+                        if (2 * k >= L) pair = 0u;
+                        w[k] = (pair << 16) | (pair >> 16);
+                    }
+                    cs.code[off + t] = prune_lookup_any(w, (L + 1) / 2, set_cache, cs.slots, cs.slot_mask,
+                                                        cs.cap_T, cs.n_inserted, spin_limit, err);
+                }
+            }
+            rpe_stream_rows(sc.n_rows, lane, L, ids_lds, cnt_lds32, off, ids, cnt);
         }
         wave_sync();  // the LDS words are free again
         return true;
@@ -162,16 +206,17 @@ static int walk_rpe_lds_words(int M, int m) {
         const int32_t *col_idx, const int4 *rec, int32_t n_nodes, int64_t n_edges,                \
         const int32_t *seeds, int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,           \
         int32_t *walks, int64_t cap_rows, int64_t *rpe_off, int32_t *ids, uint16_t *cnt,          \
-        uint64_t *lb, uint32_t spin_limit, uint32_t *err
+        uint64_t *lb, uint32_t spin_limit, uint32_t *err, const CodeSet &cs
 #define SUREL_WR_ARGS                                                                             \
     stream, max_lds_bytes, n_cu, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m,   \
-        rng_seed, walks, cap_rows, rpe_off, ids, cnt, lb, spin_limit, err
+        rng_seed, walks, cap_rows, rpe_off, ids, cnt, lb, spin_limit, err, cs
 
-template <int E, bool kRec>
-static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
+template <int E, bool kRec, bool kCodes>
+static hipError_t launch_walk_rpe_erc(SUREL_WR_PARAMS) {
     const int words = walk_rpe_lds_words(M, m);
     const size_t per_wave = (size_t)words * 4;
-    const void* fn = reinterpret_cast<const void*>(walk_rpe_kernel<E, kRec>);
+    const size_t static_lds = 1024 + (kCodes ? (size_t)kFusedCacheWords * 4 : 0);
+    const void* fn = reinterpret_cast<const void*>(walk_rpe_kernel<E, kRec, kCodes>);
     // waves per compute unit that LDS (160 KB) and registers allow, split into as few equal
     // workgroups as possible (a workgroup has at most 16 waves)
     hipFuncAttributes attr;
@@ -179,19 +224,19 @@ static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
     if (rc != hipSuccess) return rc;
     const int regs = attr.numRegs > 0 ? attr.numRegs : 128;
     int cu_waves = 4 * (512 / ((regs + 7) / 8 * 8));
-    const int by_lds = (int)((160 * 1024 - 1024) / per_wave);
+    const int by_lds = (int)((160 * 1024 - static_lds) / per_wave);
     if (cu_waves > by_lds) cu_waves = by_lds;
     if (cu_waves > 32) cu_waves = 32;
     constexpr int kMaxW = 16;
     int groups = (cu_waves + kMaxW - 1) / kMaxW;
     int W = groups > 0 ? cu_waves / groups : 0;
     if (W < 1) {  // not even one wave next to other workgroups: what one workgroup may have
-        W = (int)(((size_t)max_lds_bytes - 64) / per_wave);
+        W = (int)(((size_t)max_lds_bytes - static_lds) / per_wave);
         if (W > kMaxW) W = kMaxW;
     }
     if (W < 1) return hipErrorInvalidValue;
     const size_t lds_bytes = (size_t)W * per_wave;
-    if (lds_bytes + 64 > (size_t)max_lds_bytes) return hipErrorInvalidValue;
+    if (lds_bytes + static_lds > (size_t)max_lds_bytes) return hipErrorInvalidValue;
     if (lds_bytes > 48 * 1024) {
         rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (rc != hipSuccess) return rc;
@@ -209,11 +254,17 @@ static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
     rc = launch_lookback_clear(stream, lb, n_seeds, rpe_off + n_seeds);
     if (rc != hipSuccess) return rc;
     const uint32_t magic_L = 65536u / (uint32_t)(m + 1) + 1u;
-    hipLaunchKernelGGL((walk_rpe_kernel<E, kRec>), dim3((unsigned)blocks), dim3(W * kWave),
+    hipLaunchKernelGGL((walk_rpe_kernel<E, kRec, kCodes>), dim3((unsigned)blocks), dim3(W * kWave),
                        lds_bytes, stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M,
                        m, (uint32_t)(rng_seed & 0xFFFFFFFFull), (uint32_t)(rng_seed >> 32), magic_L,
-                       walks, cap_rows, rpe_off, ids, cnt, words, lb, spin_limit, err);
+                       walks, cap_rows, rpe_off, ids, cnt, words, lb, spin_limit, err, cs);
     return hipGetLastError();
+}
+
+template <int E, bool kRec>
+static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
+    if (cs.code != nullptr) return launch_walk_rpe_erc<E, kRec, true>(SUREL_WR_ARGS);
+    return launch_walk_rpe_erc<E, kRec, false>(SUREL_WR_ARGS);
 }
 
 template <int E>
@@ -227,8 +278,10 @@ hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, cons
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
                            uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
                            int32_t* ids, uint16_t* cnt, const void* edge_records, uint64_t* lb,
-                           uint32_t spin_limit, uint32_t* err) {
+                           uint32_t spin_limit, uint32_t* err, int32_t* code, uint32_t* slots,
+                           int64_t cap_T, unsigned long long* counters) {
     const int4* rec = static_cast<const int4*>(edge_records);
+    const CodeSet cs{code, slots, code ? prune_slot_mask(cap_T) : 0u, cap_T, counters};
     const int n_key = M * (m + 1);
 #define SUREL_WR_CASE(E_) \
     if (n_key <= kWave * (E_)) return launch_walk_rpe_e<E_>(SUREL_WR_ARGS);

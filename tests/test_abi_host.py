@@ -183,6 +183,40 @@ def test_sample_walks_rpe_argument_checks(lib, kw, want):
     assert lib.surel_sample_walks_rpe(*fused_args(**kw)) == want
 
 
+def fused_ids_args(**kw):
+    a = dict(ctx=NULL, row_ptr=P, col_idx=P, n_nodes=100, n_edges=500, seeds=P, n_seeds=10,
+             M=50, m=4, rng_seed=0, walks=P, cap_rows=1000, off=P, ids=P, cnt=P, code=P, cap_T=64,
+             T=P, h_rows=ctypes.pointer(ctypes.c_int64(0)), h_n_T=ctypes.pointer(ctypes.c_int64(0)))
+    a.update(kw)
+    return [a[k] for k in ("ctx", "row_ptr", "col_idx", "n_nodes", "n_edges", "seeds", "n_seeds",
+                           "M", "m", "rng_seed", "walks", "cap_rows", "off", "ids", "cnt", "code",
+                           "cap_T", "T", "h_rows", "h_n_T")]
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), binding.E_CTX),
+    (dict(cnt=NULL), binding.E_CTX),              # a table of RPE-IDs only
+    (dict(n_nodes=0), binding.E_RANGE),
+    (dict(n_edges=-1), binding.E_RANGE),
+    (dict(M=410, m=4), binding.E_RANGE),
+    (dict(cap_rows=-1), binding.E_RANGE),
+    (dict(cap_T=0), binding.E_RANGE),
+    (dict(cap_T=binding.MAX_DISTINCT + 1), binding.E_RANGE),
+    (dict(row_ptr=NULL), binding.E_NULL),
+    (dict(seeds=NULL), binding.E_NULL),
+    (dict(walks=NULL), binding.E_NULL),
+    (dict(off=NULL), binding.E_NULL),
+    (dict(ids=NULL), binding.E_NULL),
+    (dict(code=NULL), binding.E_NULL),
+    (dict(T=NULL), binding.E_NULL),
+    (dict(h_rows=NULL), binding.E_NULL),
+    (dict(h_n_T=NULL), binding.E_NULL),
+    (dict(cnt=ctypes.c_void_p(0x1002)), binding.E_RANGE),
+])
+def test_sample_walks_rpe_ids_argument_checks(lib, kw, want):
+    assert lib.surel_sample_walks_rpe_ids(*fused_ids_args(**kw)) == want
+
+
 def join_ids_args(**kw):
     a = dict(ctx=NULL, off=P, ids=P, code=P, n_blocks=100, max_set=201, queries=P, n_q=10, k=2,
              cap_rows=1000, joff=P, jids=P, jcodes=P, h_rows=NULL)

@@ -235,6 +235,14 @@ def check_workload(ctx, name, say):
         assert np.array_equal(host_u16(T), want_T), "pruned array differs"
         assert np.array_equal(code.cpu().numpy(), want_code), "re-indexed rows differ"
         say(f"[{name}] pruning: {T.shape[0]} distinct vectors, all {R} codes equal the oracle's")
+        # the same from the call that walks, builds and prunes at once (table of RPE-IDs only)
+        i_walks, i_off, i_ids, _, i_code, i_T = binding.sample_walks_rpe_ids(
+            ctx, d_rp, d_ci, d_seeds, M, m, wl.rng_seed, with_counts=False)
+        assert ctx.check() == 0
+        assert torch.equal(i_walks, walks) and torch.equal(i_off, off) and torch.equal(i_ids, ids)
+        assert torch.equal(i_code, code) and same_u16(i_T, T), "one call: codes or T differ"
+        del i_walks, i_off, i_ids, i_code, i_T
+        say(f"[{name}] walks + RPE-IDs + T from one call equal the separate calls")
 
         # the union join over the codes: same offsets and ids as the join over counts (checked
         # above), and every code names, in T (checked above), the count vector that the join over

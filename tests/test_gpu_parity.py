@@ -87,6 +87,19 @@ def full_compare(ctx, rp, ci, seeds, M, m, rng_seed, queries):
     want_T, want_code = oracle.prune_rpe(table[2])
     assert np.array_equal(host_u16(T), want_T), "pruned array differs"
     assert np.array_equal(code.cpu().numpy(), want_code), "re-indexed rows differ"
+    # walks, table and pruned array from one call, with and without the count vectors
+    for with_counts in (True, False):
+        i_walks, i_off, i_ids, i_cnt, i_code, i_T = binding.sample_walks_rpe_ids(
+            ctx, dev(rp), dev(ci), d_seeds, M, m, rng_seed, cap_T=max(1, table[2].shape[0]),
+            with_counts=with_counts)
+        assert ctx.check() == 0
+        assert np.array_equal(i_walks.cpu().numpy(), w), "one call: walks differ"
+        assert np.array_equal(i_off.cpu().numpy(), table[0]), "one call: offsets differ"
+        assert np.array_equal(i_ids.cpu().numpy(), table[1]), "one call: ids differ"
+        if with_counts:
+            assert np.array_equal(host_u16(i_cnt), table[2]), "one call: counts differ"
+        assert np.array_equal(host_u16(i_T).reshape(want_T.shape), want_T), "one call: T differs"
+        assert np.array_equal(i_code.cpu().numpy(), want_code), "one call: codes differ"
     if queries is not None and np.asarray(queries).shape[0] > 0:
         # query-level RPE-IDs of every walk position
         got = binding.query_rpe_ids(ctx, f_walks, f_off, f_ids, dev(np.asarray(queries, np.int32)),
