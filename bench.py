@@ -242,8 +242,8 @@ def main() -> int:
     ap.add_argument("--membench", action="store_true",
                     help="instead of the pipeline, run the memory-system micro-benchmarks "
                          "(streaming, dependent random gathers by table size, scatters) and print "
-                         "them as one JSON line: the measured ceilings that DESIGN.md's memory "
-                         "table and profiles/membench_mi355x.txt quote")
+                         "them as one JSON line: the measured ceilings of this GPU that the "
+                         "roofline.as_moved figures are compared with")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB read + 1 GiB write "
                          "elementwise kernels (the known-size reference for rocprofv3 FETCH_SIZE "

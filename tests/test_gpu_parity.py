@@ -673,3 +673,17 @@ def test_join_query_counts_around_workgroup_and_scan_tile_sizes(ctx, k):
                                    cap_rows=int(want[0][-1]) + 5)
         assert ctx.check() == 0
         assert_table_equal(got, want, f"join of {n} queries")
+
+
+def test_largest_node_ids(ctx):
+    # a graph with the most nodes the library takes (2^28 - 1): the largest ids make sort keys
+    # (id << 4 | position) that use all 32 bits and must still sort in front of the padding
+    n = binding.MAX_NODES
+    top = [n - 1, n - 2, n - 3, n - 4]
+    edges = [(a, b) for i, a in enumerate(top) for b in top[i + 1:]]
+    edges += [(0, n - 1), (12345, n - 2), (n - 5, 7), (7, 12345)]
+    rp, ci = synth.csr_from_edge_list(n, edges)
+    seeds = np.array([n - 1, 0, n - 2, 12345, n - 5, 7, n - 3, 5, n - 1], dtype=np.int32)  # 5: isolated
+    queries = np.array([[0, 2], [1, 6], [8, 0], [7, 7], [3, 4], [5, 2]], dtype=np.int32)
+    out = full_compare(ctx, rp, ci, seeds, 60, 4, 3, queries)
+    assert int(out["walks"].max()) == n - 1
