@@ -687,3 +687,49 @@ def test_largest_node_ids(ctx):
     queries = np.array([[0, 2], [1, 6], [8, 0], [7, 7], [3, 4], [5, 2]], dtype=np.int32)
     out = full_compare(ctx, rp, ci, seeds, 60, 4, 3, queries)
     assert int(out["walks"].max()) == n - 1
+
+
+def test_one_call_rpe_ids_capacity(ctx):
+    # surel_sample_walks_rpe_ids with too little room: for the table, for the distinct vectors
+    wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
+    rp, ci = synth.make_graph(wl)
+    M, m, L = wl.M, wl.m, wl.m + 1
+    seeds = np.arange(64, dtype=np.int32)
+    w = oracle.sample_walks(rp, ci, seeds, M, m, 3)
+    t_off, t_ids, t_cnt = oracle.build_rpe(w)
+    want_T, want_code = oracle.prune_rpe(t_cnt)
+    total, n_T = int(t_off[-1]), want_T.shape[0]
+    d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(seeds)
+    walks = torch.empty((64, M, L), dtype=torch.int32, device="cuda")
+    off = torch.empty(65, dtype=torch.int64, device="cuda")
+    ids = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    code = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    T = torch.zeros((n_T, L), dtype=torch.int16, device="cuda").view(torch.uint16)
+    # exactly enough room for both
+    rc, rows, got_T = binding.sample_walks_rpe_ids_raw(ctx, d_rp, d_ci, d_seeds, M, m, 3, walks,
+                                                       total, off, ids, None, code, n_T, T)
+    assert rc == binding.OK and rows == total and got_T == n_T and ctx.check() == 0
+    assert np.array_equal(host_u16(T), want_T) and np.array_equal(code.cpu().numpy(), want_code)
+    assert np.array_equal(ids.cpu().numpy(), t_ids) and np.array_equal(off.cpu().numpy(), t_off)
+    # one distinct vector too many
+    rc, rows, got_T = binding.sample_walks_rpe_ids_raw(ctx, d_rp, d_ci, d_seeds, M, m, 3, walks,
+                                                       total, off, ids, None, code, n_T - 1, T)
+    assert rc == binding.E_CAPACITY and rows == total and got_T == n_T
+    assert ctx.check() == binding.DEV_CAPACITY
+    # a table that is too small: complete offsets and walks, the totals reported, nothing
+    # written at or past cap_rows
+    cap = total // 2
+    ids.fill_(-7)
+    code.fill_(-7)
+    rc, rows, got_T = binding.sample_walks_rpe_ids_raw(ctx, d_rp, d_ci, d_seeds, M, m, 3, walks,
+                                                       cap, off, ids, None, code, n_T, T)
+    assert rc == binding.E_CAPACITY and rows == total
+    assert ctx.check() == binding.DEV_CAPACITY
+    assert np.array_equal(off.cpu().numpy(), t_off) and np.array_equal(walks.cpu().numpy(), w)
+    assert (ids.cpu().numpy()[cap:] == -7).all() and (code.cpu().numpy()[cap:] == -7).all()
+    last = int(t_off[1:][t_off[1:] <= cap].max())
+    assert np.array_equal(ids.cpu().numpy()[:last], t_ids[:last])
+    # no seeds at all
+    rc, rows, got_T = binding.sample_walks_rpe_ids_raw(ctx, d_rp, d_ci, d_seeds[:0], M, m, 3,
+                                                       walks[:0], 0, off[:1], ids, None, code, n_T, T)
+    assert rc == binding.OK and rows == 0 and got_T == 0 and int(off[0]) == 0

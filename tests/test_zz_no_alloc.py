@@ -113,3 +113,44 @@ def test_noalloc_join_at_its_largest_size_and_device_memory_stays_as_it_was():
     assert torch.equal(jcnt.view(torch.int16), jcnt2.view(torch.int16))
     fresh.close()
     ctx.close()
+
+
+def test_noalloc_join_under_graph_capture():
+    # what the entry point is for: captured once (no allocation, no memset, no wait inside),
+    # replayed with other work on the stream in between, every replay against the eager bytes
+    wl = synth.Workload("t", "rmat", 4096, 30000, 0.0, 50, 4, 0, 2, "uniform", graph_seed=9)
+    rp, ci = synth.make_graph(wl)
+    rng = np.random.default_rng(4)
+    queries = rng.integers(0, wl.n_nodes, size=(3001, 2)).astype(np.int32)
+    max_set = 1 + wl.M * wl.m
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        c = binding.Context(stream=stream)
+        seeds = torch.arange(wl.n_nodes, dtype=torch.int32, device="cuda")
+        _, off, ids, cnt = binding.sample_walks_rpe(c, dev(rp), dev(ci), seeds, wl.M, wl.m, 3)
+        d_q = dev(queries)
+        want = join_into_fresh_buffers(c, (off, ids, cnt), d_q, max_set,
+                                       rows=int(binding.join_queries(c, off, ids, cnt, d_q, max_set)[1].numel()),
+                                       noalloc=False)
+        rows = want[1].numel()
+        joff = torch.empty(queries.shape[0] + 1, dtype=torch.int64, device="cuda")
+        jids = torch.empty(rows, dtype=torch.int32, device="cuda")
+        jcnt = torch.empty((rows, 2, wl.m + 1), dtype=torch.uint16, device="cuda")
+        # a fresh context: nothing has grown its workspace, and nothing will
+        g_ctx = binding.Context(stream=stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream, capture_error_mode="thread_local"):
+            rc, _ = binding.join_queries_raw(g_ctx, off, ids, cnt, d_q, max_set, rows, joff, jids,
+                                             jcnt, want_rows=False, noalloc=True)
+        assert rc == binding.OK
+        for replay in range(3):
+            for t in (joff, jids, jcnt.view(torch.int16)):
+                t.fill_(-7 - replay)                 # eager work between the replays
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            assert g_ctx.check() == 0, f"replay {replay}"
+            for got, ref in zip((joff, jids, jcnt.view(torch.int16)), want):
+                assert torch.equal(got, ref), f"replay {replay} differs from the eager call"
+        g_ctx.close()
+        c.close()
