@@ -37,11 +37,14 @@ namespace surel {
 constexpr uint16_t kNoSrc = 0xFFFFu;
 constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
 constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
-// Rounds of 64 union rows whose gathers a wave has in flight together: 5 for pairs, 4 for
-// larger tuples.  More rounds shorten a wave's chain of memory round trips but cost registers,
-// and the launch is bound by its waves in flight: 8 rounds (118 registers, 16 waves per compute
-// unit) took 5.75 ms on the 2.9M-node workload, 3 to 5 rounds (20 waves, what LDS allows) 5.59.
+// Rounds of 64 union rows whose gathers a wave has in flight together: 5 for pairs (4 where the
+// smaller LDS footprint of join_tile_over_ids lets a sixth workgroup onto the compute unit, which
+// needs the registers of a round), 4 for larger tuples.  More rounds shorten a wave's chain of
+// memory round trips but cost registers, and the launch is bound by its waves in flight: 8
+// rounds (118 registers, 16 waves per compute unit) took 5.75 ms on the 2.9M-node workload, 3
+// to 5 rounds (20 waves) 5.59.
 constexpr int kGatherRoundsPairs = 5;
+constexpr int kGatherRoundsPairsSmallLds = 4;
 constexpr int kGatherRoundsTuples = 4;
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
@@ -81,14 +84,28 @@ __host__ __device__ constexpr bool join_uses_tile(int K, int LT) {
     return !join_rows_direct(K, LT) || (K == 2 && LT % 2 == 1);
 }
 
+// Where rows go out of registers but through the tile (pairs of odd-length vectors), a query's
+// ids are written out before its first count, and the tile then takes the place of the id lists:
+// less LDS per wave means more waves per compute unit, which is what this kernel runs on.
+__host__ __device__ constexpr bool join_tile_over_ids(int K, int LT) {
+    return join_rows_direct(K, LT) && join_uses_tile(K, LT);
+}
+
 __host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L, bool fill,
-                                                      bool tile) {
+                                                      int LT) {
     JoinLds o{};
     o.ids = 0;
     o.new_pre = o.ids + K * max_set;
     o.src = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
-    o.tile = o.src + (fill ? (K * K * max_set + 1) / 2 : 0);
-    o.total = o.tile + (fill && tile ? (kJoinChunkRows * K * L + 1) / 2 : 0);
+    const int src_end = o.src + (fill ? (K * K * max_set + 1) / 2 : 0);
+    const int tile_words = fill && join_uses_tile(K, LT) ? (kJoinChunkRows * K * L + 1) / 2 : 0;
+    if (join_tile_over_ids(K, LT) && tile_words <= K * max_set) {
+        o.tile = o.ids;
+        o.total = src_end;
+    } else {
+        o.tile = src_end;
+        o.total = src_end + tile_words;
+    }
     return o;
 }
 
@@ -269,7 +286,7 @@ __device__ __forceinline__ int join_prepare(
     const int32_t* __restrict__ rpe_ids, int64_t n_blocks, int32_t m, int32_t max_set,
     const int32_t* __restrict__ queries, JoinQuery<K>& jq, uint32_t* __restrict__ err) {
     const int L = LT > 0 ? LT : m + 1;
-    const JoinLds lay = join_lds_layout(K, max_set, L, kSrc, join_uses_tile(K, LT));
+    const JoinLds lay = join_lds_layout(K, max_set, L, kSrc, LT);
     uint32_t* ids_lds = base + lay.ids;
     uint16_t* new_pre = reinterpret_cast<uint16_t*>(base + lay.new_pre);
     uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
@@ -327,7 +344,7 @@ __device__ __forceinline__ void join_write(
     const uint16_t* __restrict__ rpe_cnt, int32_t m, int32_t max_set,
     int32_t* __restrict__ out_ids, uint16_t* __restrict__ out_cnt, uint16_t absent16) {
     const int L = LT > 0 ? LT : m + 1;
-    const JoinLds lay = join_lds_layout(K, max_set, L, true, join_uses_tile(K, LT));
+    const JoinLds lay = join_lds_layout(K, max_set, L, true, LT);
     uint32_t* ids_lds = base + lay.ids;
     uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
     uint32_t* tile32 = base + lay.tile;
@@ -345,8 +362,23 @@ __device__ __forceinline__ void join_write(
         // kRounds rounds of 64 rows are gathered together (all their loads are in
         // flight before the first is waited for: a wave's time is a chain of memory round
         // trips), then the rounds go out one after the other
-        constexpr int kRounds = K == 2 ? kGatherRoundsPairs : kGatherRoundsTuples;
+        constexpr int kRounds = K != 2 ? kGatherRoundsTuples
+                                : join_tile_over_ids(K, LT) ? kGatherRoundsPairsSmallLds
+                                                            : kGatherRoundsPairs;
         const uint32_t* cnt_words = reinterpret_cast<const uint32_t*>(rpe_cnt);
+        const bool ids_first = lay.tile == lay.ids;  // the tile will overwrite the id lists
+        if (ids_first) {
+            for (int r = lane; r < n_out; r += kWave) {
+                uint32_t id = 0;
+#pragma unroll
+                for (int j = K - 1; j >= 0; --j) {
+                    const uint16_t sj = src[j * src_stride + r];
+                    if ((int)sj < n[j]) id = ids_lds[j * max_set + sj];
+                }
+                out_ids[off + r] = (int32_t)id;
+            }
+            wave_sync();
+        }
         for (int r0 = 0; r0 < n_out; r0 += kRounds * kWave) {
             constexpr int kCover = LT / 2 + 1;  // aligned words that cover a vector
             uint32_t raw[kRounds][K][kCover + 1];
@@ -363,8 +395,10 @@ __device__ __forceinline__ void join_write(
                     const uint16_t sj = src[j * src_stride + r];
                     // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
                     present[g][j] = (int)sj < n[j];
-                    const uint32_t id_j = ids_lds[j * max_set + (present[g][j] ? sj : 0)];
-                    if (present[g][j]) id[g] = id_j;
+                    if (!ids_first) {
+                        const uint32_t id_j = ids_lds[j * max_set + (present[g][j] ? sj : 0)];
+                        if (present[g][j]) id[g] = id_j;
+                    }
                     // unconditional loads, from the table's first row where the list has no
                     // row for the node: a branch would make every load wait for the one
                     // before it.  A vector is read as the aligned words that cover it
@@ -396,7 +430,7 @@ __device__ __forceinline__ void join_write(
                 }
                 const int r = r0 + g * kWave + lane;
                 const bool live = r < n_out;
-                if (live) out_ids[off + r] = (int32_t)id[g];
+                if (live && !ids_first) out_ids[off + r] = (int32_t)id[g];
                 if constexpr (LT % 2 == 0) {
                     // count vectors of whole words: a lane's row is stored from its registers
                     // (the rows of neighbouring lanes adjoin, so a wave's stores are contiguous)
@@ -503,7 +537,7 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int L = LT > 0 ? LT : m + 1;
-    uint32_t* base = lds32 + wave * join_lds_layout(K, max_set, L, kFill, join_uses_tile(K, LT)).total;
+    uint32_t* base = lds32 + wave * join_lds_layout(K, max_set, L, kFill, LT).total;
     const int64_t stride = (int64_t)gridDim.x * WPB;
     for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
         JoinQuery<K> jq;
@@ -555,7 +589,7 @@ template <int K, int WPB, JoinMode kMode, int LT>
 static hipError_t launch_join_cfg(const JoinJob& j) {
     constexpr bool kFill = kMode == kJoinFill;
     const size_t lds_bytes =
-        (size_t)WPB * join_lds_layout(K, j.max_set, j.m + 1, kFill, join_uses_tile(K, LT)).total * 4;
+        (size_t)WPB * join_lds_layout(K, j.max_set, j.m + 1, kFill, LT).total * 4;
     const void* fn = reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>);
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -596,8 +630,7 @@ static hipError_t launch_join_kw(const JoinJob& j) {
 template <int K, JoinMode kMode>
 static hipError_t launch_join_k(const JoinJob& j) {
     const int LT = join_static_len(kMode, j.m + 1);
-    const size_t per_wave = (size_t)join_lds_layout(K, j.max_set, j.m + 1, kMode != kJoinCount,
-                                                    join_uses_tile(K, LT)).total * 4;
+    const size_t per_wave = (size_t)join_lds_layout(K, j.max_set, j.m + 1, kMode != kJoinCount, LT).total * 4;
     // as many waves per workgroup as the LDS a wave needs allows
     if (per_wave * 4 <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 4, kMode>(j);
     if (per_wave * 2 <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 2, kMode>(j);
