@@ -105,6 +105,8 @@ def membench(torch) -> dict:
                                           ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
     lib.surel_membench_scatter.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp,
                                            ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
+    lib.surel_membench_bin.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp, vp,
+                                       ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
     size = 8 << 30
     buf = torch.empty(size, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(16, dtype=torch.int32, device="cuda")
@@ -130,6 +132,20 @@ def membench(torch) -> dict:
         assert lib.surel_membench_scatter(p, 4 << 30, width, 8, stream, ctypes.byref(ms),
                                           ctypes.byref(units)) == 0
         out[f"scatter_{width}B_rows_Gs"] = round(units.value / (ms.value * 1e-3) / 1e9, 2)
+    # one pass of binning 290 M 12-byte items (as many as the 2.9M-node workload has walkers)
+    # into 256 bins through LDS: what regrouping walkers by graph region would cost per exchange
+    assert lib.surel_membench_init(p, size, stream) == 0
+    n_items = 290_000_000
+    out_off = 7 << 29                                     # 3.5 GiB in: behind the items
+    cursor = torch.zeros(512, dtype=torch.int32, device="cuda")
+    assert lib.surel_membench_bin(p, n_items, vp(buf.data_ptr() + out_off), size - out_off,
+                                  vp(cursor.data_ptr()), stream, ctypes.byref(ms),
+                                  ctypes.byref(units)) == 0
+    out["bin_12B_256bins_ms_per_290M"] = round(ms.value, 3)
+    out["bin_12B_256bins_TBs"] = round(2 * n_items * 12 / (ms.value * 1e-3) / 1e12, 3)
+    out["bin_dropped_items"] = units.value
+    placed = int(cursor[:256].long().sum())               # every item has a place in its bin
+    assert placed + int(units.value) == n_items, (placed, units.value)
     del buf
     return out
 

@@ -1,7 +1,8 @@
 // Memory-system micro-benchmarks of the GPU that libsurel's kernels are judged against:
 // streaming read / write / copy, chains of dependent random gathers from a table of a given
-// size (what a walker does: the address of the next load comes out of the previous one), and
-// random scatters of short rows.  Benchmark tooling, not part of the hot path: `bench.py
+// size (what a walker does: the address of the next load comes out of the previous one),
+// random scatters of short rows, and one pass of binning 12-byte items by a key through LDS
+// (what it would cost to regroup walkers by the part of the graph they read next).  Benchmark tooling, not part of the hot path: `bench.py
 // --membench` calls it through the C ABI below and prints the table.
 //
 // All buffers are the caller's device memory; every call runs its kernel twice on the given
@@ -78,6 +79,104 @@ __global__ void scatter_kernel(uint32_t* __restrict__ dst, uint32_t row_mask, in
 #pragma unroll
         for (int j = 0; j < W; ++j) p[j] = idx + (uint32_t)j;
         idx = mix32(idx + (uint32_t)c);
+    }
+}
+
+// One pass of a bucket sort: n items of three 32-bit words (word 0 is the key) go to kBins
+// bins by the key's top bits.  A workgroup stages items per bin in LDS and writes a bin's items
+// out 16 at a time (192 contiguous bytes) at a position drawn from the bin's global cursor, so
+// that the output is written in whole cache lines although consecutive items go to different
+// bins.  bin b owns out[b * cap .. (b + 1) * cap); items beyond a bin's capacity are dropped and
+// counted in cursor[kBins].
+constexpr int kBins = 256;
+constexpr int kBinStage = 40;       // items a bin can hold in LDS
+constexpr int kBinFlush = 16;       // items written out at a time
+constexpr int kBinThreads = 1024;
+constexpr int kBinItemsPerThread = 2;
+
+__global__ __launch_bounds__(kBinThreads) void bin_kernel(const uint32_t* __restrict__ items,
+                                                          size_t n, int shift, uint32_t cap,
+                                                          uint32_t* __restrict__ out,
+                                                          uint32_t* __restrict__ cursor) {
+    extern __shared__ uint32_t lds[];
+    uint32_t* stage = lds;                                  // [kBins][kBinStage][3]
+    uint32_t* cnt = lds + kBins * kBinStage * 3;            // [kBins]
+    uint32_t* gpos = cnt + kBins;                           // [kBins]
+    uint32_t* nflush = gpos + kBins;                        // [kBins]
+    __shared__ int any_left;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int b = tid; b < kBins; b += kBinThreads) cnt[b] = 0;
+    __syncthreads();
+    const size_t tile = (size_t)kBinThreads * kBinItemsPerThread;
+    const size_t n_tiles = (n + tile - 1) / tile;
+    for (size_t t = blockIdx.x;; t += gridDim.x) {
+        const bool last = t >= n_tiles;  // every workgroup's final round only empties its stages
+        uint32_t it[kBinItemsPerThread][3];
+        bool have[kBinItemsPerThread];
+#pragma unroll
+        for (int u = 0; u < kBinItemsPerThread; ++u) {
+            const size_t i = t * tile + (size_t)u * kBinThreads + tid;
+            have[u] = !last && i < n;
+            if (have[u]) {
+                it[u][0] = items[i * 3];
+                it[u][1] = items[i * 3 + 1];
+                it[u][2] = items[i * 3 + 2];
+            }
+        }
+        for (;;) {
+            // place what fits; what does not waits for the flush below
+#pragma unroll
+            for (int u = 0; u < kBinItemsPerThread; ++u) {
+                if (!have[u]) continue;
+                const uint32_t b = it[u][0] >> shift;
+                const uint32_t pos = atomicAdd(&cnt[b], 1u);
+                if (pos < (uint32_t)kBinStage) {
+                    uint32_t* s = stage + ((size_t)b * kBinStage + pos) * 3;
+                    s[0] = it[u][0];
+                    s[1] = it[u][1];
+                    s[2] = it[u][2];
+                    have[u] = false;
+                }
+            }
+            if (tid == 0) any_left = 0;
+            __syncthreads();
+            // every bin: how many whole groups go out, and where
+            for (int b = tid; b < kBins; b += kBinThreads) {
+                const uint32_t c = min(cnt[b], (uint32_t)kBinStage);
+                const uint32_t nf = last ? c : c / kBinFlush * kBinFlush;
+                nflush[b] = nf;
+                cnt[b] = c;  // arrivals beyond the stage were not stored
+                if (nf > 0) gpos[b] = atomicAdd(&cursor[b], nf);
+            }
+            bool mine_left = false;
+#pragma unroll
+            for (int u = 0; u < kBinItemsPerThread; ++u) mine_left = mine_left || have[u];
+            if (mine_left) any_left = 1;
+            __syncthreads();
+            // a wave per bin in turn: write the groups out, move the rest to the front
+            for (int b = wave; b < kBins; b += kBinThreads / 64) {
+                const uint32_t nf = nflush[b];
+                if (nf == 0) continue;
+                const uint32_t c = cnt[b];
+                const uint32_t at = gpos[b];
+                const uint32_t* s = stage + (size_t)b * kBinStage * 3;
+                uint32_t keep = at < cap ? min(nf, cap - at) : 0u;
+                if (keep < nf && lane == 0) atomicAdd(&cursor[kBins], nf - keep);
+                uint32_t* dst = out + ((size_t)b * cap + at) * 3;
+                for (uint32_t w = lane; w < keep * 3; w += 64) dst[w] = s[w];
+                const uint32_t rest = c - nf;  // < kBinFlush <= nf: source and target do not overlap
+                uint32_t moved = 0;
+                if (lane < (int)(rest * 3)) moved = s[nf * 3 + lane];
+                if (lane < (int)(rest * 3)) stage[(size_t)b * kBinStage * 3 + lane] = moved;
+                if (lane == 0) cnt[b] = rest;
+            }
+            __syncthreads();
+            const bool again = any_left != 0;
+            __syncthreads();  // everybody has read the flag before it is reset
+            if (!again) break;
+        }
+        if (last) break;
     }
 }
 
@@ -169,6 +268,39 @@ int surel_membench_scatter(void* d_buf, size_t bytes, int width, int rows, void*
         if (width == 20) hipLaunchKernelGGL(scatter_kernel<5>, grid, block, 0, s, dst, row_mask, rows);
         if (width == 64) hipLaunchKernelGGL(scatter_kernel<16>, grid, block, 0, s, dst, row_mask, rows);
     }, h_ms);
+}
+
+// One binning pass over n 12-byte items (d_items, words 0 = key = 32 random bits) into 256 bins
+// of d_out (cap items each, cap = n / 256 * 5 / 4) through LDS; d_cursor: 257 words.  *h_ms =
+// time of the pass; *h_dropped = items that did not fit their bin (0 for uniform keys).
+int surel_membench_bin(const void* d_items, size_t n, void* d_out, size_t out_bytes,
+                       uint32_t* d_cursor, void* hip_stream, double* h_ms, double* h_dropped) {
+    if (!d_items || !d_out || !d_cursor || !h_ms || !h_dropped || n < 1 || n > 0x7FFFFFFFull)
+        return -1;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint32_t cap = (uint32_t)(n / kBins * 5 / 4 + kBinFlush);
+    if ((size_t)cap * kBins * 12 > out_bytes) return -1;
+    const size_t lds_bytes = ((size_t)kBins * kBinStage * 3 + 3 * kBins) * 4;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(bin_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+        return -3;
+    int n_cu = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return -3;
+    const int rc = time_second_run(s, [&] {
+        (void)hipMemsetAsync(d_cursor, 0, (kBins + 1) * sizeof(uint32_t), s);
+        hipLaunchKernelGGL(bin_kernel, dim3((unsigned)n_cu), dim3(kBinThreads), lds_bytes, s,
+                           static_cast<const uint32_t*>(d_items), n, 24, cap,
+                           static_cast<uint32_t*>(d_out), d_cursor);
+    }, h_ms);
+    if (rc != 0) return rc;
+    uint32_t dropped = 0;
+    if (hipMemcpy(&dropped, d_cursor + kBins, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return -3;
+    *h_dropped = (double)dropped;
+    return 0;
 }
 
 }  // extern "C"
