@@ -177,17 +177,19 @@ int read_total(surel_ctx* ctx, const int64_t* d_off, int64_t n, int64_t* h_rows)
 // error: the walk then reads the CSR directly).
 int make_edge_records(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* d_col_idx,
                       int32_t n_nodes, int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m,
-                      void** records) {
-    *records = nullptr;
+                      surel::EdgeRecords* records) {
+    *records = surel::EdgeRecords{};
     if (!surel::walks_want_records(n_edges, n_seeds, M, m)) return SUREL_OK;
-    const size_t need = (size_t)n_edges * 16;
+    surel::EdgeRecords plan = surel::edge_record_plan(n_nodes, n_edges);
+    const size_t need = surel::edge_record_bytes(plan, n_edges);
     (void)grow_buffer(ctx, &ctx->d_rec, &ctx->rec_bytes, need);
     if (ctx->rec_bytes < need) return SUREL_OK;
+    plan.data = ctx->d_rec;
     KernelSpan span(ctx, SUREL_K_EDGE_RECORDS);
-    if (surel::launch_edge_records(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges,
-                                   ctx->d_rec) != hipSuccess)
+    if (surel::launch_edge_records(ctx->stream, d_row_ptr, d_col_idx, n_nodes, n_edges, plan) !=
+        hipSuccess)
         return SUREL_E_HIP;
-    *records = ctx->d_rec;
+    *records = plan;
     return SUREL_OK;
 }
 
@@ -290,7 +292,7 @@ int surel_sample_walks(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t* 
     if (n_seeds == 0) return SUREL_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
-    void* records = nullptr;
+    surel::EdgeRecords records;
     if (int rc = make_edge_records(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, n_seeds, M, m,
                                    &records))
         return rc;
@@ -423,7 +425,7 @@ static int fused_launch(surel_ctx* ctx, const int32_t* d_row_ptr, const int32_t*
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* d_walks, int64_t cap_rows,
                         int64_t* d_rpe_off, int32_t* d_rpe_ids, uint16_t* d_rpe_cnt, int32_t* d_code,
                         uint32_t* slots, int64_t cap_T, unsigned long long* counters) {
-    void* records = nullptr;
+    surel::EdgeRecords records;
     if (int rc = make_edge_records(ctx, d_row_ptr, d_col_idx, n_nodes, n_edges, n_seeds, M, m,
                                    &records))
         return rc;

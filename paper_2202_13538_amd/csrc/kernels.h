@@ -6,19 +6,26 @@
 
 namespace surel {
 
-// walk.hip.  set_sizes (optional): int32[n_seeds], receives the number of distinct nodes of
-// every seed's walks; needs 1 + M*m <= 2048.  edge_records (optional): the per-edge neighbour
-// records that launch_edge_records made of this CSR (16 * n_edges bytes; worth making when
-// walks_want_records says so).
+// walk.hip.  The per-edge neighbour records that launch_edge_records makes of a CSR (layouts in
+// walk_core.h; worth making when walks_want_records says so): edge_record_plan picks the layout
+// for a graph, the caller provides edge_record_bytes(plan, n_edges) bytes in plan.data.
+struct EdgeRecords {
+    const void* data = nullptr;  // null: no records, the walk reads the CSR
+    int format = 0;
+    int id_bits = 0, lo_bits = 0;  // field widths of the packed layout
+};
 bool walks_want_records(int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m);
+EdgeRecords edge_record_plan(int32_t n_nodes, int64_t n_edges);
+size_t edge_record_bytes(const EdgeRecords& plan, int64_t n_edges);
+hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
+                               int32_t n_nodes, int64_t n_edges, const EdgeRecords& rec);
+
+// set_sizes (optional): int32[n_seeds], receives the number of distinct nodes of every seed's
+// walks; needs 1 + M*m <= 2048.
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
-                        int32_t* set_sizes, const void* edge_records, uint32_t* err);
-
-// Expands the CSR into edge_records (16 * n_edges bytes), see walk.hip.
-hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
-                               int32_t n_nodes, int64_t n_edges, void* edge_records);
+                        int32_t* set_sizes, const EdgeRecords& rec, uint32_t* err);
 
 // walk_rpe.hip.  Walks and the RPE table in one persistent kernel: writes walks,
 // rpe_off[0..n_seeds] and (unless ids is null) the rows.  lb: device scratch of
@@ -35,7 +42,7 @@ hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, cons
                            const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
                            uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
-                           int32_t* ids, uint16_t* cnt, const void* edge_records, uint64_t* lb,
+                           int32_t* ids, uint16_t* cnt, const EdgeRecords& rec, uint64_t* lb,
                            uint32_t spin_limit, uint32_t* err, int32_t* code = nullptr,
                            uint32_t* slots = nullptr, int64_t cap_T = 0,
                            unsigned long long* counters = nullptr);

@@ -28,27 +28,42 @@ namespace surel {
 constexpr int kWalkWavesPerBlock = 4;
 constexpr int kWalkChains = 2;  // walks a lane moves at a time
 
-// rec[e] = (col_idx[e], row_ptr[col_idx[e]], degree of col_idx[e], 0); an entry that names no
-// node, or whose row is malformed, gets id -1 (the walker will stay in place and flag it).
+// The record of every CSR entry e (layouts in walk_core.h): the neighbour col_idx[e], the start
+// of its row and its degree; an entry that names no node, or whose row is malformed, gets the
+// layout's "bad entry" id (the walker will stay in place and flag it).
+template <int kRec>
 __global__ void edge_record_kernel(const int32_t* __restrict__ row_ptr,
                                    const int32_t* __restrict__ col_idx, int32_t n_nodes,
-                                   int64_t n_edges, int4* __restrict__ rec) {
+                                   int64_t n_edges, int id_bits, int lo_bits,
+                                   void* __restrict__ rec) {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n_edges) return;
     const int32_t t = col_idx[e];
-    int4 r = make_int4(-1, 0, 0, 0);
+    bool ok = false;
+    int32_t lo = 0, hi = 0;
     if ((uint32_t)t < (uint32_t)n_nodes) {
-        const int32_t lo = row_ptr[t];
-        const int32_t hi = row_ptr[t + 1];
-        if (lo >= 0 && hi >= lo && (int64_t)hi <= n_edges) r = make_int4(t, lo, hi - lo, 0);
+        lo = row_ptr[t];
+        hi = row_ptr[t + 1];
+        ok = lo >= 0 && hi >= lo && (int64_t)hi <= n_edges;
     }
-    rec[e] = r;
+    if (kRec == kRecWide) {
+        static_cast<int4*>(rec)[e] = ok ? make_int4(t, lo, hi - lo, 0) : make_int4(-1, 0, 0, 0);
+    } else {
+        const uint32_t deg_big = (1u << rec_degree_bits(id_bits, lo_bits)) - 1u;
+        unsigned long long r = (unsigned long long)(uint32_t)n_nodes;  // bad entry
+        if (ok) {
+            const uint32_t deg = min((uint32_t)(hi - lo), deg_big);
+            r = (unsigned long long)(uint32_t)t | ((unsigned long long)(uint32_t)lo << id_bits) |
+                ((unsigned long long)deg << (id_bits + lo_bits));
+        }
+        static_cast<unsigned long long*>(rec)[e] = r;
+    }
 }
 
-template <bool kCount, bool kRec>
+template <bool kCount, int kRec>
 __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    const int4* __restrict__ rec, int32_t n_nodes, int64_t n_edges,
+    const void* __restrict__ rec, int id_bits, int lo_bits, int32_t n_nodes, int64_t n_edges,
     const int32_t* __restrict__ seeds, int64_t n_seeds, int32_t M, int32_t m, uint32_t key0,
     uint32_t key1, int32_t* __restrict__ walks, int32_t* __restrict__ set_sizes, int32_t slots,
     uint32_t* __restrict__ err) {
@@ -82,7 +97,7 @@ __global__ __launch_bounds__(kWalkWavesPerBlock* kWave) void walk_kernel(
         n_distinct = distinct_insert(table, slots, (uint32_t)u, lane == 0);
     }
 
-    const WalkGraph g{row_ptr, col_idx, rec, n_nodes, n_edges};
+    const WalkGraph g{row_ptr, col_idx, rec, id_bits, lo_bits, n_nodes, n_edges};
     int32_t u_lo, u_deg;
     bool bad_graph = seed_row(g, u, &u_lo, &u_deg);
     for (int w0 = 0; w0 < M; w0 += kWalkChains * kWave) {
@@ -115,9 +130,30 @@ bool walks_want_records(int64_t n_edges, int64_t n_seeds, int32_t M, int32_t m) 
     return m >= 2 && n_edges > 0 && n_seeds * (int64_t)M * (m - 1) >= 4 * n_edges;
 }
 
-template <bool kCount, bool kRec>
+static int bits_for(uint64_t max_value) {  // bits that hold 0 .. max_value
+    int b = 1;
+    while (b < 64 && (max_value >> b) != 0) b += 1;
+    return b;
+}
+
+EdgeRecords edge_record_plan(int32_t n_nodes, int64_t n_edges) {
+    EdgeRecords plan;
+    plan.id_bits = bits_for((uint64_t)n_nodes);   // n_nodes itself marks a bad entry
+    plan.lo_bits = bits_for((uint64_t)n_edges);
+    // packed records where they matter (an array well beyond the caches) and where ordinary
+    // degrees fit their field; the wide layout otherwise
+    const bool packed = n_edges >= (1ll << 22) && rec_degree_bits(plan.id_bits, plan.lo_bits) >= 12;
+    plan.format = packed ? kRecPacked : kRecWide;
+    return plan;
+}
+
+size_t edge_record_bytes(const EdgeRecords& plan, int64_t n_edges) {
+    return (size_t)n_edges * (plan.format == kRecPacked ? 8 : 16);
+}
+
+template <bool kCount, int kRec>
 static hipError_t launch_walks_cfg(hipStream_t stream, const int32_t* row_ptr,
-                                   const int32_t* col_idx, const int4* rec, int32_t n_nodes,
+                                   const int32_t* col_idx, const EdgeRecords& rec, int32_t n_nodes,
                                    int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                                    int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
                                    int32_t* set_sizes, uint32_t* err) {
@@ -131,39 +167,50 @@ static hipError_t launch_walks_cfg(hipStream_t stream, const int32_t* row_ptr,
         if (rc != hipSuccess) return rc;
     }
     hipLaunchKernelGGL((walk_kernel<kCount, kRec>), dim3((unsigned)blocks),
-                       dim3(kWalkWavesPerBlock * kWave), lds_bytes, stream, row_ptr, col_idx, rec,
-                       n_nodes, n_edges, seeds, n_seeds, M, m,
+                       dim3(kWalkWavesPerBlock * kWave), lds_bytes, stream, row_ptr, col_idx,
+                       rec.data, rec.id_bits, rec.lo_bits, n_nodes, n_edges, seeds, n_seeds, M, m,
                        (uint32_t)(rng_seed & 0xFFFFFFFFull), (uint32_t)(rng_seed >> 32), walks,
                        set_sizes, slots, err);
     return hipGetLastError();
 }
 
 hipError_t launch_edge_records(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
-                               int32_t n_nodes, int64_t n_edges, void* edge_records) {
+                               int32_t n_nodes, int64_t n_edges, const EdgeRecords& rec) {
     if (n_edges <= 0) return hipSuccess;
     const int threads = 256;
-    hipLaunchKernelGGL(edge_record_kernel, dim3((unsigned)((n_edges + threads - 1) / threads)),
-                       dim3(threads), 0, stream, row_ptr, col_idx, n_nodes, n_edges,
-                       static_cast<int4*>(edge_records));
+    const dim3 grid((unsigned)((n_edges + threads - 1) / threads));
+    void* data = const_cast<void*>(rec.data);
+    if (rec.format == kRecPacked) {
+        hipLaunchKernelGGL(edge_record_kernel<kRecPacked>, grid, dim3(threads), 0, stream, row_ptr,
+                           col_idx, n_nodes, n_edges, rec.id_bits, rec.lo_bits, data);
+    } else {
+        hipLaunchKernelGGL(edge_record_kernel<kRecWide>, grid, dim3(threads), 0, stream, row_ptr,
+                           col_idx, n_nodes, n_edges, rec.id_bits, rec.lo_bits, data);
+    }
     return hipGetLastError();
+}
+
+template <bool kCount>
+static hipError_t launch_walks_c(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
+                                 const EdgeRecords& rec, int32_t n_nodes, int64_t n_edges,
+                                 const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
+                                 uint64_t rng_seed, int32_t* walks, int32_t* set_sizes,
+                                 uint32_t* err) {
+#define SUREL_WALK_ARGS \
+    stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m, rng_seed, walks, set_sizes, err
+    if (rec.data == nullptr) return launch_walks_cfg<kCount, kRecNone>(SUREL_WALK_ARGS);
+    if (rec.format == kRecPacked) return launch_walks_cfg<kCount, kRecPacked>(SUREL_WALK_ARGS);
+    return launch_walks_cfg<kCount, kRecWide>(SUREL_WALK_ARGS);
 }
 
 hipError_t launch_walks(hipStream_t stream, const int32_t* row_ptr, const int32_t* col_idx,
                         int32_t n_nodes, int64_t n_edges, const int32_t* seeds, int64_t n_seeds,
                         int32_t M, int32_t m, uint64_t rng_seed, int32_t* walks,
-                        int32_t* set_sizes, const void* edge_records, uint32_t* err) {
+                        int32_t* set_sizes, const EdgeRecords& rec, uint32_t* err) {
     if (n_seeds == 0) return hipSuccess;
-    const int4* rec = static_cast<const int4*>(edge_records);
-#define SUREL_WALK_ARGS \
-    stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m, rng_seed, walks, set_sizes, err
-    if (set_sizes != nullptr) {
-        if (rec != nullptr) return launch_walks_cfg<true, true>(SUREL_WALK_ARGS);
-        return launch_walks_cfg<true, false>(SUREL_WALK_ARGS);
-    }
-    if (rec != nullptr) return launch_walks_cfg<false, true>(SUREL_WALK_ARGS);
-    return launch_walks_cfg<false, false>(SUREL_WALK_ARGS);
+    if (set_sizes != nullptr) return launch_walks_c<true>(SUREL_WALK_ARGS);
+    return launch_walks_c<false>(SUREL_WALK_ARGS);
 #undef SUREL_WALK_ARGS
 }
-
 
 }  // namespace surel

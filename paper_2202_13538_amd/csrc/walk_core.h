@@ -6,13 +6,28 @@
 
 namespace surel {
 
-// The graph as a walker sees it: the CSR, and optionally the per-edge neighbour records
-// rec[e] = (col_idx[e], row start of that neighbour, its degree, 0), id -1 for an entry that
-// names no node or whose row is malformed.
+// Per-edge neighbour records: one record per CSR entry e with the neighbour col_idx[e], the start
+// of that neighbour's row and its degree, so that a step is one gather instead of two dependent
+// ones.  Two layouts:
+//   kRecWide    int4 (id, row start, degree, 0); id -1 for an entry that names no node or whose
+//               row is malformed;
+//   kRecPacked  one 64-bit word, id in the low id_bits, row start in the next lo_bits, degree in
+//               the rest; id = n_nodes marks a bad entry, a degree field of all ones means "does
+//               not fit, it is row_ptr[id + 1] - row start".  Half the bytes: the seed's own row
+//               and the rows of its neighbours take fewer cache lines.
+constexpr int kRecNone = 0, kRecWide = 1, kRecPacked = 2;
+
+// Bits of the degree field of a packed record: what the two other fields leave, 31 at most.
+__host__ __device__ constexpr int rec_degree_bits(int id_bits, int lo_bits) {
+    return 64 - id_bits - lo_bits < 31 ? 64 - id_bits - lo_bits : 31;
+}
+
+// The graph as a walker sees it: the CSR, and optionally the records in one of the layouts.
 struct WalkGraph {
     const int32_t* __restrict__ row_ptr;
     const int32_t* __restrict__ col_idx;
-    const int4* __restrict__ rec;
+    const void* __restrict__ rec;
+    int id_bits, lo_bits;  // kRecPacked only
     int32_t n_nodes;
     int64_t n_edges;
 };
@@ -34,7 +49,7 @@ __device__ __forceinline__ bool seed_row(const WalkGraph& g, int32_t u, int32_t*
 // ignores.  Step s uses word (s-1)&3 of Philox(counter (u, w, (s-1)>>2, 0), key).
 // Returns true if a malformed CSR row or a neighbour id outside the graph was met (the
 // walker then stays in place for that step).
-template <bool kRec, int C, typename Visit>
+template <int kRec, int C, typename Visit>
 __device__ __forceinline__ bool walk_many(const WalkGraph& g, int32_t u, int32_t u_lo, int32_t u_deg,
                                           const int (&w)[C], const bool (&active)[C], int m,
                                           uint32_t key0, uint32_t key1, int32_t* const (&row)[C],
@@ -58,14 +73,15 @@ __device__ __forceinline__ bool walk_many(const WalkGraph& g, int32_t u, int32_t
         for (int j = 0; j < 4; ++j) {
             const int s = s0 + j;
             if (s <= m) {
-                if (kRec) {
+                if (kRec == kRecWide) {
+                    const int4* rec = static_cast<const int4*>(g.rec);
                     int4 nb[C];
 #pragma unroll
                     for (int c = 0; c < C; ++c) {
                         const bool go = active[c] && cur_deg[c] > 0;
                         const uint32_t pick = go ? r[c][j] % (uint32_t)cur_deg[c] : 0u;
                         nb[c] = make_int4(cur[c], cur_lo[c], cur_deg[c], 0);
-                        if (go) nb[c] = g.rec[(int64_t)cur_lo[c] + (int64_t)pick];
+                        if (go) nb[c] = rec[(int64_t)cur_lo[c] + (int64_t)pick];
                     }
 #pragma unroll
                     for (int c = 0; c < C; ++c) {
@@ -75,6 +91,36 @@ __device__ __forceinline__ bool walk_many(const WalkGraph& g, int32_t u, int32_t
                             cur[c] = nb[c].x;
                             cur_lo[c] = nb[c].y;
                             cur_deg[c] = nb[c].z;
+                        }
+                    }
+                } else if (kRec == kRecPacked) {
+                    const unsigned long long* rec = static_cast<const unsigned long long*>(g.rec);
+                    const int deg_shift = g.id_bits + g.lo_bits;
+                    const uint32_t deg_big = (1u << rec_degree_bits(g.id_bits, g.lo_bits)) - 1u;
+                    unsigned long long nb[C];
+                    bool go[C];
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        go[c] = active[c] && cur_deg[c] > 0;
+                        const uint32_t pick = go[c] ? r[c][j] % (uint32_t)cur_deg[c] : 0u;
+                        nb[c] = 0ull;
+                        if (go[c]) nb[c] = rec[(int64_t)cur_lo[c] + (int64_t)pick];
+                    }
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        if (!go[c]) continue;
+                        const int32_t id = (int32_t)(nb[c] & ((1ull << g.id_bits) - 1ull));
+                        const int32_t lo = (int32_t)((nb[c] >> g.id_bits) & ((1ull << g.lo_bits) - 1ull));
+                        uint32_t deg = (uint32_t)(nb[c] >> deg_shift) & deg_big;
+                        if (id >= g.n_nodes) {
+                            bad_graph = true;
+                        } else {
+                            // a degree too large for its field: the record's row was validated
+                            // when the records were made, so its end can be taken from the CSR
+                            if (deg == deg_big) deg = (uint32_t)(g.row_ptr[id + 1] - lo);
+                            cur[c] = id;
+                            cur_lo[c] = lo;
+                            cur_deg[c] = (int32_t)deg;
                         }
                     }
                 } else {

@@ -40,10 +40,10 @@ struct CodeSet {
 // kCodes: every finished row's count vector is looked up in the hash set while the row still
 // lies in LDS (Algorithm 1's last step, pruning, done on the fly as well), and its slot number
 // goes to cs.code; cnt may then be null.
-template <int E, bool kRec, bool kCodes>
+template <int E, int kRec, bool kCodes>
 __global__ __launch_bounds__(1024) void walk_rpe_kernel(
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    const int4* __restrict__ rec, int32_t n_nodes, int64_t n_edges,
+    const void* __restrict__ rec, int id_bits, int lo_bits, int32_t n_nodes, int64_t n_edges,
     const int32_t* __restrict__ seeds, int64_t n_seeds, int32_t M, int32_t m, uint32_t key0,
     uint32_t key1, uint32_t magic_L, int32_t* __restrict__ walks, int64_t cap_rows,
     int64_t* __restrict__ rpe_off, int32_t* __restrict__ ids, uint16_t* __restrict__ cnt,
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(1024) void walk_rpe_kernel(
     // the seed's walks [M][L] while it is walked, the rows of the seed before while they go out
     uint32_t* wave_lds = lds32 + wave * lds_words_per_wave;
     int32_t* block = reinterpret_cast<int32_t*>(wave_lds);
-    const WalkGraph g{row_ptr, col_idx, rec, n_nodes, n_edges};
+    const WalkGraph g{row_ptr, col_idx, rec, id_bits, lo_bits, n_nodes, n_edges};
 
     // the seed whose offset and rows are not written yet: its sorted keys stay in registers
     uint32_t x[E];
@@ -203,7 +203,7 @@ static int walk_rpe_lds_words(int M, int m) {
 
 #define SUREL_WR_PARAMS                                                                           \
     hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t *row_ptr,                      \
-        const int32_t *col_idx, const int4 *rec, int32_t n_nodes, int64_t n_edges,                \
+        const int32_t *col_idx, const EdgeRecords &rec, int32_t n_nodes, int64_t n_edges,          \
         const int32_t *seeds, int64_t n_seeds, int32_t M, int32_t m, uint64_t rng_seed,           \
         int32_t *walks, int64_t cap_rows, int64_t *rpe_off, int32_t *ids, uint16_t *cnt,          \
         uint64_t *lb, uint32_t spin_limit, uint32_t *err, const CodeSet &cs
@@ -211,7 +211,7 @@ static int walk_rpe_lds_words(int M, int m) {
     stream, max_lds_bytes, n_cu, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M, m,   \
         rng_seed, walks, cap_rows, rpe_off, ids, cnt, lb, spin_limit, err, cs
 
-template <int E, bool kRec, bool kCodes>
+template <int E, int kRec, bool kCodes>
 static hipError_t launch_walk_rpe_erc(SUREL_WR_PARAMS) {
     const int words = walk_rpe_lds_words(M, m);
     const size_t per_wave = (size_t)words * 4;
@@ -255,13 +255,14 @@ static hipError_t launch_walk_rpe_erc(SUREL_WR_PARAMS) {
     if (rc != hipSuccess) return rc;
     const uint32_t magic_L = 65536u / (uint32_t)(m + 1) + 1u;
     hipLaunchKernelGGL((walk_rpe_kernel<E, kRec, kCodes>), dim3((unsigned)blocks), dim3(W * kWave),
-                       lds_bytes, stream, row_ptr, col_idx, rec, n_nodes, n_edges, seeds, n_seeds, M,
+                       lds_bytes, stream, row_ptr, col_idx, rec.data, rec.id_bits, rec.lo_bits, n_nodes,
+                       n_edges, seeds, n_seeds, M,
                        m, (uint32_t)(rng_seed & 0xFFFFFFFFull), (uint32_t)(rng_seed >> 32), magic_L,
                        walks, cap_rows, rpe_off, ids, cnt, words, lb, spin_limit, err, cs);
     return hipGetLastError();
 }
 
-template <int E, bool kRec>
+template <int E, int kRec>
 static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
     if (cs.code != nullptr) return launch_walk_rpe_erc<E, kRec, true>(SUREL_WR_ARGS);
     return launch_walk_rpe_erc<E, kRec, false>(SUREL_WR_ARGS);
@@ -269,18 +270,18 @@ static hipError_t launch_walk_rpe_er(SUREL_WR_PARAMS) {
 
 template <int E>
 static hipError_t launch_walk_rpe_e(SUREL_WR_PARAMS) {
-    if (rec != nullptr) return launch_walk_rpe_er<E, true>(SUREL_WR_ARGS);
-    return launch_walk_rpe_er<E, false>(SUREL_WR_ARGS);
+    if (rec.data == nullptr) return launch_walk_rpe_er<E, kRecNone>(SUREL_WR_ARGS);
+    if (rec.format == kRecPacked) return launch_walk_rpe_er<E, kRecPacked>(SUREL_WR_ARGS);
+    return launch_walk_rpe_er<E, kRecWide>(SUREL_WR_ARGS);
 }
 
 hipError_t launch_walk_rpe(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* row_ptr,
                            const int32_t* col_idx, int32_t n_nodes, int64_t n_edges,
                            const int32_t* seeds, int64_t n_seeds, int32_t M, int32_t m,
                            uint64_t rng_seed, int32_t* walks, int64_t cap_rows, int64_t* rpe_off,
-                           int32_t* ids, uint16_t* cnt, const void* edge_records, uint64_t* lb,
+                           int32_t* ids, uint16_t* cnt, const EdgeRecords& rec, uint64_t* lb,
                            uint32_t spin_limit, uint32_t* err, int32_t* code, uint32_t* slots,
                            int64_t cap_T, unsigned long long* counters) {
-    const int4* rec = static_cast<const int4*>(edge_records);
     const CodeSet cs{code, slots, code ? prune_slot_mask(cap_T) : 0u, cap_T, counters};
     const int n_key = M * (m + 1);
 #define SUREL_WR_CASE(E_) \

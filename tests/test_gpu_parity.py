@@ -689,6 +689,56 @@ def test_largest_node_ids(ctx):
     assert int(out["walks"].max()) == n - 1
 
 
+def hub_and_ring(n_leaves):
+    """Node 0 joined to every one of n_leaves leaves, the leaves joined in a chain."""
+    leaf = np.arange(1, n_leaves + 1, dtype=np.int64)
+    deg = np.full(n_leaves + 1, 3, dtype=np.int64)
+    deg[0], deg[1], deg[n_leaves] = n_leaves, 2, 2
+    rp = np.zeros(n_leaves + 2, dtype=np.int64)
+    np.cumsum(deg, out=rp[1:])
+    ci = np.empty(int(rp[-1]), dtype=np.int32)
+    ci[:n_leaves] = leaf
+    ci[rp[1:-1]] = 0                                       # every leaf's row: hub, left, right
+    ci[rp[2:-1] + 1] = leaf[1:] - 1
+    ci[rp[1:-2] + 2 - (leaf[:-1] == 1)] = leaf[:-1] + 1
+    return rp.astype(np.int32), ci
+
+
+def test_packed_edge_records_and_a_degree_beyond_their_field(ctx):
+    # from 2^22 edge entries on, the walks read 8-byte neighbour records; the hub's degree
+    # (1.2 M) does not fit the 20 bits the record leaves for it and is taken from the CSR
+    n_leaves = 1_200_000
+    rp, ci = hub_and_ring(n_leaves)
+    assert ci.size >= 1 << 22 and np.all(np.diff(rp) > 0)
+    rng = np.random.default_rng(5)
+    seeds = rng.integers(0, n_leaves + 1, size=50_000, dtype=np.int32)
+    seeds[:3] = [0, 1, n_leaves]
+    M, m = 200, 3
+    assert seeds.size * M * (m - 1) >= 4 * ci.size         # enough steps to make the records
+    w = oracle.sample_walks(rp, ci, seeds, M, m, 11)
+    assert (w[:, :, 1:] == 0).mean() > 0.2                 # walks do pass through the hub
+    table = oracle.build_rpe(w)
+    d_rp, d_ci, d_seeds = dev(rp), dev(ci), dev(seeds)
+    walks = binding.sample_walks(ctx, d_rp, d_ci, d_seeds, M, m, 11)
+    assert ctx.check() == 0
+    assert np.array_equal(walks.cpu().numpy(), w), "walks differ"
+    del walks
+    f_walks, f_off, f_ids, f_cnt = binding.sample_walks_rpe(ctx, d_rp, d_ci, d_seeds, M, m, 11)
+    assert ctx.check() == 0
+    assert np.array_equal(f_walks.cpu().numpy(), w), "fused: walks differ"
+    assert_table_equal((f_off, f_ids, f_cnt), table, "fused rpe")
+    # an entry that names no node: flagged, the walker stays where it is
+    bad = ci.copy()
+    bad[rp[7]] = n_leaves + 1 + 40
+    walks = binding.sample_walks(ctx, d_rp, dev(bad), dev(np.full(seeds.size, 7, dtype=np.int32)),
+                                 M, m, 11)
+    assert ctx.check() == binding.DEV_BAD_GRAPH
+    got = walks.cpu().numpy()
+    assert ((got >= 0) & (got <= n_leaves)).all()
+    stay = (got[:, :, 1] == 7)
+    assert 0.2 < stay.mean() < 0.5                         # one of node 7's three entries
+
+
 def test_one_call_rpe_ids_capacity(ctx):
     # surel_sample_walks_rpe_ids with too little room: for the table, for the distinct vectors
     wl = synth.Workload("t", "rmat", 256, 900, 0.0, 20, 3, 0, 2, "uniform", graph_seed=3)
