@@ -16,15 +16,20 @@
 // Which union row a node lands in, and which table rows feed it ("sources"):
 //   - pairs: a merge path.  Lane l owns merged positions [l*VT, (l+1)*VT): a binary search on
 //     its diagonal finds where it starts in both lists, then it merges VT steps serially,
-//     list 0 first on ties, so an equal pair is one row with two sources.
+//     list 0 first on ties, so an equal pair is one row with two sources.  What the merge
+//     leaves behind is two bits per union row ("list 0 has this node", "list 1 has it"), kept
+//     as two bit masks in LDS: both lists are ascending like the union, so the table row of
+//     list j that feeds union row r is the number of rows before r whose bit j is set, a
+//     population count away for the lane that handles row r.
 //   - triples: ranks.  A row is owned by the first list that holds its node; its position is
 //     #{a in list 0 : a < x} + sum over j >= 1 of #{b in list j : b < x, b in no earlier list},
-//     each term a lower bound in LDS plus a lookup in a prefix count of "new" elements.
+//     each term a lower bound in LDS plus a lookup in a prefix count of "new" elements; the
+//     sources go to LDS as one 16-bit index per (list, row).
 // Count vectors.  For the usual walk lengths (m + 1 = 2 .. 6 entries per vector) a lane takes
 // one union row: it gathers the row's K vectors from the table (zeros where the node is
 // absent), packs them into the row's K*L/2 words in registers, and the row goes out either
 // straight from the registers (vectors of whole words) or through a small LDS tile that is
-// streamed out as whole words (pairs of vectors with an odd number of entries, whose rows
+// streamed out 16 bytes per lane (pairs of vectors with an odd number of entries, whose rows
 // straddle words).  Other
 // shapes take a generic path: a lane moves one (row, list) vector into an LDS tile laid out
 // like the output.  The kernel keeps its LDS footprint small on purpose: the vectors are read
@@ -37,14 +42,10 @@ namespace surel {
 constexpr uint16_t kNoSrc = 0xFFFFu;
 constexpr uint32_t kNoId = 0xFFFFFFFFu;  // no node id reaches 2^28
 constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output tile
-// Rounds of 64 union rows whose gathers a wave has in flight together: 5 for pairs (4 where the
-// smaller LDS footprint of join_tile_over_ids lets a sixth workgroup onto the compute unit, which
-// needs the registers of a round), 4 for larger tuples.  More rounds shorten a wave's chain of
-// memory round trips but cost registers, and the launch is bound by its waves in flight: 8
-// rounds (118 registers, 16 waves per compute unit) took 5.75 ms on the 2.9M-node workload, 3
-// to 5 rounds (20 waves) 5.59.
+// Rounds of 64 union rows whose gathers a wave has in flight together.  More rounds shorten a
+// wave's chain of memory round trips but cost registers, and the launch is bound by its waves
+// in flight.
 constexpr int kGatherRoundsPairs = 5;
-constexpr int kGatherRoundsPairsSmallLds = 4;
 constexpr int kGatherRoundsTuples = 4;
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
@@ -67,9 +68,11 @@ __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint
 struct JoinLds {
     int ids;      // [K][max_set] uint32
     int new_pre;  // [K-1][max_set+1] uint16 (triples only)
+    int mask;     // [2][mask_words] uint32: which union rows lists 0 and 1 feed (pairs, fill only)
+    int mask_words;
     int src;      // [K][K*max_set] uint16: table row of list j that feeds union row r, or kNoSrc
-    int tile;     // [kJoinChunkRows][K][L] uint16 (fill only)
-    int total;
+    int tile;     // fill only; 16-byte aligned
+    int total;    // a multiple of 4 words, so that every wave's part starts 16-byte aligned
 };
 
 // Rows whose K*L counts fill whole 32-bit words are put together in registers and written
@@ -78,17 +81,17 @@ __host__ __device__ constexpr bool join_rows_direct(int K, int LT) {
     return LT > 0 && (K * LT) % 2 == 0;
 }
 
-// The LDS tile is needed by the generic path and by pairs whose count vectors have an odd
-// number of entries (their rows are put together in the tile before they go out).
+// The LDS tile is needed by the generic path ([kJoinChunkRows][K][L] uint16) and by pairs whose
+// count vectors have an odd number of entries (their rows are put together in the tile before
+// they go out: 64 rows of LT words, plus up to 3 words in front so that the tile is aligned
+// like the output it goes to).
 __host__ __device__ constexpr bool join_uses_tile(int K, int LT) {
     return !join_rows_direct(K, LT) || (K == 2 && LT % 2 == 1);
 }
 
-// Where rows go out of registers but through the tile (pairs of odd-length vectors), a query's
-// ids are written out before its first count, and the tile then takes the place of the id lists:
-// less LDS per wave means more waves per compute unit, which is what this kernel runs on.
-__host__ __device__ constexpr bool join_tile_over_ids(int K, int LT) {
-    return join_rows_direct(K, LT) && join_uses_tile(K, LT);
+// Pairs keep their sources as bit masks; the generic path expands them to indices.
+__host__ __device__ constexpr bool join_uses_src(int K, int LT) {
+    return K != 2 || !join_rows_direct(K, LT);
 }
 
 __host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L, bool fill,
@@ -96,26 +99,29 @@ __host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L,
     JoinLds o{};
     o.ids = 0;
     o.new_pre = o.ids + K * max_set;
-    o.src = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
-    const int src_end = o.src + (fill ? (K * K * max_set + 1) / 2 : 0);
-    const int tile_words = fill && join_uses_tile(K, LT) ? (kJoinChunkRows * K * L + 1) / 2 : 0;
-    if (join_tile_over_ids(K, LT) && tile_words <= K * max_set) {
-        o.tile = o.ids;
-        o.total = src_end;
-    } else {
-        o.tile = src_end;
-        o.total = src_end + tile_words;
-    }
+    o.mask = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
+    o.mask += o.mask & 1;  // the masks are read as 64-bit words
+    // one bit per union row, in whole 64-bit words, and two words of slack: a lane's bits are
+    // put in as three 32-bit words at a time
+    o.mask_words = (K == 2 && fill) ? 2 * ((2 * max_set + 63) / 64) + 2 : 0;
+    o.src = o.mask + 2 * o.mask_words;
+    const int src_end = o.src + (fill && join_uses_src(K, LT) ? (K * K * max_set + 1) / 2 : 0);
+    o.tile = (src_end + 3) & ~3;
+    int tile_words = 0;
+    if (fill && join_uses_tile(K, LT))
+        tile_words = join_rows_direct(K, LT) ? kWave * LT + 4 : (kJoinChunkRows * K * L + 1) / 2;
+    o.total = (o.tile + tile_words + 3) & ~3;
     return o;
 }
 
-// Pairs: union size and (when kFill) the sources of every union row, by merge path.
-template <bool kFill>
+// Pairs: union size by merge path and, with kFlags, the two bit masks of the union rows (bit r
+// of amask: list A holds the node of row r; bmask likewise).  The masks must be zero on entry.
+template <bool kFlags>
 __device__ __forceinline__ int union_pair_merge_path(const uint32_t* A, int nA, const uint32_t* B,
-                                                     int nB, uint16_t* src, int src_stride,
+                                                     int nB, uint32_t* amask, uint32_t* bmask,
                                                      int lane) {
     const int T = nA + nB;
-    const int VT = (T + kWave - 1) / kWave;
+    const int VT = (T + kWave - 1) / kWave;  // at most 64: a set has at most 2048 nodes
     const int d0 = min(lane * VT, T);
     const int d1 = min(d0 + VT, T);
     // split of the first d0 merged elements: a0 from A (ties go to A first), d0 - a0 from B
@@ -129,56 +135,80 @@ __device__ __forceinline__ int union_pair_merge_path(const uint32_t* A, int nA, 
             hi = mid;
         }
     }
-    const int a0 = lo;
-    const int b0 = d0 - lo;
+    int a = lo, b = d0 - lo;
 
-    // pass 1: rows this lane emits.  A B element equal to the last A element taken is the
-    // same node (ids are distinct inside a list) and adds no row.
+    // The lane's VT merge steps.  Every step that takes an A element emits a row; a step that
+    // takes a B element emits one unless it equals the last A element taken (the same node:
+    // ids are distinct inside a list), which may have been taken by the lane before this one.
+    // Only the list that moved is read again.
     int n_emit = 0;
-    {
-        int a = a0, b = b0;
-        uint32_t last_a = a > 0 ? A[a - 1] : kNoId;
-        for (int d = d0; d < d1; ++d) {
-            const uint32_t va = a < nA ? A[a] : kNoId;
-            const uint32_t vb = b < nB ? B[b] : kNoId;
-            const bool take_a = (b >= nB) || (a < nA && va <= vb);
-            if (take_a) {
-                n_emit += 1;
-                last_a = va;
-                a += 1;
-            } else {
-                n_emit += (vb != last_a) ? 1 : 0;
-                b += 1;
+    uint64_t fa = 0, fb = 0;  // bit i: this lane's i-th row has a source in A / in B
+    uint32_t last_a = a > 0 ? A[a - 1] : kNoId;
+    uint32_t va = a < nA ? A[a] : kNoId;
+    uint32_t vb = b < nB ? B[b] : kNoId;
+    for (int d = d0; d < d1; ++d) {
+        const bool take_a = (b >= nB) || (a < nA && va <= vb);
+        if (take_a) {
+            if (kFlags) {
+                fa |= 1ull << n_emit;
+                if (b < nB && vb == va) fb |= 1ull << n_emit;
             }
+            n_emit += 1;
+            last_a = va;
+            a += 1;
+        } else {
+            if (vb != last_a) {
+                if (kFlags) fb |= 1ull << n_emit;
+                n_emit += 1;
+            }
+            b += 1;
         }
+        const uint32_t* list = take_a ? A : B;
+        const int at = take_a ? a : b;
+        const bool more = at < (take_a ? nA : nB);
+        const uint32_t next = more ? list[at] : kNoId;
+        va = take_a ? next : va;
+        vb = take_a ? vb : next;
     }
     const int incl = (int)wave_incl_sum((uint32_t)n_emit);
     const int n_out = (int)wave_bcast_u32((uint32_t)incl, kWave - 1);
-    if (kFill) {
-        int row = incl - n_emit;
-        int a = a0, b = b0;
-        uint32_t last_a = a > 0 ? A[a - 1] : kNoId;
-        for (int d = d0; d < d1; ++d) {
-            const uint32_t va = a < nA ? A[a] : kNoId;
-            const uint32_t vb = b < nB ? B[b] : kNoId;
-            const bool take_a = (b >= nB) || (a < nA && va <= vb);
-            if (take_a) {
-                src[row] = (uint16_t)a;
-                src[src_stride + row] = (b < nB && vb == va) ? (uint16_t)b : kNoSrc;
-                row += 1;
-                last_a = va;
-                a += 1;
-            } else {
-                if (vb != last_a) {
-                    src[row] = kNoSrc;
-                    src[src_stride + row] = (uint16_t)b;
-                    row += 1;
-                }
-                b += 1;
-            }
+    if (kFlags) {
+        // the lane's rows start at row0: its bits go in there, as up to three 32-bit words
+        const int row0 = incl - n_emit;
+        const int w = row0 >> 5;
+        const int sh = row0 & 31;
+        const uint64_t fl[2] = {fa, fb};
+        uint32_t* const mask[2] = {amask, bmask};
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint64_t low = fl[j] << sh;
+            const uint32_t w0 = (uint32_t)low;
+            const uint32_t w1 = (uint32_t)(low >> 32);
+            const uint32_t w2 = sh ? (uint32_t)(fl[j] >> (64 - sh)) : 0u;
+            if (w0) atomicOr(mask[j] + w, w0);
+            if (w1) atomicOr(mask[j] + w + 1, w1);
+            if (w2) atomicOr(mask[j] + w + 2, w2);
         }
     }
     return n_out;
+}
+
+// The sources of the 64 union rows r0 .. r0+63 of a pair, from the masks: lane l learns for
+// row r0 + l whether list j feeds it and from which of the list's rows.  before[j] = rows of
+// list j that feed union rows below r0; it is moved on to r0 + 64.  A source index is checked
+// against the list's length, which only a malformed (unsorted) table can exceed.
+__device__ __forceinline__ void pair_sources(const uint32_t* mask, int mask_words, int r0,
+                                             const int (&n)[2], int (&before)[2], int lane,
+                                             bool (&present)[2], int (&index)[2]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint64_t bits = *reinterpret_cast<const uint64_t*>(mask + j * mask_words + (r0 >> 5));
+        const int rank = (int)__builtin_amdgcn_mbcnt_hi(
+            (uint32_t)(bits >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bits, 0u));
+        index[j] = before[j] + rank;
+        present[j] = ((bits >> lane) & 1ull) != 0ull && index[j] < n[j];
+        before[j] += __popcll(bits);
+    }
 }
 
 // Any K: union size and (when kFill) the sources of every union row, by ranks.
@@ -289,6 +319,7 @@ __device__ __forceinline__ int join_prepare(
     const JoinLds lay = join_lds_layout(K, max_set, L, kSrc, LT);
     uint32_t* ids_lds = base + lay.ids;
     uint16_t* new_pre = reinterpret_cast<uint16_t*>(base + lay.new_pre);
+    uint32_t* mask = base + lay.mask;
     uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
     const int src_stride = K * max_set;
 
@@ -328,8 +359,27 @@ __device__ __forceinline__ int join_prepare(
 
     int n_out;
     if constexpr (K == 2) {
-        n_out = union_pair_merge_path<kSrc>(ids_lds, jq.n[0], ids_lds + max_set, jq.n[1], src,
-                                            src_stride, lane);
+        if (kSrc) {
+            for (int t = lane; t < 2 * lay.mask_words; t += kWave) mask[t] = 0u;
+            wave_sync();
+        }
+        n_out = union_pair_merge_path<kSrc>(ids_lds, jq.n[0], ids_lds + max_set, jq.n[1], mask,
+                                            mask + lay.mask_words, lane);
+        if constexpr (kSrc && join_uses_src(K, LT)) {
+            // the generic path wants an index per (list, row)
+            wave_sync();
+            int before[2] = {0, 0};
+            for (int r0 = 0; r0 < n_out; r0 += kWave) {
+                bool present[2];
+                int index[2];
+                pair_sources(mask, lay.mask_words, r0, jq.n, before, lane, present, index);
+                if (r0 + lane < n_out) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        src[j * src_stride + r0 + lane] = present[j] ? (uint16_t)index[j] : kNoSrc;
+                }
+            }
+        }
     } else {
         n_out = union_ranked<K, kSrc>(ids_lds, jq.n, max_set, new_pre, src, src_stride, lane);
     }
@@ -346,6 +396,7 @@ __device__ __forceinline__ void join_write(
     const int L = LT > 0 ? LT : m + 1;
     const JoinLds lay = join_lds_layout(K, max_set, L, true, LT);
     uint32_t* ids_lds = base + lay.ids;
+    const uint32_t* mask = base + lay.mask;
     uint16_t* src = reinterpret_cast<uint16_t*>(base + lay.src);
     uint32_t* tile32 = base + lay.tile;
     uint16_t* tile = reinterpret_cast<uint16_t*>(tile32);
@@ -358,29 +409,29 @@ __device__ __forceinline__ void join_write(
         // one lane per union row: the K count vectors (or zeros) are packed into the row's
         // K*L/2 words in registers and stored at the row's place
         constexpr int kWords = K * LT / 2;
+        constexpr int kHalf = LT / 2;       // whole words of a vector
+        constexpr int kCover = LT / 2 + 1;  // aligned words that cover a vector wherever it starts
         uint32_t* out_words = reinterpret_cast<uint32_t*>(out_cnt) + off * kWords;
         // kRounds rounds of 64 rows are gathered together (all their loads are in
         // flight before the first is waited for: a wave's time is a chain of memory round
         // trips), then the rounds go out one after the other
-        constexpr int kRounds = K != 2 ? kGatherRoundsTuples
-                                : join_tile_over_ids(K, LT) ? kGatherRoundsPairsSmallLds
-                                                            : kGatherRoundsPairs;
-        const uint32_t* cnt_words = reinterpret_cast<const uint32_t*>(rpe_cnt);
-        const bool ids_first = lay.tile == lay.ids;  // the tile will overwrite the id lists
-        if (ids_first) {
-            for (int r = lane; r < n_out; r += kWave) {
-                uint32_t id = 0;
+        constexpr int kRounds = K == 2 ? kGatherRoundsPairs : kGatherRoundsTuples;
+        const uint32_t absent32 = (uint32_t)absent16 * 0x10001u;
+        // Where list j's vectors are: the aligned word at or before the first of them (uniform),
+        // and whether that one starts in the word's upper half.  A lane then gets by with
+        // 32-bit arithmetic: its vector starts odd[j] + (row in the list) * LT counts in.  A
+        // list without rows has no vectors to point at: the table's first row stands in (the
+        // table has rows, or there would be no union rows to write).
+        const uint32_t* vec_words[K];
+        uint32_t odd[K];
 #pragma unroll
-                for (int j = K - 1; j >= 0; --j) {
-                    const uint16_t sj = src[j * src_stride + r];
-                    if ((int)sj < n[j]) id = ids_lds[j * max_set + sj];
-                }
-                out_ids[off + r] = (int32_t)id;
-            }
-            wave_sync();
+        for (int j = 0; j < K; ++j) {
+            const uint16_t* first = rpe_cnt + (n[j] > 0 ? lo[j] : 0) * LT;
+            odd[j] = (uint32_t)((reinterpret_cast<uintptr_t>(first) >> 1) & 1u);
+            vec_words[j] = reinterpret_cast<const uint32_t*>(first - odd[j]);
         }
+        int before[2] = {0, 0};
         for (int r0 = 0; r0 < n_out; r0 += kRounds * kWave) {
-            constexpr int kCover = LT / 2 + 1;  // aligned words that cover a vector
             uint32_t raw[kRounds][K][kCover + 1];
             uint32_t shift[kRounds][K];
             bool present[kRounds][K];
@@ -388,26 +439,37 @@ __device__ __forceinline__ void join_write(
 #pragma unroll
             for (int g = 0; g < kRounds; ++g) {
                 if (r0 + g * kWave >= n_out) break;  // wave-uniform: no round past the last row
-                const int r = min(r0 + g * kWave + lane, n_out - 1);
-                id[g] = 0;
+                int index[K];
+                if constexpr (K == 2) {
+                    pair_sources(mask, lay.mask_words, r0 + g * kWave, n, before, lane, present[g],
+                                 index);
+                } else {
+                    const int r = min(r0 + g * kWave + lane, n_out - 1);
 #pragma unroll
-                for (int j = K - 1; j >= 0; --j) {
-                    const uint16_t sj = src[j * src_stride + r];
-                    // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
-                    present[g][j] = (int)sj < n[j];
-                    if (!ids_first) {
-                        const uint32_t id_j = ids_lds[j * max_set + (present[g][j] ? sj : 0)];
-                        if (present[g][j]) id[g] = id_j;
+                    for (int j = 0; j < K; ++j) {
+                        // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
+                        index[j] = src[j * src_stride + r];
+                        present[g][j] = index[j] < n[j];
                     }
-                    // unconditional loads, from the table's first row where the list has no
-                    // row for the node: a branch would make every load wait for the one
-                    // before it.  A vector is read as the aligned words that cover it
-                    // (misaligned wide loads are taken apart lane by lane by the L1) and
-                    // shifted into place afterwards; the last word may reach one count past
-                    // the vector, never past the word that holds the table's last count.
-                    const int64_t first = present[g][j] ? (lo[j] + sj) * LT : 0;  // uint16 index
-                    shift[g][j] = (uint32_t)(first & 1) * 2u;
-                    const uint32_t* aligned = cnt_words + (first >> 1);
+                }
+                // the node's id, from the first list that has it (a lane past the last row
+                // reads the first id and stores nothing)
+                int id_at = 0;
+#pragma unroll
+                for (int j = K - 1; j >= 0; --j)
+                    if (present[g][j]) id_at = j * max_set + index[j];
+                id[g] = ids_lds[id_at];
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    // unconditional loads, from the list's first row where it has no row for
+                    // the node: a branch would make every load wait for the one before it.  A
+                    // vector is read as the aligned words that cover it (misaligned wide loads
+                    // are taken apart lane by lane by the L1) and shifted into place
+                    // afterwards; the last word may reach one count past the vector, never
+                    // past the word that holds the table's last count.
+                    const uint32_t first = odd[j] + (uint32_t)(present[g][j] ? index[j] : 0) * LT;
+                    shift[g][j] = (first & 1u) * 2u;
+                    const uint32_t* aligned = vec_words[j] + (first >> 1);
 #pragma unroll
                     for (int t = 0; t < kCover; ++t)
                         raw[g][j][t] = (LT % 2 == 0 && t == kCover - 1) ? 0u : aligned[t];
@@ -417,44 +479,60 @@ __device__ __forceinline__ void join_write(
 #pragma unroll
             for (int g = 0; g < kRounds; ++g) {
                 if (r0 + g * kWave >= n_out) break;
-                uint16_t v[K * LT];
+                // word t of vector j holds its counts 2t and 2t+1; a vector of an odd number of
+                // counts ends in the low half of its last word
+                uint32_t w[kWords];
 #pragma unroll
                 for (int j = 0; j < K; ++j) {
+                    uint32_t vec[kCover];
 #pragma unroll
-                    for (int e = 0; e < LT; ++e) {
-                        const uint32_t word = __builtin_amdgcn_alignbyte(
-                            raw[g][j][e / 2 + 1], raw[g][j][e / 2], shift[g][j]);
-                        const uint32_t c = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
-                        v[j * LT + e] = present[g][j] ? (uint16_t)c : absent16;
+                    for (int t = 0; t < kCover; ++t) {
+                        vec[t] = __builtin_amdgcn_alignbyte(raw[g][j][t + 1], raw[g][j][t],
+                                                            shift[g][j]);
+                        if (!present[g][j]) vec[t] = absent32;
+                    }
+                    const int start = j * LT;  // first count of the vector inside the row
+                    if (start % 2 == 0) {
+#pragma unroll
+                        for (int t = 0; t < kHalf; ++t) w[start / 2 + t] = vec[t];
+                        if (LT % 2 == 1) w[start / 2 + kHalf] = vec[kHalf] & 0xFFFFu;
+                    } else {
+                        w[(start - 1) / 2] |= vec[0] << 16;
+#pragma unroll
+                        for (int t = 0; t < kHalf; ++t)
+                            w[(start + 1) / 2 + t] =
+                                __builtin_amdgcn_alignbyte(vec[t + 1], vec[t], 2u);
                     }
                 }
                 const int r = r0 + g * kWave + lane;
                 const bool live = r < n_out;
-                if (live && !ids_first) out_ids[off + r] = (int32_t)id[g];
+                if (live) out_ids[off + r] = (int32_t)id[g];
                 if constexpr (LT % 2 == 0) {
                     // count vectors of whole words: a lane's row is stored from its registers
                     // (the rows of neighbouring lanes adjoin, so a wave's stores are contiguous)
                     if (live) {
                         uint32_t* row_words = out_words + (int64_t)r * kWords;
 #pragma unroll
-                        for (int d = 0; d < kWords; ++d)
-                            row_words[d] = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+                        for (int d = 0; d < kWords; ++d) row_words[d] = w[d];
                     }
                 } else {
                     // an odd number of 16-bit counts per list: the rows are put together in an
-                    // LDS tile laid out like the output and go out as whole words, lane by lane
+                    // LDS tile and go out 16 bytes per lane.  The tile starts `head` words in,
+                    // so that 16-byte pieces of the tile are 16-byte pieces of the output.
+                    uint32_t* dst = out_words + (int64_t)(r0 + g * kWave) * kWords;
+                    const int head = (int)((reinterpret_cast<uintptr_t>(dst) >> 2) & 3u);
 #pragma unroll
-                    for (int d = 0; d < kWords; ++d)
-                        tile32[lane * kWords + d] =
-                            (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+                    for (int d = 0; d < kWords; ++d) tile32[head + lane * kWords + d] = w[d];
                     wave_sync();
                     const int n_words = min(kWave, n_out - (r0 + g * kWave)) * kWords;
-                    uint32_t* dst = out_words + (int64_t)(r0 + g * kWave) * kWords;
-#pragma unroll
-                    for (int d = 0; d < kWords; ++d) {
-                        const int t = d * kWave + lane;
-                        if (t < n_words) dst[t] = tile32[t];
-                    }
+                    const int lead = min((4 - head) & 3, n_words);  // words before the first piece
+                    const int n_quads = (n_words - lead) >> 2;
+                    const int tail = lead + 4 * n_quads;           // words after the last piece
+                    if (lane < lead) dst[lane] = tile32[head + lane];
+                    const uint4* tile_quads = reinterpret_cast<const uint4*>(tile32 + head + lead);
+                    uint4* dst_quads = reinterpret_cast<uint4*>(dst + lead);
+                    for (int t = lane; t < n_quads; t += kWave) dst_quads[t] = tile_quads[t];
+                    if (lane < n_words - tail) dst[tail + lane] = tile32[head + tail + lane];
                     wave_sync();
                 }
             }
@@ -533,7 +611,7 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const int32_t* __restrict__ queries, int64_t n_queries, int32_t* __restrict__ counts,
     const int64_t* __restrict__ join_off, int64_t cap_rows, int32_t* __restrict__ out_ids,
     uint16_t* __restrict__ out_cnt, uint16_t absent16, uint32_t* __restrict__ err) {
-    extern __shared__ uint32_t lds32[];
+    extern __shared__ __align__(16) uint32_t lds32[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int L = LT > 0 ? LT : m + 1;
@@ -541,8 +619,9 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
     const int64_t stride = (int64_t)gridDim.x * WPB;
     for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
         JoinQuery<K> jq;
-        const int n_out = join_prepare<K, kFill, LT>(base, lane, q, rpe_off, rpe_ids, n_blocks, m,
-                                                     max_set, queries, jq, err);
+        // the same in every lane; said so, the loops over the rows are scalar loops
+        const int n_out = __builtin_amdgcn_readfirstlane(join_prepare<K, kFill, LT>(
+            base, lane, q, rpe_off, rpe_ids, n_blocks, m, max_set, queries, jq, err));
         if constexpr (!kFill) {
             if (lane == 0) counts[q] = n_out > 0 ? n_out : 0;  // an unusable query yields no rows
         } else {
