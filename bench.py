@@ -410,8 +410,8 @@ def main() -> int:
     # ONCE (compulsory traffic: a perfect cache would read the CSR once, not 12 bytes a step);
     # (2) what the kernel really moves, from the request counters of profiles/ (per launch;
     # 128-byte reads and 64-byte writes between the L2s and the memory fabric) over the launch
-    # time measured here, against the HBM peak and against the measured rate of dependent
-    # random gathers (profiles/membench_mi355x.txt).
+    # time measured here, against the HBM peak and against the time the bus needs for them at
+    # the measured rates of line fetches and streaming writes (profiles/membench_mi355x.txt).
     if dom_stage in ("walk_rpe", "walk"):
         walk_steps_read = N * M * m * 12
         csr_once = (N + 1) * 4 + ci.size * 4
@@ -434,10 +434,17 @@ def main() -> int:
             "requests_per_s": round(n_req / (kern[dom] * 1e-3), 1),
             "source": f"profiles/requests_{wl.name}.txt (counts per launch) / launch time measured here",
         }
-        if "gather_16B_1GiB_Gs" in ceil:
-            as_moved["measured_gather_ceiling_per_s"] = ceil["gather_16B_1GiB_Gs"] * 1e9
-            as_moved["frac_of_gather_ceiling"] = round(
-                n_req / (kern[dom] * 1e-3) / (ceil["gather_16B_1GiB_Gs"] * 1e9), 4)
+        if "gather_16B_1GiB_Gs" in ceil and "stream_write_TBs" in ceil:
+            # the time the memory bus needs for these requests at the rates it was measured to
+            # give: line fetches at the rate of dependent random gathers, writes at the rate
+            # of streaming writes, one after the other
+            fetch_rate = ceil["gather_16B_1GiB_Gs"] * 1e9 * 128        # bytes/s as moved
+            write_rate = ceil["stream_write_TBs"] * 1e12
+            bus_ms = (rd / fetch_rate + wr / write_rate) * 1e3
+            as_moved["measured_line_fetch_GBs"] = round(fetch_rate / 1e9, 1)
+            as_moved["measured_stream_write_GBs"] = round(write_rate / 1e9, 1)
+            as_moved["bus_time_ms_at_measured_rates"] = round(bus_ms, 3)
+            as_moved["bus_time_over_launch_time"] = round(bus_ms / kern[dom], 4)
         roofline["as_moved"] = as_moved
 
     out = {

@@ -569,7 +569,7 @@ static int join_layout(surel_ctx* ctx, const JoinScratch& ws, const int64_t* d_r
     hipError_t hrc;
     {
         KernelSpan span(ctx, SUREL_K_JOIN_COUNT);
-        hrc = surel::launch_join_count(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off,
+        hrc = surel::launch_join_count(ctx->stream, ctx->max_lds_bytes, d_rpe_off,
                                        d_rpe_ids, n_blocks, max_set, d_queries, n_queries, k,
                                        ws.counts, ctx->d_err);
     }
@@ -589,7 +589,7 @@ static int join_rows(surel_ctx* ctx, const int64_t* d_rpe_off, const int32_t* d_
                      const int64_t* d_join_off, int64_t cap_rows, int32_t* d_join_ids,
                      uint16_t* d_join_cnt, uint16_t absent16) {
     KernelSpan span(ctx, SUREL_K_JOIN_FILL);
-    hipError_t hrc = surel::launch_join_fill(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_rpe_off,
+    hipError_t hrc = surel::launch_join_fill(ctx->stream, ctx->max_lds_bytes, d_rpe_off,
                                              d_rpe_ids, d_rpe_cnt, n_blocks, m, max_set, d_queries,
                                              n_queries, k, d_join_off, cap_rows, d_join_ids,
                                              d_join_cnt, absent16, ctx->d_err);

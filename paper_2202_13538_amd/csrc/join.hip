@@ -4,9 +4,8 @@
 //
 // Two launches of one kernel body.  Counting: every query's union rows (an exclusive scan then
 // turns the counts into join_off).  Filling: join_off is given (by that scan, or kept by the
-// caller from an earlier call), the rows are written.  A wavefront handles one query at a time
-// and loops over the queries (the grid is as large as the device holds at once); the K sorted id
-// lists are staged in LDS.  (Doing both in one launch, with the offsets from a scanner wave
+// caller from an earlier call), the rows are written.  A wavefront handles one query at a time;
+// the K sorted id lists are staged in LDS.  (Doing both in one launch, with the offsets from a scanner wave
 // inside the kernel as the fused walk + RPE kernel has them, was built and measured: a wave has
 // to wait for its query's offset between uniting and writing, which took 10.0 ms against
 // 0.83 + 5.6 ms for the two launches on the 2.9M-node workload; holding one query back to hide
@@ -71,8 +70,8 @@ struct JoinLds {
     int mask;     // [2][mask_words] uint32: which union rows lists 0 and 1 feed (pairs, fill only)
     int mask_words;
     int src;      // [K][K*max_set] uint16: table row of list j that feeds union row r, or kNoSrc
-    int tile;     // fill only; 16-byte aligned
-    int total;    // a multiple of 4 words, so that every wave's part starts 16-byte aligned
+    int tile;     // fill only
+    int total;
 };
 
 // Rows whose K*L counts fill whole 32-bit words are put together in registers and written
@@ -100,17 +99,21 @@ __host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L,
     o.ids = 0;
     o.new_pre = o.ids + K * max_set;
     o.mask = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
-    o.mask += o.mask & 1;  // the masks are read as 64-bit words
     // one bit per union row, in whole 64-bit words, and two words of slack: a lane's bits are
     // put in as three 32-bit words at a time
     o.mask_words = (K == 2 && fill) ? 2 * ((2 * max_set + 63) / 64) + 2 : 0;
+    if (o.mask_words > 0) o.mask += o.mask & 1;  // the masks are read as 64-bit words
     o.src = o.mask + 2 * o.mask_words;
     const int src_end = o.src + (fill && join_uses_src(K, LT) ? (K * K * max_set + 1) / 2 : 0);
-    o.tile = (src_end + 3) & ~3;
+    // Only the tile of the pairs is moved 16 bytes at a time; nothing else is padded: the
+    // words a wave needs decide how many waves a compute unit holds.
+    const bool quads = fill && join_uses_tile(K, LT) && join_rows_direct(K, LT);
+    o.tile = quads ? (src_end + 3) & ~3 : src_end;
     int tile_words = 0;
     if (fill && join_uses_tile(K, LT))
-        tile_words = join_rows_direct(K, LT) ? kWave * LT + 4 : (kJoinChunkRows * K * L + 1) / 2;
-    o.total = (o.tile + tile_words + 3) & ~3;
+        tile_words = quads ? kWave * LT + 4 : (kJoinChunkRows * K * L + 1) / 2;
+    o.total = o.tile + tile_words;
+    if (quads) o.total = (o.total + 3) & ~3;  // every wave's part starts 16-byte aligned
     return o;
 }
 
@@ -598,26 +601,33 @@ __device__ __forceinline__ void join_write(
     }
 }
 
-// Counting and filling.  Waves loop over the queries (wave w of the grid takes queries w,
-// w + waves, ...): a query is little work, and a grid of one short-lived wave per query is bound
-// by how fast waves can be launched.  No workgroup-wide barrier is used.
+// Counting and filling.  One wavefront per workgroup; it takes `per_wave` consecutive queries
+// (the grid covers the list).  The hardware hands workgroups out as others retire, which keeps
+// every compute unit full whatever the queries' sizes are and however many waves it really
+// holds.  (A grid of exactly as many waves as the occupancy query promises, each looping over
+// a strided share of the queries, was slower: where the device held fewer workgroups than
+// promised, the surplus ran as a tail after the others, +25 % on one workload; and with four
+// waves to a workgroup a slot stays taken until the slowest of the four is done.)  Filling
+// takes one query per wave; the counting launch, whose queries are short, four.
 // kFill = false: write counts[q] only; kFill = true: join_off is complete (the caller's, or the
 // scan of a counting launch), write the rows.  A query whose union does not have the
 // join_off[q+1] - join_off[q] rows that the offsets give it is flagged and writes nothing.
-template <int K, int WPB, bool kFill, int LT>
-__global__ __launch_bounds__(WPB* kWave) void join_kernel(
+constexpr int kQueriesPerWaveCount = 4;
+constexpr int kQueriesPerWaveFill = 1;
+
+template <int K, bool kFill, int LT>
+__global__ __launch_bounds__(kWave) void join_kernel(
     const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids,
     const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
     const int32_t* __restrict__ queries, int64_t n_queries, int32_t* __restrict__ counts,
     const int64_t* __restrict__ join_off, int64_t cap_rows, int32_t* __restrict__ out_ids,
     uint16_t* __restrict__ out_cnt, uint16_t absent16, uint32_t* __restrict__ err) {
-    extern __shared__ __align__(16) uint32_t lds32[];
+    extern __shared__ __align__(16) uint32_t base[];
+    constexpr int kPerWave = kFill ? kQueriesPerWaveFill : kQueriesPerWaveCount;
     const int lane = lane_id();
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int L = LT > 0 ? LT : m + 1;
-    uint32_t* base = lds32 + wave * join_lds_layout(K, max_set, L, kFill, LT).total;
-    const int64_t stride = (int64_t)gridDim.x * WPB;
-    for (int64_t q = (int64_t)blockIdx.x * WPB + wave; q < n_queries; q += stride) {
+    const int64_t q_first = (int64_t)blockIdx.x * kPerWave;
+#pragma unroll 1
+    for (int64_t q = q_first; q < min(q_first + kPerWave, n_queries); ++q) {
         JoinQuery<K> jq;
         // the same in every lane; said so, the loops over the rows are scalar loops
         const int n_out = __builtin_amdgcn_readfirstlane(join_prepare<K, kFill, LT>(
@@ -644,7 +654,6 @@ __global__ __launch_bounds__(WPB* kWave) void join_kernel(
 struct JoinJob {
     hipStream_t stream;
     int max_lds_bytes;
-    int n_cu;
     const int64_t* rpe_off;
     const int32_t* rpe_ids;
     const uint16_t* rpe_cnt;
@@ -664,28 +673,24 @@ struct JoinJob {
 
 enum JoinMode { kJoinCount, kJoinFill };
 
-template <int K, int WPB, JoinMode kMode, int LT>
+template <int K, JoinMode kMode, int LT>
 static hipError_t launch_join_cfg(const JoinJob& j) {
     constexpr bool kFill = kMode == kJoinFill;
-    const size_t lds_bytes =
-        (size_t)WPB * join_lds_layout(K, j.max_set, j.m + 1, kFill, LT).total * 4;
-    const void* fn = reinterpret_cast<const void*>(join_kernel<K, WPB, kFill, LT>);
+    constexpr int kPerWave = kFill ? kQueriesPerWaveFill : kQueriesPerWaveCount;
+    const size_t lds_bytes = (size_t)join_lds_layout(K, j.max_set, j.m + 1, kFill, LT).total * 4;
+    if (lds_bytes > (size_t)j.max_lds_bytes) return hipErrorInvalidValue;
+    const void* fn = reinterpret_cast<const void*>(join_kernel<K, kFill, LT>);
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)lds_bytes);
         if (rc != hipSuccess) return rc;
     }
-    // no more workgroups than the device holds at once: their waves loop over the queries
-    int per_cu = 0;
-    hipError_t orc = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, WPB * kWave, lds_bytes);
-    if (orc != hipSuccess) return orc;
-    if (per_cu < 1) return hipErrorInvalidValue;
-    int64_t blocks = (j.n_queries + WPB - 1) / WPB;
-    if (blocks > (int64_t)per_cu * j.n_cu) blocks = (int64_t)per_cu * j.n_cu;
-    const dim3 grid((unsigned)blocks), block(WPB * kWave);
-    hipLaunchKernelGGL((join_kernel<K, WPB, kFill, LT>), grid, block, lds_bytes, j.stream, j.rpe_off,
-                       j.rpe_ids, j.rpe_cnt, j.n_blocks, j.m, j.max_set, j.queries, j.n_queries,
-                       j.counts, j.join_off, j.cap_rows, j.out_ids, j.out_cnt, j.absent16, j.err);
+    const int64_t blocks = (j.n_queries + kPerWave - 1) / kPerWave;
+    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((join_kernel<K, kFill, LT>), dim3((unsigned)blocks), dim3(kWave), lds_bytes,
+                       j.stream, j.rpe_off, j.rpe_ids, j.rpe_cnt, j.n_blocks, j.m, j.max_set,
+                       j.queries, j.n_queries, j.counts, j.join_off, j.cap_rows, j.out_ids,
+                       j.out_cnt, j.absent16, j.err);
     return hipGetLastError();
 }
 
@@ -694,27 +699,16 @@ constexpr int join_static_len(JoinMode mode, int L) {
     return (mode != kJoinCount && L >= 2 && L <= 6) ? L : 0;
 }
 
-template <int K, int WPB, JoinMode kMode>
-static hipError_t launch_join_kw(const JoinJob& j) {
-    switch (join_static_len(kMode, j.m + 1)) {
-        case 2: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 2>(j);
-        case 3: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 3>(j);
-        case 4: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 4>(j);
-        case 5: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 5>(j);
-        case 6: return launch_join_cfg<K, WPB, kMode, kMode == kJoinCount ? 0 : 6>(j);
-        default: return launch_join_cfg<K, WPB, kMode, 0>(j);
-    }
-}
-
 template <int K, JoinMode kMode>
 static hipError_t launch_join_k(const JoinJob& j) {
-    const int LT = join_static_len(kMode, j.m + 1);
-    const size_t per_wave = (size_t)join_lds_layout(K, j.max_set, j.m + 1, kMode != kJoinCount, LT).total * 4;
-    // as many waves per workgroup as the LDS a wave needs allows
-    if (per_wave * 4 <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 4, kMode>(j);
-    if (per_wave * 2 <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 2, kMode>(j);
-    if (per_wave <= (size_t)j.max_lds_bytes) return launch_join_kw<K, 1, kMode>(j);
-    return hipErrorInvalidValue;
+    switch (join_static_len(kMode, j.m + 1)) {
+        case 2: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 2>(j);
+        case 3: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 3>(j);
+        case 4: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 4>(j);
+        case 5: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 5>(j);
+        case 6: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 6>(j);
+        default: return launch_join_cfg<K, kMode, 0>(j);
+    }
 }
 
 template <JoinMode kMode>
@@ -725,24 +719,24 @@ static hipError_t launch_join_mode(const JoinJob& j, int32_t k) {
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
                              const int32_t* rpe_ids, int64_t n_blocks, int32_t max_set,
                              const int32_t* queries, int64_t n_queries, int32_t k, int32_t* counts,
                              uint32_t* err) {
     JoinJob j{};
-    j.stream = stream, j.max_lds_bytes = max_lds_bytes, j.n_cu = n_cu;
+    j.stream = stream, j.max_lds_bytes = max_lds_bytes;
     j.rpe_off = rpe_off, j.rpe_ids = rpe_ids, j.n_blocks = n_blocks, j.m = 1, j.max_set = max_set;
     j.queries = queries, j.n_queries = n_queries, j.counts = counts, j.err = err;
     return launch_join_mode<kJoinCount>(j, k);
 }
 
-hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
                             const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                             int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
                             int32_t k, const int64_t* join_off, int64_t cap_rows, int32_t* out_ids,
                             uint16_t* out_cnt, uint16_t absent16, uint32_t* err) {
     JoinJob j{};
-    j.stream = stream, j.max_lds_bytes = max_lds_bytes, j.n_cu = n_cu;
+    j.stream = stream, j.max_lds_bytes = max_lds_bytes;
     j.rpe_off = rpe_off, j.rpe_ids = rpe_ids, j.rpe_cnt = rpe_cnt, j.n_blocks = n_blocks, j.m = m;
     j.max_set = max_set, j.queries = queries, j.n_queries = n_queries, j.join_off = join_off;
     j.cap_rows = cap_rows, j.out_ids = out_ids, j.out_cnt = out_cnt, j.absent16 = absent16;

@@ -63,11 +63,11 @@ hipError_t launch_rpe_fill(hipStream_t stream, int max_lds_bytes, const int32_t*
 // rows, or whose rows would pass cap_rows, is skipped and flagged).  absent16: what the entries
 // of a vector hold where a list has no row for the node (0 for counts).
 // hipErrorInvalidValue = the shape does not fit the device's LDS.
-hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
                              const int32_t* rpe_ids, int64_t n_blocks, int32_t max_set,
                              const int32_t* queries, int64_t n_queries, int32_t k, int32_t* counts,
                              uint32_t* err);
-hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, int n_cu, const int64_t* rpe_off,
+hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
                             const int32_t* rpe_ids, const uint16_t* rpe_cnt, int64_t n_blocks,
                             int32_t m, int32_t max_set, const int32_t* queries, int64_t n_queries,
                             int32_t k, const int64_t* join_off, int64_t cap_rows, int32_t* out_ids,
