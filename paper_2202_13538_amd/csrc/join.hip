@@ -44,8 +44,8 @@ constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output 
 // Rounds of 64 union rows whose gathers a wave has in flight together.  More rounds shorten a
 // wave's chain of memory round trips but cost registers, and the launch is bound by its waves
 // in flight.
-constexpr int kGatherRoundsPairs = 5;
-constexpr int kGatherRoundsTuples = 4;
+constexpr int kGatherRoundsPairs = 6;
+constexpr int kGatherRoundsTuples = 6;
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {

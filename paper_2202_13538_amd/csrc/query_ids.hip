@@ -211,12 +211,10 @@ static hipError_t launch_query_ids_kwe(hipStream_t stream, int n_cu, const int32
                                             (int)lds_bytes);
         if (rc != hipSuccess) return rc;
     }
-    int per_cu = 0;
-    hipError_t rc = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, WPB * kWave, lds_bytes);
-    if (rc != hipSuccess) return rc;
-    if (per_cu < 1) return hipErrorInvalidValue;
+    // a wave per query and the hardware hands the workgroups out (a wave loops only where the
+    // grid cannot be that large)
     int64_t blocks = (n_queries + WPB - 1) / WPB;
-    if (blocks > (int64_t)per_cu * n_cu) blocks = (int64_t)per_cu * n_cu;
+    if (blocks > 0x7FFFFFFFll) blocks = 0x7FFFFFFFll;
     hipLaunchKernelGGL((query_ids_kernel<K, WPB, QE, kCode>), dim3((unsigned)blocks),
                        dim3(WPB * kWave), lds_bytes, stream, walks, rpe_off, rpe_ids, code, n_blocks,
                        M * (m + 1), max_set,
