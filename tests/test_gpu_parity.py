@@ -675,6 +675,49 @@ def test_join_query_counts_around_workgroup_and_scan_tile_sizes(ctx, k):
         assert_table_equal(got, want, f"join of {n} queries")
 
 
+def hand_made_table(blocks, L, rng):
+    """An RPE table whose blocks hold the given ascending id lists and random counts."""
+    off = np.zeros(len(blocks) + 1, dtype=np.int64)
+    off[1:] = np.cumsum([len(b) for b in blocks])
+    ids = np.concatenate([np.asarray(b, dtype=np.int32) for b in blocks]) if off[-1] else \
+        np.zeros(0, dtype=np.int32)
+    cnt = rng.integers(0, 65536, size=(int(off[-1]), L)).astype(np.uint16)
+    return off, ids, cnt
+
+
+@pytest.mark.parametrize("max_set", [1, 31, 32, 33, 64, 96, 2048])
+@pytest.mark.parametrize("L", [2, 4, 5, 7])
+def test_join_of_hand_made_tables_around_64_row_boundaries(ctx, max_set, L):
+    # pairs whose unions end exactly at, one before and one after a multiple of 64 rows (the
+    # union's bit masks are 64-bit words; a round of the filling loop is 64 rows), from lists
+    # that are disjoint, equal, interleaved, nested, empty, and full sets of max_set nodes
+    rng = np.random.default_rng(1000 * max_set + L)
+    n = max_set
+    even, odd = np.arange(0, 2 * n, 2), np.arange(1, 2 * n, 2)
+    low, high = np.arange(n), np.arange(n, 2 * n)
+    blocks = [even, odd, low, high, low[: n // 2], low[n // 2:], np.zeros(0, dtype=np.int64),
+              low[:1], high[-1:], even[: max(n - 1, 0)], np.sort(rng.choice(4 * n, n, replace=False)),
+              np.sort(rng.choice(4 * n, n, replace=False))]
+    table = hand_made_table(blocks, L, rng)
+    nb = len(blocks)
+    queries = np.array([(a, b) for a in range(nb) for b in range(nb)], dtype=np.int32)
+    want = oracle.join_queries(*table, queries)
+    sizes = np.diff(want[0])
+    assert sizes.max() == 2 * n and (sizes == 0).any()
+    d_table = (dev(table[0]), dev(table[1]), dev(table[2].view(np.int16)).view(torch.uint16))
+    got = binding.join_queries(ctx, *d_table, dev(queries), max_set=max_set)
+    assert ctx.check() == 0
+    assert_table_equal(got, want, f"hand-made join, max_set {max_set}, L {L}")
+    if max_set > 96:
+        return
+    # and as triples: (a, b, b) and (a, a, b) have the union of (a, b) with a list repeated
+    tri = np.concatenate([queries[:, [0, 1, 1]], queries[:, [0, 0, 1]]])[:: 3]
+    want3 = oracle.join_queries(*table, tri)
+    got3 = binding.join_queries(ctx, *d_table, dev(tri), max_set=max_set)
+    assert ctx.check() == 0
+    assert_table_equal(got3, want3, f"hand-made join of triples, max_set {max_set}, L {L}")
+
+
 def test_largest_node_ids(ctx):
     # a graph with the most nodes the library takes (2^28 - 1): the largest ids make sort keys
     # (id << 4 | position) that use all 32 bits and must still sort in front of the padding
