@@ -116,7 +116,8 @@ def membench(torch) -> dict:
     out = {}
     ms, units = dbl(0), dbl(0)
     for kind, name, moved in ((0, "stream_read_TBs", 4 << 30), (1, "stream_write_TBs", 4 << 30),
-                              (2, "stream_copy_TBs", 8 << 30)):
+                              (2, "stream_copy_TBs", 8 << 30),
+                              (3, "stream_read1_write2_TBs", 6 << 30)):
         nbytes = (4 << 30) if kind < 2 else (8 << 30)
         assert lib.surel_membench_stream(kind, p, nbytes, sk, stream, ctypes.byref(ms)) == 0
         out[name] = round(moved / (ms.value * 1e-3) / 1e12, 3)

@@ -85,6 +85,27 @@ __global__ void copy_kernel(const v4i* __restrict__ a, v4i* __restrict__ b, size
     }
 }
 
+// One byte read for every two written (close to the join's filling launch): per turn a lane
+// reads kStreamUnroll / 2 items and writes kStreamUnroll.
+__global__ void read1_write2_kernel(const v4i* __restrict__ a, v4i* __restrict__ b, size_t n) {
+    size_t base = (size_t)blockIdx.x * blockDim.x * kStreamUnroll + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x * kStreamUnroll;
+    for (; base < n; base += stride) {
+        v4i v[kStreamUnroll / 2];
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll / 2; ++u) {
+            const size_t i = base + (size_t)u * blockDim.x;
+            v[u] = v4i{0, 0, 0, 0};
+            if (i < n) v[u] = __builtin_nontemporal_load(a + i);
+        }
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) {
+            const size_t i = base + (size_t)u * blockDim.x;
+            if (i < n) __builtin_nontemporal_store(v[u / 2] + v4i{u, 0, 0, 0}, b + i);
+        }
+    }
+}
+
 // Every lane follows `chain` dependent gathers of one T (4, 8 or 16 bytes) through a table of
 // mask+1 entries.
 template <typename T>
@@ -254,11 +275,12 @@ int surel_membench_init(void* d_buf, size_t bytes, void* hip_stream) {
     return hipStreamSynchronize(s) == hipSuccess ? 0 : -3;
 }
 
-// kind 0: read `bytes` of d_buf; 1: write them; 2: copy the first half of d_buf to the second
+// kind 0: read `bytes` of d_buf; 1: write them; 2: copy the first half of d_buf to the second;
+// 3: write the second half and read a quarter of d_buf for it (bytes / 4 read, bytes / 2 written)
 // (bytes / 2 read and bytes / 2 written).  *h_ms = kernel time.
 int surel_membench_stream(int kind, void* d_buf, size_t bytes, uint32_t* d_sink, void* hip_stream,
                           double* h_ms) {
-    if (!d_buf || !d_sink || !h_ms || bytes < 32 || kind < 0 || kind > 2) return -1;
+    if (!d_buf || !d_sink || !h_ms || bytes < 32 || kind < 0 || kind > 3) return -1;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     v4i* a = static_cast<v4i*>(d_buf);
     const size_t n = bytes / 16;
@@ -267,6 +289,7 @@ int surel_membench_stream(int kind, void* d_buf, size_t bytes, uint32_t* d_sink,
         if (kind == 0) hipLaunchKernelGGL(read_kernel, grid, block, 0, s, a, n, d_sink);
         if (kind == 1) hipLaunchKernelGGL(write_kernel, grid, block, 0, s, a, n);
         if (kind == 2) hipLaunchKernelGGL(copy_kernel, grid, block, 0, s, a, a + n / 2, n / 2);
+        if (kind == 3) hipLaunchKernelGGL(read1_write2_kernel, grid, block, 0, s, a, a + n / 2, n / 2);
     }, h_ms);
 }
 
