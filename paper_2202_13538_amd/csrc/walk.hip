@@ -10,9 +10,10 @@
 // Neighbour records.  A step needs the chosen neighbour's id and then that neighbour's own
 // row (start, degree) for the next step: two dependent gathers that each miss the L2 and
 // pull a whole cache line for a few bytes, which is what bounds this kernel.  When the job
-// is large next to the graph, a small kernel first expands the CSR into one 16-byte record
-// per edge entry, (neighbour id, its row start, its degree), so that every step after the
-// first is a single gather.  Both forms make exactly the same walks.
+// is large next to the graph, a small kernel first expands the CSR into one record per edge
+// entry, (neighbour id, its row start, its degree), so that every step after the first is a
+// single gather: one 64-bit word for large graphs, 16 bytes otherwise (walk_core.h).  All
+// forms make exactly the same walks.
 //
 // Optionally the kernel also reports |V_u|, the number of distinct nodes of each seed's
 // walks (Algorithm 1: V_u = set(W_u)), through an LDS hash set fed while the walkers move.
