@@ -163,4 +163,63 @@ __device__ __forceinline__ int32_t prune_lookup_any(const uint32_t (&w)[kMaxVecW
     return found;
 }
 
+// For vectors of at most three words (m + 1 <= 6, the usual walk lengths) with the length known
+// at compile time, the cache entries are packed: [0] 0 = free, 1 = being written, 2^31 | slot =
+// valid; [1 .. NW] the vector; 2 words an entry for NW = 1, else 4, so that an entry is one LDS
+// read.  The entry is read as a whole: should the read ever see the valid word next to vector
+// words that are not yet there, the comparison fails and the lane asks the global table, which is
+// slower and right; a valid entry never changes again.
+template <int NW>
+struct PackedCache {
+    static_assert(NW >= 1 && NW <= 3, "packed cache entries hold up to three words");
+    static constexpr int kEntryWords = NW == 1 ? 2 : 4;
+    static constexpr int entries() {
+        int e = 64;
+        while (e * 2 * kEntryWords <= kFusedCacheWords) e *= 2;
+        return e;
+    }
+};
+constexpr uint32_t kPackedValid = 0x80000000u;
+
+template <int NW>
+__device__ __forceinline__ int32_t prune_lookup_packed(const uint32_t (&w)[NW], uint32_t* cache,
+                                                       uint32_t* __restrict__ slots,
+                                                       uint32_t slot_mask, int64_t cap_T,
+                                                       unsigned long long* __restrict__ n_inserted,
+                                                       uint32_t spin_limit,
+                                                       uint32_t* __restrict__ err) {
+    constexpr int EW = PackedCache<NW>::kEntryWords;
+    const uint32_t hv = hash_vector<NW>(w);
+    uint32_t* entry = cache + ((hv >> 18) & (uint32_t)(PackedCache<NW>::entries() - 1)) * EW;
+    uint32_t e[4] = {0u, 0u, 0u, 0u};
+    if constexpr (EW == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(entry);
+        e[0] = v.x, e[1] = v.y;
+    } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(entry);
+        e[0] = v.x, e[1] = v.y, e[2] = v.z, e[3] = v.w;
+    }
+    if (e[0] & kPackedValid) {
+        bool same = true;
+#pragma unroll
+        for (int k = 0; k < NW; ++k) same = same && e[1 + k] == w[k];
+        if (same) return (int32_t)(e[0] & ~kPackedValid);
+    }
+    const int32_t found = find_or_insert<NW>(w, hv & slot_mask, slots, slot_mask, cap_T, n_inserted,
+                                             spin_limit, err);
+    if (found >= 0 && atomicCAS(entry, 0u, 1u) == 0u) {
+#pragma unroll
+        for (int k = 0; k < NW; ++k) entry[1 + k] = w[k];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __hip_atomic_store(entry, kPackedValid | (uint32_t)found, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    return found;
+}
+
+// Clears the whole cache: all-zero words are free entries in both layouts.
+__device__ __forceinline__ void fused_cache_clear_all(uint32_t* cache, int tid, int n_threads) {
+    for (int t = tid; t < kFusedCacheWords; t += n_threads) cache[t] = 0u;
+}
+
 }  // namespace surel

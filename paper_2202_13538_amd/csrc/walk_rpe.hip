@@ -40,6 +40,53 @@ struct CodeSet {
 // kCodes: every finished row's count vector is looked up in the hash set while the row still
 // lies in LDS (Algorithm 1's last step, pruning, done on the fly as well), and its slot number
 // goes to cs.code; cnt may then be null.
+// The codes of a seed's rows while they lie in LDS (cnt_lds32: the rows' 16-bit counts, densely
+// packed): a lane per row reads its vector as the aligned words that cover it, shifts it into
+// place, turns it into the set's word form (entry 2k in the upper half of word k, absent entries
+// zero) and looks it up.  LT = m + 1 at compile time for 2 .. 6 (packed cache entries), 0 = any.
+template <int LT>
+__device__ __forceinline__ void row_codes(int n_rows, int lane, int L, const uint32_t* cnt_lds32,
+                                          int64_t off, uint32_t* set_cache, const CodeSet& cs,
+                                          uint32_t spin_limit, uint32_t* __restrict__ err) {
+    const int n_words = (n_rows * L + 1) / 2;  // words the rows occupy in LDS
+    for (int t = lane; t < n_rows; t += kWave) {
+        const int first = t * L;
+        const uint32_t shift = (uint32_t)(first & 1) * 2u;
+        if constexpr (LT > 0) {
+            constexpr int NW = (LT + 1) / 2;
+            uint32_t raw[NW + 1];
+#pragma unroll
+            for (int k = 0; k <= NW; ++k)
+                raw[k] = 2 * k <= LT ? cnt_lds32[min((first >> 1) + k, n_words - 1)] : 0u;
+            uint32_t w[NW];
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                // entries 2k (low half) and 2k+1 (high half) as they lie in memory
+                uint32_t pair = __builtin_amdgcn_alignbyte(raw[k + 1], raw[k], shift);
+                if (2 * k + 1 >= LT) pair &= 0xFFFFu;  // the high half is the next row's
+                w[k] = (pair << 16) | (pair >> 16);
+            }
+            cs.code[off + t] = prune_lookup_packed<NW>(w, set_cache, cs.slots, cs.slot_mask,
+                                                       cs.cap_T, cs.n_inserted, spin_limit, err);
+        } else {
+            uint32_t raw[kMaxVecWords + 1];
+#pragma unroll
+            for (int k = 0; k <= kMaxVecWords; ++k)
+                raw[k] = 2 * k <= L ? cnt_lds32[min((first >> 1) + k, n_words - 1)] : 0u;
+            uint32_t w[kMaxVecWords];
+#pragma unroll
+            for (int k = 0; k < kMaxVecWords; ++k) {
+                uint32_t pair = __builtin_amdgcn_alignbyte(raw[k + 1], raw[k], shift);
+                if (2 * k + 1 >= L) pair &= 0xFFFFu;
+                if (2 * k >= L) pair = 0u;
+                w[k] = (pair << 16) | (pair >> 16);
+            }
+            cs.code[off + t] = prune_lookup_any(w, (L + 1) / 2, set_cache, cs.slots, cs.slot_mask,
+                                                cs.cap_T, cs.n_inserted, spin_limit, err);
+        }
+    }
+}
+
 template <int E, int kRec, bool kCodes>
 __global__ __launch_bounds__(1024) void walk_rpe_kernel(
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
@@ -51,12 +98,12 @@ __global__ __launch_bounds__(1024) void walk_rpe_kernel(
     uint32_t* __restrict__ err, CodeSet cs) {
     extern __shared__ uint32_t lds32[];
     __shared__ unsigned long long chunk;
-    __shared__ uint32_t set_cache[kCodes ? kFusedCacheWords : 1];
+    __shared__ __align__(16) uint32_t set_cache[kCodes ? kFusedCacheWords : 1];
 
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (threadIdx.x == 0) chunk = 0ull;  // empty
-    if constexpr (kCodes) fused_cache_clear(set_cache, (m + 2) / 2, (int)threadIdx.x, (int)blockDim.x);
+    if constexpr (kCodes) fused_cache_clear_all(set_cache, (int)threadIdx.x, (int)blockDim.x);
     __syncthreads();                     // the only workgroup-wide barrier of the kernel
     const LookbackScratch scr = lookback_scratch(n_seeds);
     int64_t* base = lookback_base(lb);
@@ -95,29 +142,14 @@ __global__ __launch_bounds__(1024) void walk_rpe_kernel(
             uint32_t* cnt_lds32 = wave_lds + sc.n_rows;
             rpe_assemble_rows<E>(x, sc, lane, L, ids_lds, cnt_lds32);
             if constexpr (kCodes) {
-                // a lane per row: the row's vector as words (entry 2k in the upper half of word
-                // k, absent entries zero), then its slot in the set of distinct vectors.  The L
-                // 16-bit counts of row t start at halfword t*L of the LDS rows: they are read as
-                // the aligned words that cover them and shifted into place.
-                const int n_words = (sc.n_rows * L + 1) / 2;  // words the rows occupy in LDS
-                for (int t = lane; t < sc.n_rows; t += kWave) {
-                    const int first = t * L;
-                    const uint32_t shift = (uint32_t)(first & 1) * 2u;
-                    uint32_t raw[kMaxVecWords + 1];
-#pragma unroll
-                    for (int k = 0; k <= kMaxVecWords; ++k)
-                        raw[k] = 2 * k <= L ? cnt_lds32[min((first >> 1) + k, n_words - 1)] : 0u;
-                    uint32_t w[kMaxVecWords];
-#pragma unroll
-                    for (int k = 0; k < kMaxVecWords; ++k) {
-                        // entries 2k (low half) and 2k+1 (high half) as they lie in memory
-                        uint32_t pair = __builtin_amdgcn_alignbyte(raw[k + 1], raw[k], shift);
-                        if (2 * k + 1 >= L) pair &= 0xFFFFu;  // the high half is the next row's
-                        if (2 * k >= L) pair = 0u;
-                        w[k] = (pair << 16) | (pair >> 16);
-                    }
-                    cs.code[off + t] = prune_lookup_any(w, (L + 1) / 2, set_cache, cs.slots, cs.slot_mask,
-                                                        cs.cap_T, cs.n_inserted, spin_limit, err);
+                // a lane per row: its slot in the set of distinct vectors
+                switch (L) {
+                    case 2: row_codes<2>(sc.n_rows, lane, L, cnt_lds32, off, set_cache, cs, spin_limit, err); break;
+                    case 3: row_codes<3>(sc.n_rows, lane, L, cnt_lds32, off, set_cache, cs, spin_limit, err); break;
+                    case 4: row_codes<4>(sc.n_rows, lane, L, cnt_lds32, off, set_cache, cs, spin_limit, err); break;
+                    case 5: row_codes<5>(sc.n_rows, lane, L, cnt_lds32, off, set_cache, cs, spin_limit, err); break;
+                    case 6: row_codes<6>(sc.n_rows, lane, L, cnt_lds32, off, set_cache, cs, spin_limit, err); break;
+                    default: row_codes<0>(sc.n_rows, lane, L, cnt_lds32, off, set_cache, cs, spin_limit, err); break;
                 }
             }
             rpe_stream_rows(sc.n_rows, lane, L, ids_lds, cnt_lds32, off, ids, cnt);
