@@ -63,7 +63,10 @@ __device__ __forceinline__ bool walk_many(const WalkGraph& g, int32_t u, int32_t
         cur_deg[c] = u_deg;
         row[c][0] = u;
     }
-    for (int s0 = 1; s0 <= m; s0 += 4) {
+    // One group of four steps (one Philox call).  The first group is written out on its own:
+    // there s0 is the constant 1, so the steps' row offsets and the Philox counter are known
+    // at compile time (walks of up to four steps never leave it).
+    auto group = [&](const int s0) __attribute__((always_inline)) {
         uint32_t r[C][4];
 #pragma unroll
         for (int c = 0; c < C; ++c)
@@ -161,7 +164,9 @@ __device__ __forceinline__ bool walk_many(const WalkGraph& g, int32_t u, int32_t
                 }
             }
         }
-    }
+    };
+    group(1);
+    for (int s0 = 5; s0 <= m; s0 += 4) group(s0);
     return bad_graph;
 }
 
