@@ -249,20 +249,26 @@ static hipError_t launch_walk_rpe_erc(SUREL_WR_PARAMS) {
     const size_t per_wave = (size_t)words * 4;
     const size_t static_lds = 1024 + (kCodes ? (size_t)kFusedCacheWords * 4 : 0);
     const void* fn = reinterpret_cast<const void*>(walk_rpe_kernel<E, kRec, kCodes>);
-    // waves per compute unit that LDS (160 KB) and registers allow, split into as few equal
-    // workgroups as possible (a workgroup has at most 16 waves)
+    // A workgroup has as many waves as LDS (160 KB) and registers allow a compute unit, 16 at
+    // most, so that a compute unit holds one such workgroup (two, where 32 waves fit).
+    // (Kernels with few registers could have 20 or 24 waves in two or more smaller workgroups,
+    // and were measured with them on the 2.9M-node graph: M = 50, m = 4, where 20 waves fit,
+    // takes 8.2 ms as one workgroup of 16, 9.1 as two of 8, 11.9 as five of 4, and 11.3 as two
+    // of 10, of which the second never starts beside the first: a workgroup's waves go to the
+    // four SIMDs in turn, and two of 10 ask two of the SIMDs for six waves when five fit.
+    // M = 25: 6.7 ms as 16, 6.9 as two of 12.  Only at M = 12 are two of 12 ahead, 5.4 against
+    // 5.6 ms.)
     hipFuncAttributes attr;
     hipError_t rc = hipFuncGetAttributes(&attr, fn);
     if (rc != hipSuccess) return rc;
     const int regs = attr.numRegs > 0 ? attr.numRegs : 128;
+    constexpr int kMaxW = 16;
     int cu_waves = 4 * (512 / ((regs + 7) / 8 * 8));
     const int by_lds = (int)((160 * 1024 - static_lds) / per_wave);
     if (cu_waves > by_lds) cu_waves = by_lds;
-    if (cu_waves > 32) cu_waves = 32;
-    constexpr int kMaxW = 16;
-    int groups = (cu_waves + kMaxW - 1) / kMaxW;
-    int W = groups > 0 ? cu_waves / groups : 0;
-    if (W < 1) {  // not even one wave next to other workgroups: what one workgroup may have
+    if (cu_waves > kMaxW) cu_waves = kMaxW;
+    int W = cu_waves;
+    if (W < 1) {  // what one workgroup may have (the checks below turn down what does not fit)
         W = (int)(((size_t)max_lds_bytes - static_lds) / per_wave);
         if (W > kMaxW) W = kMaxW;
     }
