@@ -213,7 +213,8 @@ hipError_t launch_prune_collect(hipStream_t stream, int n_cu, const uint16_t* cn
     if (n_rows == 0) return hipSuccess;
     const int L = m + 1;
     int64_t blocks = (n_rows + 256 * kPruneRows - 1) / (256 * kPruneRows);
-    if (blocks > (int64_t)n_cu * 16) blocks = (int64_t)n_cu * 16;
+    // several workgroups per slot of the device, so that the last ones to start have little left
+    if (blocks > (int64_t)n_cu * 32) blocks = (int64_t)n_cu * 32;
 #define SUREL_PRUNE_CASE(NW_)                                                                  \
     if ((L + 1) / 2 == (NW_)) {                                                                \
         hipLaunchKernelGGL((prune_collect_kernel<NW_>), dim3((unsigned)blocks), dim3(256), 0,  \
@@ -255,7 +256,7 @@ hipError_t launch_prune_finish(hipStream_t stream, int n_cu, int64_t n_rows, int
     }
     if (n_rows > 0) {
         int64_t blocks = (n_rows / 4 + 256) / 256;
-        if (blocks > (int64_t)n_cu * 16) blocks = (int64_t)n_cu * 16;
+        if (blocks > (int64_t)n_cu * 32) blocks = (int64_t)n_cu * 32;
         hipLaunchKernelGGL(prune_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, slots,
                            (uint32_t)prune_slots(cap_T), n_rows, code);
     }
