@@ -23,7 +23,7 @@
 //   - triples: ranks.  A row is owned by the first list that holds its node; its position is
 //     #{a in list 0 : a < x} + sum over j >= 1 of #{b in list j : b < x, b in no earlier list},
 //     each term a lower bound in LDS plus a lookup in a prefix count of "new" elements; the
-//     sources go to LDS as one 16-bit index per (list, row).
+//     owner sets the row's bit in the mask of every list that holds the node.
 // Count vectors.  For the usual walk lengths (m + 1 = 2 .. 6 entries per vector) a lane takes
 // one union row: it gathers the row's K vectors from the table (zeros where the node is
 // absent), packs them into the row's K*L/2 words in registers, and the row goes out either
@@ -68,7 +68,7 @@ __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint
 struct JoinLds {
     int ids;      // [K][max_set] uint32
     int new_pre;  // [K-1][max_set+1] uint16 (triples only)
-    int mask;     // [2][mask_words] uint32: which union rows lists 0 and 1 feed (pairs, fill only)
+    int mask;     // [K][mask_words] uint32: bit r of mask j = list j feeds union row r (fill only)
     int mask_words;
     int src;      // [K][K*max_set] uint16: table row of list j that feeds union row r, or kNoSrc
     int tile;     // fill only
@@ -89,10 +89,8 @@ __host__ __device__ constexpr bool join_uses_tile(int K, int LT) {
     return !join_rows_direct(K, LT) || (K == 2 && LT % 2 == 1);
 }
 
-// Pairs keep their sources as bit masks; the generic path expands them to indices.
-__host__ __device__ constexpr bool join_uses_src(int K, int LT) {
-    return K != 2 || !join_rows_direct(K, LT);
-}
+// The sources of the union rows are kept as bit masks; the generic path expands them to indices.
+__host__ __device__ constexpr bool join_uses_src(int K, int LT) { return !join_rows_direct(K, LT); }
 
 __host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L, bool fill,
                                                       int LT) {
@@ -102,9 +100,9 @@ __host__ __device__ constexpr JoinLds join_lds_layout(int K, int max_set, int L,
     o.mask = o.new_pre + (K > 2 ? ((K - 1) * (max_set + 1) + 1) / 2 : 0);
     // one bit per union row, in whole 64-bit words, and two words of slack: a lane's bits are
     // put in as three 32-bit words at a time
-    o.mask_words = (K == 2 && fill) ? 2 * ((2 * max_set + 63) / 64) + 2 : 0;
+    o.mask_words = fill ? 2 * ((K * max_set + 63) / 64) + 2 : 0;
     if (o.mask_words > 0) o.mask += o.mask & 1;  // the masks are read as 64-bit words
-    o.src = o.mask + 2 * o.mask_words;
+    o.src = o.mask + K * o.mask_words;
     const int src_end = o.src + (fill && join_uses_src(K, LT) ? (K * K * max_set + 1) / 2 : 0);
     // Only the tile of the pairs is moved 16 bytes at a time; nothing else is padded: the
     // words a wave needs decide how many waves a compute unit holds.
@@ -197,15 +195,16 @@ __device__ __forceinline__ int union_pair_merge_path(const uint32_t* A, int nA, 
     return n_out;
 }
 
-// The sources of the 64 union rows r0 .. r0+63 of a pair, from the masks: lane l learns for
-// row r0 + l whether list j feeds it and from which of the list's rows.  before[j] = rows of
-// list j that feed union rows below r0; it is moved on to r0 + 64.  A source index is checked
-// against the list's length, which only a malformed (unsorted) table can exceed.
-__device__ __forceinline__ void pair_sources(const uint32_t* mask, int mask_words, int r0,
-                                             const int (&n)[2], int (&before)[2], int lane,
-                                             bool (&present)[2], int (&index)[2]) {
+// The sources of the 64 union rows r0 .. r0+63, from the masks: lane l learns for row r0 + l
+// whether list j feeds it and from which of the list's rows.  before[j] = rows of list j that
+// feed union rows below r0; it is moved on to r0 + 64.  A source index is checked against the
+// list's length, which only a malformed (unsorted) table can exceed.
+template <int K>
+__device__ __forceinline__ void row_sources(const uint32_t* mask, int mask_words, int r0,
+                                            const int (&n)[K], int (&before)[K], int lane,
+                                            bool (&present)[K], int (&index)[K]) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < K; ++j) {
         const uint64_t bits = *reinterpret_cast<const uint64_t*>(mask + j * mask_words + (r0 >> 5));
         const int rank = (int)__builtin_amdgcn_mbcnt_hi(
             (uint32_t)(bits >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bits, 0u));
@@ -215,10 +214,11 @@ __device__ __forceinline__ void pair_sources(const uint32_t* mask, int mask_word
     }
 }
 
-// Any K: union size and (when kFill) the sources of every union row, by ranks.
+// Any K: union size and (when kFill) the masks of the union rows, by ranks.  The masks must be
+// zero on entry.
 template <int K, bool kFill>
 __device__ __forceinline__ int union_ranked(const uint32_t* ids_lds, const int (&n)[K], int max_set,
-                                            uint16_t* new_pre, uint16_t* src, int src_stride,
+                                            uint16_t* new_pre, uint32_t* mask, int mask_words,
                                             int lane) {
     // per list j >= 1: exclusive prefix count of elements that no earlier list contains
     int n_out = n[0];
@@ -250,7 +250,7 @@ __device__ __forceinline__ int union_ranked(const uint32_t* ids_lds, const int (
     }
     if (!kFill || n_out == 0) return n_out;
     wave_sync();
-    // every union row is written by the first list that holds its node
+    // every union row is marked by the first list that holds its node
 #pragma unroll
     for (int j = 0; j < K; ++j) {
         const uint16_t* pre_j = new_pre + (j > 0 ? j - 1 : 0) * (max_set + 1);  // j >= 1 only
@@ -258,22 +258,23 @@ __device__ __forceinline__ int union_ranked(const uint32_t* ids_lds, const int (
             const uint32_t x = ids_lds[j * max_set + t];
             if (j > 0 && pre_j[t + 1] == pre_j[t]) continue;  // owned by an earlier list
             int pos = 0;
-            uint16_t s_idx[K];
+            bool present[K];
 #pragma unroll
             for (int jj = 0; jj < K; ++jj) {
                 if (jj == j) {
                     pos += (j == 0) ? t : (int)pre_j[t];
-                    s_idx[jj] = (uint16_t)t;
+                    present[jj] = true;
                 } else {
                     const uint32_t* other = ids_lds + jj * max_set;
                     const int p = lower_bound_lds(other, n[jj], x);
                     pos += (jj == 0) ? p : (int)new_pre[(jj - 1) * (max_set + 1) + p];
-                    const bool present = jj > j && p < n[jj] && other[p] == x;
-                    s_idx[jj] = present ? (uint16_t)p : kNoSrc;
+                    present[jj] = jj > j && p < n[jj] && other[p] == x;
                 }
             }
+            // pos < K * max_set whatever the lists hold: every term is at most a list's length
 #pragma unroll
-            for (int jj = 0; jj < K; ++jj) src[jj * src_stride + pos] = s_idx[jj];
+            for (int jj = 0; jj < K; ++jj)
+                if (present[jj]) atomicOr(mask + jj * mask_words + (pos >> 5), 1u << (pos & 31));
         }
     }
     return n_out;
@@ -361,31 +362,33 @@ __device__ __forceinline__ int join_prepare(
                        jq.n[j], lane);
     wave_sync();
 
+    if (kSrc) {
+        for (int t = lane; t < K * lay.mask_words; t += kWave) mask[t] = 0u;
+        wave_sync();
+    }
     int n_out;
     if constexpr (K == 2) {
-        if (kSrc) {
-            for (int t = lane; t < 2 * lay.mask_words; t += kWave) mask[t] = 0u;
-            wave_sync();
-        }
         n_out = union_pair_merge_path<kSrc>(ids_lds, jq.n[0], ids_lds + max_set, jq.n[1], mask,
                                             mask + lay.mask_words, lane);
-        if constexpr (kSrc && join_uses_src(K, LT)) {
-            // the generic path wants an index per (list, row)
-            wave_sync();
-            int before[2] = {0, 0};
-            for (int r0 = 0; r0 < n_out; r0 += kWave) {
-                bool present[2];
-                int index[2];
-                pair_sources(mask, lay.mask_words, r0, jq.n, before, lane, present, index);
-                if (r0 + lane < n_out) {
+    } else {
+        n_out = union_ranked<K, kSrc>(ids_lds, jq.n, max_set, new_pre, mask, lay.mask_words, lane);
+    }
+    if constexpr (kSrc && join_uses_src(K, LT)) {
+        // the generic path wants an index per (list, row)
+        wave_sync();
+        int before[K];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        src[j * src_stride + r0 + lane] = present[j] ? (uint16_t)index[j] : kNoSrc;
-                }
+        for (int j = 0; j < K; ++j) before[j] = 0;
+        for (int r0 = 0; r0 < n_out; r0 += kWave) {
+            bool present[K];
+            int index[K];
+            row_sources<K>(mask, lay.mask_words, r0, jq.n, before, lane, present, index);
+            if (r0 + lane < n_out) {
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+                    src[j * src_stride + r0 + lane] = present[j] ? (uint16_t)index[j] : kNoSrc;
             }
         }
-    } else {
-        n_out = union_ranked<K, kSrc>(ids_lds, jq.n, max_set, new_pre, src, src_stride, lane);
     }
     return n_out;
 }
@@ -434,7 +437,9 @@ __device__ __forceinline__ void join_write(
             odd[j] = (uint32_t)((reinterpret_cast<uintptr_t>(first) >> 1) & 1u);
             vec_words[j] = reinterpret_cast<const uint32_t*>(first - odd[j]);
         }
-        int before[2] = {0, 0};
+        int before[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) before[j] = 0;
         for (int r0 = 0; r0 < n_out; r0 += kRounds * kWave) {
             uint32_t raw[kRounds][K][kCover + 1];
             uint32_t shift[kRounds][K];
@@ -444,18 +449,8 @@ __device__ __forceinline__ void join_write(
             for (int g = 0; g < kRounds; ++g) {
                 if (r0 + g * kWave >= n_out) break;  // wave-uniform: no round past the last row
                 int index[K];
-                if constexpr (K == 2) {
-                    pair_sources(mask, lay.mask_words, r0 + g * kWave, n, before, lane, present[g],
-                                 index);
-                } else {
-                    const int r = min(r0 + g * kWave + lane, n_out - 1);
-#pragma unroll
-                    for (int j = 0; j < K; ++j) {
-                        // kNoSrc is >= any n; the bound also covers a malformed (unsorted) table
-                        index[j] = src[j * src_stride + r];
-                        present[g][j] = index[j] < n[j];
-                    }
-                }
+                row_sources<K>(mask, lay.mask_words, r0 + g * kWave, n, before, lane, present[g],
+                               index);
                 // the node's id, from the first list that has it (a lane past the last row
                 // reads the first id and stores nothing)
                 int id_at = 0;
