@@ -44,9 +44,10 @@ constexpr int kJoinChunkRows = 64;       // union rows staged in LDS per output 
 // Rounds of 64 union rows whose gathers a wave has in flight together.  More rounds shorten a
 // wave's chain of memory round trips but cost registers, i.e. waves per compute unit: of 2 to
 // 10 rounds, six made the fastest filling launch on the 2.9M-node workload (5.30 ms with two,
-// 5.09 with six, 5.55 with eight).
+// 5.09 with six, 5.55 with eight); for the triples of the 1M-node workload four (1.80 ms with
+// three, 1.77 with four, 1.96 with six, 2.26 with eight).
 constexpr int kGatherRoundsPairs = 6;
-constexpr int kGatherRoundsTuples = 6;
+constexpr int kGatherRoundsTuples = 4;
 
 // First index t in [0, n) with list[t] >= x (n if none).  n is wave-uniform.
 __device__ __forceinline__ int lower_bound_lds(const uint32_t* list, int n, uint32_t x) {
