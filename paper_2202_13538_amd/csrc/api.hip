@@ -756,7 +756,7 @@ int surel_query_rpe_ids(surel_ctx* ctx, const int32_t* d_walks, const int64_t* d
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return SUREL_E_HIP;
     KernelSpan span(ctx, SUREL_K_QUERY_IDS);
-    hipError_t hrc = surel::launch_query_ids(ctx->stream, ctx->max_lds_bytes, ctx->n_cu, d_walks,
+    hipError_t hrc = surel::launch_query_ids(ctx->stream, ctx->max_lds_bytes, d_walks,
                                              d_rpe_off, d_rpe_ids, d_code, n_blocks, M, m, max_set,
                                              table_rows, d_queries, n_queries, k, d_out,
                                              ctx->d_err);

@@ -77,7 +77,7 @@ hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, const int64_t
 // query's k table blocks, the table rows that hold its node in each of the k blocks (-1 where
 // a block does not hold it).  walks[b] must be the walk block of table block b.  code
 // (optional): int32[table_rows]; if given, code[row] goes out instead of row.
-hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* walks,
+hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, const int32_t* walks,
                             const int64_t* rpe_off, const int32_t* rpe_ids, const int32_t* code,
                             int64_t n_blocks,
                             int32_t M, int32_t m, int32_t max_set, int64_t table_rows,

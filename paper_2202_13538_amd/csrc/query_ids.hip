@@ -7,8 +7,8 @@
 // dictionaries in LDS were measured too and lost: their probe loops diverge, and their
 // footprint leaves a compute unit too few waves.)
 //
-// A wavefront handles one query at a time and loops over the queries (the grid is as large as
-// the device holds at once).  It stages the K id lists in LDS, then runs over the K walk
+// A wavefront handles one query (the grid covers the query list; a wave loops only where the
+// grid cannot be that large).  It stages the K id lists in LDS, then runs over the K walk
 // blocks as flat arrays: a lane takes kQiEntries walk entries at a time and searches each in
 // all K lists with a fixed number of branch-free steps, so that the K * kQiEntries searches
 // of a round advance together and their LDS reads overlap; the K row indices of an entry lie
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(WPB* kWave) void query_ids_kernel(
 }
 
 template <int K, int WPB, int QE, bool kCode>
-static hipError_t launch_query_ids_kwe(hipStream_t stream, int n_cu, const int32_t* walks,
+static hipError_t launch_query_ids_kwe(hipStream_t stream, const int32_t* walks,
                                       const int64_t* rpe_off, const int32_t* rpe_ids,
                                       const int32_t* code,
                                       int64_t n_blocks, int32_t M, int32_t m, int32_t max_set,
@@ -223,14 +223,14 @@ static hipError_t launch_query_ids_kwe(hipStream_t stream, int n_cu, const int32
 }
 
 template <int K, int WPB, bool kCode>
-static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_t* walks,
+static hipError_t launch_query_ids_kw(hipStream_t stream, const int32_t* walks,
                                       const int64_t* rpe_off, const int32_t* rpe_ids,
                                       const int32_t* code, int64_t n_blocks, int32_t M, int32_t m,
                                       int32_t max_set, int64_t table_rows, const int32_t* queries,
                                       int64_t n_queries, int32_t* out, uint32_t* err) {
     const int64_t n_key = (int64_t)M * (m + 1);
 #define SUREL_QI_ENTRIES(QE_)                                                                  \
-    return launch_query_ids_kwe<K, WPB, QE_, kCode>(stream, n_cu, walks, rpe_off, rpe_ids, code, \
+    return launch_query_ids_kwe<K, WPB, QE_, kCode>(stream, walks, rpe_off, rpe_ids, code, \
                                                     n_blocks, M, m, max_set, table_rows, queries, \
                                                     n_queries, out, err)
     if (n_key <= kWave) SUREL_QI_ENTRIES(1);
@@ -241,7 +241,7 @@ static hipError_t launch_query_ids_kw(hipStream_t stream, int n_cu, const int32_
 }
 
 template <int K, bool kCode>
-static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int n_cu,
+static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes,
                                      const int32_t* walks, const int64_t* rpe_off,
                                      const int32_t* rpe_ids, const int32_t* code, int64_t n_blocks,
                                      int32_t M, int32_t m,
@@ -262,7 +262,7 @@ static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int 
     }
 #define SUREL_QI_CASE(W_)                                                                        \
     if (best == (W_))                                                                            \
-        return launch_query_ids_kw<K, W_, kCode>(stream, n_cu, walks, rpe_off, rpe_ids, code,   \
+        return launch_query_ids_kw<K, W_, kCode>(stream, walks, rpe_off, rpe_ids, code,   \
                                                  n_blocks, M, m, max_set, table_rows, queries,  \
                                                  n_queries, out, err);
     SUREL_QI_CASE(4)
@@ -272,7 +272,7 @@ static hipError_t launch_query_ids_k(hipStream_t stream, int max_lds_bytes, int 
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, const int32_t* walks,
+hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, const int32_t* walks,
                             const int64_t* rpe_off, const int32_t* rpe_ids, const int32_t* code,
                             int64_t n_blocks,
                             int32_t M, int32_t m, int32_t max_set, int64_t table_rows,
@@ -282,7 +282,7 @@ hipError_t launch_query_ids(hipStream_t stream, int max_lds_bytes, int n_cu, con
     if ((size_t)(code ? 2 : 1) * k * (max_set + 1) * 4 > (size_t)max_lds_bytes)
         return hipErrorInvalidValue;
 #define SUREL_QI_ARGS \
-    stream, max_lds_bytes, n_cu, walks, rpe_off, rpe_ids, code, n_blocks, M, m, max_set, \
+    stream, max_lds_bytes, walks, rpe_off, rpe_ids, code, n_blocks, M, m, max_set, \
         table_rows, queries, n_queries, out, err
     if (k == 2 && !code) return launch_query_ids_k<2, false>(SUREL_QI_ARGS);
     if (k == 3 && !code) return launch_query_ids_k<3, false>(SUREL_QI_ARGS);
