@@ -2,9 +2,9 @@
 // (b_1..b_K) the ascending union of the K node sets, and per union node the K count
 // vectors in tuple order, zeros where the node is absent from a set.
 //
-// Two launches of one kernel body.  Counting: every query's union rows (an exclusive scan then
-// turns the counts into join_off).  Filling: join_off is given (by that scan, or kept by the
-// caller from an earlier call), the rows are written.  A wavefront handles one query at a time;
+// Two launches.  Counting: every query's union rows (an exclusive scan then turns the counts
+// into join_off).  Filling: join_off is given (by that scan, or kept by the caller from an
+// earlier call), the rows are written.  A wavefront handles one query at a time;
 // the K sorted id lists are staged in LDS.  (Doing both in one launch, with the offsets from a scanner wave
 // inside the kernel as the fused walk + RPE kernel has them, was built and measured: a wave has
 // to wait for its query's offset between uniting and writing, which took 10.0 ms against
@@ -598,51 +598,168 @@ __device__ __forceinline__ void join_write(
     }
 }
 
-// Counting and filling.  One wavefront per workgroup; it takes `per_wave` consecutive queries
-// (the grid covers the list).  The hardware hands workgroups out as others retire, which keeps
-// every compute unit full whatever the queries' sizes are and however many waves it really
-// holds.  (A grid of exactly as many waves as the occupancy query promises, each looping over
-// a strided share of the queries, was slower: where the device held fewer workgroups than
-// promised, the surplus ran as a tail after the others, +25 % on one workload; and with four
-// waves to a workgroup a slot stays taken until the slowest of the four is done.)  Filling
-// takes one query per wave; the counting launch, whose queries are short, four.
-// kFill = false: write counts[q] only; kFill = true: join_off is complete (the caller's, or the
-// scan of a counting launch), write the rows.  A query whose union does not have the
-// join_off[q+1] - join_off[q] rows that the offsets give it is flagged and writes nothing.
-constexpr int kQueriesPerWaveCount = 4;
-constexpr int kQueriesPerWaveFill = 1;
-
-template <int K, bool kFill, int LT>
-__global__ __launch_bounds__(kWave) void join_kernel(
+// Filling.  One wavefront per workgroup and one query per wavefront; the grid covers the query
+// list.  The hardware hands workgroups out as others retire, which keeps every compute unit
+// full whatever the queries' sizes are and however many waves it really holds.  (A grid of
+// exactly as many waves as the occupancy query promises, each looping over a strided share of
+// the queries, was slower: where the device held fewer workgroups than promised, the surplus
+// ran as a tail after the others, +25 % on one workload; and with four waves to a workgroup a
+// slot stays taken until the slowest of the four is done.)
+// join_off is complete (the caller's, or the scan of a counting launch).  A query whose union
+// does not have the join_off[q+1] - join_off[q] rows that the offsets give it is flagged and
+// writes nothing.
+template <int K, int LT>
+__global__ __launch_bounds__(kWave) void join_fill_kernel(
     const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids,
     const uint16_t* __restrict__ rpe_cnt, int64_t n_blocks, int32_t m, int32_t max_set,
-    const int32_t* __restrict__ queries, int64_t n_queries, int32_t* __restrict__ counts,
+    const int32_t* __restrict__ queries, int64_t n_queries,
     const int64_t* __restrict__ join_off, int64_t cap_rows, int32_t* __restrict__ out_ids,
     uint16_t* __restrict__ out_cnt, uint16_t absent16, uint32_t* __restrict__ err) {
     extern __shared__ __align__(16) uint32_t base[];
-    constexpr int kPerWave = kFill ? kQueriesPerWaveFill : kQueriesPerWaveCount;
     const int lane = lane_id();
+    // (written as a loop over the wave's one query: the compiler's code for this form makes the
+    // launch 2 % faster on the 2.9M-node workload than the same statements in a row)
+    constexpr int kPerWave = 1;
     const int64_t q_first = (int64_t)blockIdx.x * kPerWave;
 #pragma unroll 1
     for (int64_t q = q_first; q < min(q_first + kPerWave, n_queries); ++q) {
         JoinQuery<K> jq;
         // the same in every lane; said so, the loops over the rows are scalar loops
-        const int n_out = __builtin_amdgcn_readfirstlane(join_prepare<K, kFill, LT>(
+        const int n_out = __builtin_amdgcn_readfirstlane(join_prepare<K, true, LT>(
             base, lane, q, rpe_off, rpe_ids, n_blocks, m, max_set, queries, jq, err));
-        if constexpr (!kFill) {
-            if (lane == 0) counts[q] = n_out > 0 ? n_out : 0;  // an unusable query yields no rows
-        } else {
-            const int64_t off = join_off[q];
-            const int rows = n_out > 0 ? n_out : 0;
-            if (join_off[q + 1] - off != (int64_t)rows) {
-                if (lane == 0) atomicOr(err, kDevBadSizes);
-            } else if (rows > 0 && off + rows > cap_rows) {
-                if (lane == 0) atomicOr(err, kDevCapacity);
-            } else if (rows > 0) {
-                join_write<K, LT>(base, lane, jq, rows, off, rpe_cnt, m, max_set, out_ids, out_cnt,
-                                  absent16);
+        const int64_t off = join_off[q];
+        const int rows = n_out > 0 ? n_out : 0;  // an unusable query yields no rows
+        if (join_off[q + 1] - off != (int64_t)rows) {
+            if (lane == 0) atomicOr(err, kDevBadSizes);
+        } else if (rows > 0 && off + rows > cap_rows) {
+            if (lane == 0) atomicOr(err, kDevCapacity);
+        } else if (rows > 0) {
+            join_write<K, LT>(base, lane, jq, rows, off, rpe_cnt, m, max_set, out_ids, out_cnt,
+                              absent16);
+        }
+        wave_sync();
+    }
+}
+
+// Counting.  A wavefront takes join_count_queries(K) consecutive queries.  Their
+// blocks are looked up by one lane each (block numbers, then the blocks' offsets: two round
+// trips to memory for all of them), and while the id lists of one query are united in LDS the
+// lists of the next one are already on their way into registers: a query's time is then the
+// longer of its merge and one round trip, where looking up, staging and uniting one query
+// after the other took three round trips and the merge.
+// (Measured on the 2.9M-node workload, pairs: 0.77 ms one query after the other, four to a
+// wave; 0.71 / 0.66 / 0.64 / 0.64 ms this way with 2 / 4 / 8 / 16 to a wave.  Triples of the
+// 1M-node workload: 0.42, and 0.41 / 0.41 / 0.42 / 0.47.)
+__host__ __device__ constexpr int join_count_queries(int K) { return K == 2 ? 8 : 4; }
+constexpr int kCountStage = 8;  // words of a list a lane holds for the next query (512 ids)
+
+template <int K>
+__global__ __launch_bounds__(kWave) void join_count_kernel(
+    const int64_t* __restrict__ rpe_off, const int32_t* __restrict__ rpe_ids, int64_t n_blocks,
+    int32_t max_set, const int32_t* __restrict__ queries, int64_t n_queries,
+    int32_t* __restrict__ counts, uint32_t* __restrict__ err) {
+    extern __shared__ __align__(16) uint32_t base[];
+    const JoinLds lay = join_lds_layout(K, max_set, 2, false, 0);
+    uint32_t* ids_lds = base + lay.ids;
+    uint16_t* new_pre = reinterpret_cast<uint16_t*>(base + lay.new_pre);
+    const int lane = lane_id();
+    constexpr int kCountQueries = join_count_queries(K);
+    const int64_t q_first = (int64_t)blockIdx.x * kCountQueries;
+
+    // lane l < kCountQueries looks up the blocks of query q_first + l
+    int64_t my_lo[K];
+    int my_n[K];
+    uint32_t my_problem = 0;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        my_lo[j] = 0;
+        my_n[j] = 0;
+    }
+    if (lane < kCountQueries && q_first + lane < n_queries) {
+        int32_t b[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) b[j] = queries[(q_first + lane) * K + j];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            if (b[j] < 0 || (int64_t)b[j] >= n_blocks) {
+                my_problem |= kDevBadQuery;
+            } else {
+                const int64_t a = rpe_off[b[j]];
+                const int64_t len = rpe_off[b[j] + 1] - a;
+                if (a < 0 || len < 0) {
+                    my_problem |= kDevBadTable;
+                } else if (len > (int64_t)max_set) {
+                    my_problem |= kDevSetTooLarge;
+                } else {
+                    my_lo[j] = a;
+                    my_n[j] = (int)len;
+                }
             }
         }
+        if (my_problem != 0) {  // the query is flagged and yields no rows
+            atomicOr(err, my_problem);
+#pragma unroll
+            for (int j = 0; j < K; ++j) my_n[j] = 0;
+        }
+    }
+    // query i's blocks, the same in every lane
+    auto blocks_of = [&](int i, int64_t (&lo)[K], int (&n)[K]) {
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const uint32_t lo_l = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(uint64_t)my_lo[j], i);
+            const uint32_t lo_h = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)my_lo[j] >> 32), i);
+            lo[j] = (int64_t)(((uint64_t)lo_h << 32) | lo_l);
+            n[j] = __builtin_amdgcn_readlane(my_n[j], i);
+        }
+    };
+    uint32_t staged[K][kCountStage];
+    auto fetch = [&](const int64_t (&lo)[K], const int (&n)[K]) {
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+#pragma unroll
+            for (int u = 0; u < kCountStage; ++u) {
+                const int t = u * kWave + lane;
+                staged[j][u] = t < n[j] ? (uint32_t)rpe_ids[lo[j] + t] : 0u;
+            }
+        }
+    };
+    int64_t lo[K];
+    int n[K];
+    blocks_of(0, lo, n);
+    fetch(lo, n);
+#pragma unroll
+    for (int i = 0; i < kCountQueries; ++i) {
+        const int64_t q = q_first + i;
+        if (q >= n_queries) break;
+        // the lists of query i: from the registers, and what is longer than they hold from memory
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+#pragma unroll
+            for (int u = 0; u < kCountStage; ++u) {
+                const int t = u * kWave + lane;
+                if (t < n[j]) ids_lds[j * max_set + t] = staged[j][u];
+            }
+            if (n[j] > kCountStage * kWave)
+                stage_words<8>(ids_lds + j * max_set + kCountStage * kWave,
+                               reinterpret_cast<const uint32_t*>(rpe_ids + lo[j]) + kCountStage * kWave,
+                               n[j] - kCountStage * kWave, lane);
+        }
+        wave_sync();
+        int n_now[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) n_now[j] = n[j];
+        if (i + 1 < kCountQueries && q + 1 < n_queries) {
+            blocks_of(i + 1, lo, n);
+            fetch(lo, n);  // in flight while query i is united
+        }
+        int n_out;
+        if constexpr (K == 2) {
+            n_out = union_pair_merge_path<false>(ids_lds, n_now[0], ids_lds + max_set, n_now[1],
+                                                 nullptr, nullptr, lane);
+        } else {
+            n_out = union_ranked<K, false>(ids_lds, n_now, max_set, new_pre, nullptr, 0, lane);
+        }
+        if (lane == 0) counts[q] = n_out;
         wave_sync();  // the next query reuses the LDS words
     }
 }
@@ -668,52 +785,53 @@ struct JoinJob {
     uint32_t* err;
 };
 
-enum JoinMode { kJoinCount, kJoinFill };
-
-template <int K, JoinMode kMode, int LT>
-static hipError_t launch_join_cfg(const JoinJob& j) {
-    constexpr bool kFill = kMode == kJoinFill;
-    constexpr int kPerWave = kFill ? kQueriesPerWaveFill : kQueriesPerWaveCount;
-    const size_t lds_bytes = (size_t)join_lds_layout(K, j.max_set, j.m + 1, kFill, LT).total * 4;
+template <int K, int LT>
+static hipError_t launch_join_fill_cfg(const JoinJob& j) {
+    const size_t lds_bytes = (size_t)join_lds_layout(K, j.max_set, j.m + 1, true, LT).total * 4;
     if (lds_bytes > (size_t)j.max_lds_bytes) return hipErrorInvalidValue;
-    const void* fn = reinterpret_cast<const void*>(join_kernel<K, kFill, LT>);
+    const void* fn = reinterpret_cast<const void*>(join_fill_kernel<K, LT>);
     if (lds_bytes > 48 * 1024) {
         hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)lds_bytes);
         if (rc != hipSuccess) return rc;
     }
-    const int64_t blocks = (j.n_queries + kPerWave - 1) / kPerWave;
-    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((join_kernel<K, kFill, LT>), dim3((unsigned)blocks), dim3(kWave), lds_bytes,
-                       j.stream, j.rpe_off, j.rpe_ids, j.rpe_cnt, j.n_blocks, j.m, j.max_set,
-                       j.queries, j.n_queries, j.counts, j.join_off, j.cap_rows, j.out_ids,
+    if (j.n_queries > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((join_fill_kernel<K, LT>), dim3((unsigned)j.n_queries), dim3(kWave),
+                       lds_bytes, j.stream, j.rpe_off, j.rpe_ids, j.rpe_cnt, j.n_blocks, j.m,
+                       j.max_set, j.queries, j.n_queries, j.join_off, j.cap_rows, j.out_ids,
                        j.out_cnt, j.absent16, j.err);
     return hipGetLastError();
 }
 
-// m + 1 at compile time for the usual walk lengths (the counting launch moves no vectors)
-constexpr int join_static_len(JoinMode mode, int L) {
-    return (mode != kJoinCount && L >= 2 && L <= 6) ? L : 0;
-}
-
-template <int K, JoinMode kMode>
-static hipError_t launch_join_k(const JoinJob& j) {
-    switch (join_static_len(kMode, j.m + 1)) {
-        case 2: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 2>(j);
-        case 3: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 3>(j);
-        case 4: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 4>(j);
-        case 5: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 5>(j);
-        case 6: return launch_join_cfg<K, kMode, kMode == kJoinCount ? 0 : 6>(j);
-        default: return launch_join_cfg<K, kMode, 0>(j);
+// m + 1 at compile time for the usual walk lengths
+template <int K>
+static hipError_t launch_join_fill_k(const JoinJob& j) {
+    switch (j.m + 1) {
+        case 2: return launch_join_fill_cfg<K, 2>(j);
+        case 3: return launch_join_fill_cfg<K, 3>(j);
+        case 4: return launch_join_fill_cfg<K, 4>(j);
+        case 5: return launch_join_fill_cfg<K, 5>(j);
+        case 6: return launch_join_fill_cfg<K, 6>(j);
+        default: return launch_join_fill_cfg<K, 0>(j);
     }
 }
 
-template <JoinMode kMode>
-static hipError_t launch_join_mode(const JoinJob& j, int32_t k) {
-    if (j.n_queries == 0) return hipSuccess;
-    if (k == 2) return launch_join_k<2, kMode>(j);
-    if (k == 3) return launch_join_k<3, kMode>(j);
-    return hipErrorInvalidValue;
+template <int K>
+static hipError_t launch_join_count_k(const JoinJob& j) {
+    constexpr int kCountQueries = join_count_queries(K);
+    const size_t lds_bytes = (size_t)join_lds_layout(K, j.max_set, 2, false, 0).total * 4;
+    if (lds_bytes > (size_t)j.max_lds_bytes) return hipErrorInvalidValue;
+    const void* fn = reinterpret_cast<const void*>(join_count_kernel<K>);
+    if (lds_bytes > 48 * 1024) {
+        hipError_t rc = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)lds_bytes);
+        if (rc != hipSuccess) return rc;
+    }
+    const int64_t blocks = (j.n_queries + kCountQueries - 1) / kCountQueries;
+    hipLaunchKernelGGL((join_count_kernel<K>), dim3((unsigned)blocks), dim3(kWave), lds_bytes,
+                       j.stream, j.rpe_off, j.rpe_ids, j.n_blocks, j.max_set, j.queries,
+                       j.n_queries, j.counts, j.err);
+    return hipGetLastError();
 }
 
 hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
@@ -724,7 +842,10 @@ hipError_t launch_join_count(hipStream_t stream, int max_lds_bytes, const int64_
     j.stream = stream, j.max_lds_bytes = max_lds_bytes;
     j.rpe_off = rpe_off, j.rpe_ids = rpe_ids, j.n_blocks = n_blocks, j.m = 1, j.max_set = max_set;
     j.queries = queries, j.n_queries = n_queries, j.counts = counts, j.err = err;
-    return launch_join_mode<kJoinCount>(j, k);
+    if (n_queries == 0) return hipSuccess;
+    if (k == 2) return launch_join_count_k<2>(j);
+    if (k == 3) return launch_join_count_k<3>(j);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, const int64_t* rpe_off,
@@ -738,7 +859,10 @@ hipError_t launch_join_fill(hipStream_t stream, int max_lds_bytes, const int64_t
     j.max_set = max_set, j.queries = queries, j.n_queries = n_queries, j.join_off = join_off;
     j.cap_rows = cap_rows, j.out_ids = out_ids, j.out_cnt = out_cnt, j.absent16 = absent16;
     j.err = err;
-    return launch_join_mode<kJoinFill>(j, k);
+    if (n_queries == 0) return hipSuccess;
+    if (k == 2) return launch_join_fill_k<2>(j);
+    if (k == 3) return launch_join_fill_k<3>(j);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace surel
