@@ -151,6 +151,7 @@ __global__ __launch_bounds__(256) void prune_rank_kernel(const uint32_t* __restr
 // code[row]: slot number -> rank of that slot (-1, or anything that is no slot number, becomes -1).
 // Four rows a lane, moved as 16-byte words where the array's alignment allows (the pass is a
 // plain stream over the codes; the ranks come from a few thousand hot cache lines).
+constexpr int kCodesUnroll = 4;
 __global__ __launch_bounds__(256) void prune_codes_kernel(const uint32_t* __restrict__ slots,
                                                           uint32_t n_slots, int64_t n_rows,
                                                           int32_t* __restrict__ code) {
@@ -161,15 +162,28 @@ __global__ __launch_bounds__(256) void prune_codes_kernel(const uint32_t* __rest
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if ((reinterpret_cast<uintptr_t>(code) & 15u) == 0) {
-        int4* code4 = reinterpret_cast<int4*>(code);
+        // kCodesUnroll 16-byte words of a lane are in flight together, non-temporal both ways:
+        // every code is read once and written once
+        typedef int code4_t __attribute__((ext_vector_type(4)));
+        code4_t* code4 = reinterpret_cast<code4_t*>(code);
         const int64_t n4 = n_rows / 4;
-        for (int64_t i = tid; i < n4; i += stride) {
-            int4 c = code4[i];
-            c.x = rank_of(c.x);
-            c.y = rank_of(c.y);
-            c.z = rank_of(c.z);
-            c.w = rank_of(c.w);
-            code4[i] = c;
+        for (int64_t i0 = tid; i0 < n4; i0 += stride * kCodesUnroll) {
+            code4_t c[kCodesUnroll];
+#pragma unroll
+            for (int u = 0; u < kCodesUnroll; ++u) {
+                const int64_t i = i0 + u * stride;
+                c[u] = code4_t{-1, -1, -1, -1};
+                if (i < n4) c[u] = __builtin_nontemporal_load(code4 + i);
+            }
+#pragma unroll
+            for (int u = 0; u < kCodesUnroll; ++u) {
+                const int64_t i = i0 + u * stride;
+                c[u].x = rank_of(c[u].x);
+                c[u].y = rank_of(c[u].y);
+                c[u].z = rank_of(c[u].z);
+                c[u].w = rank_of(c[u].w);
+                if (i < n4) __builtin_nontemporal_store(c[u], code4 + i);
+            }
         }
         for (int64_t row = n4 * 4 + tid; row < n_rows; row += stride) code[row] = rank_of(code[row]);
     } else {
